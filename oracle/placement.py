@@ -1,0 +1,94 @@
+"""TEST INFRASTRUCTURE -- placement closed forms written out with exact rationals.
+
+Each function restates one definition or rule of the paper with Python
+integers and ``fractions.Fraction`` so that no rounding enters.  Used by tests
+to check the host-side evaluator of the GPU library; shares no code with it.
+"""
+from fractions import Fraction
+
+MODES = ("R", "S", "S*", "M", "O")
+
+# Table 2: (pi_Theta, pi_Omega, pi_G, pi_A) of the named strategies.
+STRATEGIES = {
+    "dp": ("R", "R", "R", "R"),
+    "zero1": ("R", "S", "R", "R"),
+    "zero2": ("R", "S", "S", "R"),
+    "zero3": ("S*", "S", "S", "R"),
+    "zero_offload": ("O", "O", "S", "R"),
+    "tp": ("S", "S", "S", "S"),
+    "pp": ("S", "S", "S", "R"),
+}
+
+
+def state_bytes(P):
+    """Remark 1: |Theta| = 2P, |Omega| = 12P (master + m + v), |G| = 2P bytes."""
+    return {"theta": 2 * P, "omega": 12 * P, "grad": 2 * P}
+
+
+def mu(mode, s, N, s_unit=0):
+    """Theorem 1, Eq. 7-11: per-device GPU bytes of a state of s bytes."""
+    if mode == "R":
+        return Fraction(s)
+    if mode == "S":
+        return Fraction(s, N)
+    if mode == "S*":
+        return Fraction(s, N) + s_unit
+    if mode == "M":
+        return Fraction(s_unit)
+    if mode == "O":
+        return Fraction(0)
+    raise ValueError(mode)
+
+
+def memory(spec, P, N, s_unit=0, act_bytes=0):
+    """Theorem 1, Eq. 6: M(Pi) = sum of mu over the four states.  ``act_bytes``
+    is the activation footprint |A| the caller accounts to one device."""
+    sz = state_bytes(P)
+    th, om, g, a = spec
+    return (mu(th, sz["theta"], N, s_unit) + mu(om, sz["omega"], N, s_unit) +
+            mu(g, sz["grad"], N, s_unit) + mu(a, act_bytes, N, s_unit))
+
+
+def all_reduce(N, T):
+    """Section 2.3: ring All-Reduce, bytes sent and received per device."""
+    return Fraction(2 * (N - 1) * T, N)
+
+
+def reduce_scatter(N, T):
+    """Section 2.3: Reduce-Scatter, bytes per device."""
+    return Fraction((N - 1) * T, N)
+
+
+def all_gather(N, T):
+    """Section 2.3: All-Gather, bytes per device."""
+    return Fraction((N - 1) * T, N)
+
+
+def communication(spec, P, N):
+    """Theorem 2, Eq. 12-14: bytes per device per step.  Gradient sync is an
+    All-Reduce under pi_G = R and a Reduce-Scatter under pi_G = S; pi_Theta =
+    S* adds two All-Gathers of the parameters."""
+    sz = state_bytes(P)
+    th, _, g, _ = spec
+    c = Fraction(0)
+    if g == "R":
+        c += all_reduce(N, sz["grad"])
+    elif g == "S":
+        c += reduce_scatter(N, sz["grad"])
+    if th == "S*":
+        c += 2 * all_gather(N, sz["theta"])
+    return c
+
+
+def shard_geometry(psi, N, i, align=1):
+    """Definition 1, Eq. 2: device i holds X[i|X|/N : (i+1)|X|/N].  When N (times
+    the alignment) does not divide psi the length is padded up to the next
+    multiple and the pad falls at the end of the flat buffer.
+    Returns (psi_padded, offset, length, valid_length)."""
+    a = max(1, align)
+    unit = N * a
+    psi_pad = -(-psi // unit) * unit
+    n = psi_pad // N
+    off = i * n
+    valid = min(max(psi - off, 0), n)
+    return psi_pad, off, n, valid
