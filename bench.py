@@ -1,0 +1,266 @@
+#!/usr/bin/env python3
+"""Benchmark of the sharded reduce + AdamW + bf16-cast step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one pass of the whole hot path over one batch of synthetic gradient
+contributions for one device's shard.  The default workload is the 70B ZeRO-3
+shard (8.75e9 elements, N = 8): 33 buckets of 2^28 elements staged on a copy
+stream while the update kernel runs on the compute stream.  All inputs are
+resident in HBM before the timed region starts.  Prints ONE JSON line.
+"""
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import threading
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def bytes_per_elem(w, clip=False):
+    """Algorithmic bytes per element: every byte touched once."""
+    g = 2 if w.grad_dtype == "bf16" else 4
+    if clip:   # phase 1: N reads + fp32 spill; phase 2: spill + state in, state + bf16 out
+        return g * w.n_devices + 4 + 4 + 12 + 14
+    return g * w.n_devices + 12 + 12 + 2
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="70b_zero3",
+                    choices=["tiny", "gpt2s", "7b_zero2", "70b_zero3", "13b_clip"])
+    ap.add_argument("--pool-buckets", type=int, default=2,
+                    help="distinct gradient buckets kept resident as the bucket source")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the other N-1 devices of the placement are "
+              "modelled as input buffers); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2601_02311_amd as ps
+    from synth import WORKLOADS
+    from synth import device as dgen
+
+    w = WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    info = ps.ps_device_info()
+    n, N = w.shard_len, w.n_devices
+    clip = w.max_grad_norm > 0
+    spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi, align_elems=w.align_elems)
+    cost = ps.ps_cost_eval(spec)
+    assert cost.shard_len == n
+    dt = ps.PS_BF16 if w.grad_dtype == "bf16" else ps.PS_F32
+    esz = 2 if w.grad_dtype == "bf16" else 4
+    tdt = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
+    log("device %s (%s), %d CUs, %.1f GB free" % (info.name.decode(), info.arch.decode(),
+                                                  info.compute_units, info.free_bytes / 1e9))
+    log("workload %s: shard of %d elements, N=%d, %s gradients" % (w.name, n, N, w.grad_dtype))
+
+    t_setup = time.time()
+    master, m, v = dgen.workload_state(w)
+    out_len = cost.psi_padded if spec.theta == ps.PS_R else n
+    out = torch.zeros(out_len, dtype=torch.bfloat16, device="cuda")
+    shard = ps.ps_shard_t(master.data_ptr(), m.data_ptr(), v.data_ptr(), out.data_ptr(), n,
+                          cost.valid_len)
+    compute = torch.cuda.Stream()
+    copy = torch.cuda.Stream()
+    bucketed = w.bucket_elems > 0
+    step_no = [w.first_step]
+
+    def hp(clip_coef=0.0, grad_scale=0.0):
+        return ps.ps_adamw_t(w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, step_no[0],
+                             grad_scale, clip_coef)
+
+    kernel_ms = []          # per-launch durations of the dominant kernel in the timed region
+    if bucketed:
+        B = w.bucket_elems
+        n_b = -(-n // B)
+        pool = [dgen.fill_gradient_(torch.empty(args.pool_buckets * B, dtype=tdt, device="cuda"),
+                                    w.seed, w.first_step, r, w.grad_std, w.outlier_frac,
+                                    w.outlier_mult, w.student_t_dof) for r in range(N)]
+        staging = [torch.empty(N * B, dtype=tdt, device="cuda") for _ in range(2)]
+        src = (C.c_void_p * N)(*[p.data_ptr() for p in pool])
+        ms = (C.c_float * n_b)()
+        plan = ps.ps_bucket_plan_t()
+        plan.source = C.cast(src, C.POINTER(C.c_void_p))
+        plan.n_contrib, plan.dtype = N, dt
+        plan.bucket_elems, plan.source_buckets = B, args.pool_buckets
+        plan.staging[0], plan.staging[1] = staging[0].data_ptr(), staging[1].data_ptr()
+        plan.copy_stream, plan.compute_stream = copy.cuda_stream, compute.cuda_stream
+        plan.kernel_ms, plan.kernel_ms_len = ms, n_b
+        launches_per_step = n_b
+
+        def step(record):
+            ps.ps_step_update_bucketed(spec, hp(), shard, plan)
+            if record:
+                kernel_ms.extend(ms[b] for b in range(n_b - 1))   # full buckets only
+            step_no[0] += 1
+        elems_per_launch = B
+    else:
+        grads = dgen.workload_gradients(w, w.first_step)
+        g = ps.make_grads([t.data_ptr() for t in grads], dt)
+        launches_per_step = 1
+        elems_per_launch = cost.valid_len
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+        if clip:
+            red = torch.empty(n, dtype=torch.float32, device="cuda")
+            ssd = torch.zeros(1, dtype=torch.float64, device="cuda")
+            ws = torch.empty(ps.ps_workspace_bytes(), dtype=torch.uint8, device="cuda")
+            gred = ps.make_grads([red.data_ptr()], ps.PS_F32)
+        rec = [0]
+
+        def step(record):
+            with torch.cuda.stream(compute):
+                s = compute.cuda_stream
+                if record:
+                    ev[rec[0]][0].record(compute)
+                if clip:
+                    ps.ps_step_reduce_sumsq(spec, g, 0.0, red.data_ptr(), ssd.data_ptr(), 0,
+                                            ws.data_ptr(), ws.numel(), 0, n, cost.valid_len, s)
+                    ss = float(ssd.item())      # the one device->host sync of a clipped step
+                    coef = ps.ps_clip_coef(ss, 5.0 * ss, w.max_grad_norm)   # five iid peer shards
+                    ps.ps_step_update(spec, hp(coef, 1.0), shard, gred, 0, n, s)
+                else:
+                    ps.ps_step_update(spec, hp(), shard, g, 0, n, s)
+                if record:
+                    ev[rec[0]][1].record(compute)
+                    rec[0] += 1
+            step_no[0] += 1
+    torch.cuda.synchronize()
+    log("setup %.1f s, %.1f GB allocated" % (time.time() - t_setup,
+                                             torch.cuda.memory_allocated() / 1e9))
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    if not bucketed:
+        kernel_ms.extend(a.elapsed_time(b) for a, b in ev)
+    elems_per_step = cost.valid_len
+    value = elems_per_step / (ms_per_step * 1e-3)
+    bpe = bytes_per_elem(w, clip)
+    avg_ms = sum(kernel_ms) / len(kernel_ms)
+    achieved = bpe * elems_per_launch / (avg_ms * 1e-3) / 1e9
+    log("%.3f ms/step, %.3e elements/s; dominant kernel %.3f ms avg -> %.0f GB/s" %
+        (ms_per_step, value, avg_ms, achieved))
+
+    # The same kernel alone on the device (no staging copy in flight) and a plain copy
+    # of equal footprint, as yardsticks; neither is the headline value.
+    extras = {}
+    if bucketed:
+        gs = ps.make_grads([staging[0].data_ptr() + r * B * esz for r in range(N)], dt)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 8
+        with torch.cuda.stream(compute):
+            ps.ps_step_update(spec, hp(), shard, gs, 0, B, compute.cuda_stream)
+            e0.record(compute)
+            for k in range(reps):
+                ps.ps_step_update(spec, hp(), shard, gs, (k % 8) * B, B, compute.cuda_stream)
+            e1.record(compute)
+        torch.cuda.synchronize()
+        iso_ms = e0.elapsed_time(e1) / reps
+        extras["kernel_alone"] = {"ms": iso_ms, "GBps": bpe * B / (iso_ms * 1e-3) / 1e9,
+                                  "note": "update kernel on one 2^28 bucket, no copy in flight"}
+    nbytes = min(master.numel() * 4, 1 << 32)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(compute):
+        ps.ps_probe_copy(m.data_ptr(), v.data_ptr(), nbytes, compute.cuda_stream)
+        e0.record(compute)
+        for _ in range(5):
+            ps.ps_probe_copy(m.data_ptr(), v.data_ptr(), nbytes, compute.cuda_stream)
+        e1.record(compute)
+    torch.cuda.synchronize()
+    cp_ms = e0.elapsed_time(e1) / 5
+    extras["copy_probe"] = {"bytes": nbytes, "ms": cp_ms, "GBps": 2 * nbytes / (cp_ms * 1e-3) / 1e9}
+    log("extras: %s" % json.dumps(extras))
+
+    result = {
+        "metric": "fused shard reduce+AdamW+cast: HBM GB/s and % of MI355X peak, elements/s",
+        "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "psi": w.psi, "n_devices": N, "shard_index": w.shard_index,
+                   "shard_elems": n, "grad_dtype": w.grad_dtype, "strategy": w.strategy,
+                   "bucket_elems": w.bucket_elems, "launches_per_step": launches_per_step,
+                   "bytes_per_elem": bpe, "step_GBps": bpe * elems_per_step / (ms_per_step * 1e-3) / 1e9,
+                   "device": info.name.decode(), "arch": info.arch.decode(),
+                   "compute_units": info.compute_units},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                     "kernel": "update_tiles" if not clip else "reduce_sumsq_tiles+update_tiles",
+                     "elems_per_launch": elems_per_launch, "avg_launch_ms": avg_ms,
+                     "launches_timed": len(kernel_ms)},
+        "extras": extras,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, bpe)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(w, bpe):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: contiguous
+    index ranges of the sample handed to host threads that share nothing."""
+    import numpy as np
+
+    from oracle import step as orc
+    from synth import host as gen
+
+    cores = min(16, os.cpu_count() or 1)
+    sample = min(w.shard_len, 1 << 25)
+    grads = [gen.gradient(sample, w.seed, w.first_step, r, w.grad_dtype, w.grad_std,
+                          w.outlier_frac, w.outlier_mult, w.student_t_dof)
+             for r in range(w.n_devices)]
+    th = gen.master(sample, w.seed)
+    m, v = gen.moments(sample, w.seed, True)
+    p = np.zeros(sample, np.uint16)
+    s = orc.derive_scalars(w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, w.first_step,
+                           w.n_devices)
+    bounds = [sample * k // cores for k in range(cores + 1)]
+
+    def one_pass():
+        ts = [threading.Thread(target=orc.step_f32, args=(grads, s, th, m, v, p, bounds[k], bounds[k + 1]))
+              for k in range(cores)]
+        t0 = time.perf_counter()
+        for t in ts:
+            t.start()
+        for t in ts:
+            t.join()
+        return time.perf_counter() - t0
+    first = one_pass()
+    reps = max(1, min(200, int(10.0 / max(first, 1e-3))))
+    total = sum(one_pass() for _ in range(reps))
+    rate = sample * reps / total
+    log("cpu oracle: %d threads, %d x %d elements in %.1f s -> %.3e elements/s" %
+        (cores, reps, sample, total, rate))
+    return {"value": rate, "unit": "elements/s", "cores": cores, "kind": "oracle",
+            "GBps": rate * bpe / 1e9,
+            "sample": "%d passes over the first %d elements of the shard (%s gradients, N=%d), "
+                      "split into %d contiguous ranges" % (reps, sample, w.grad_dtype, w.n_devices, cores)}
+
+
+if __name__ == "__main__":
+    main()

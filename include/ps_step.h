@@ -1,0 +1,244 @@
+/*
+ * ps_step.h -- C ABI of the placement-sharded optimizer step for MI355X (gfx950).
+ *
+ * One device's share of a ZeRO/FSDP training step under the paper's placement
+ * semantics: gradients G and optimizer state Omega are sharded (mode S), the
+ * 16-bit parameters Theta are replicated (R) or sharded-with-gather (S*).
+ * Device i reduces the N per-device gradient contributions for its shard in a
+ * fixed order, applies mixed-precision Adam with decoupled weight decay to its
+ * FP32 master/m/v shard, and writes the updated parameters as bf16 into the
+ * buffer the following All-Gather reads.
+ *
+ * Conventions
+ *   - Plain C types only.  Every pointer below is marked HOST or DEVICE.
+ *   - DEVICE buffers are owned by the caller, must be 16-byte aligned and must
+ *     stay alive until the work queued on the given stream has finished.  The
+ *     library never allocates, frees or keeps them.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls that take a stream only enqueue work and return; they never
+ *     synchronise the device.
+ *   - No exceptions and no aborts cross this boundary.  Every call returns a
+ *     ps_status_t; validation happens before the first HIP call, so argument
+ *     errors are reported identically with or without a GPU.
+ *   - The library keeps no state between calls except a thread-local error
+ *     string.  The step count t and all buffers belong to the caller, so a
+ *     checkpoint is a copy of the flat shard buffers plus t.
+ *   - Sizes are element counts unless the name says bytes.  GB = 1e9 bytes in
+ *     the cost figures, as in the paper's examples.
+ */
+#ifndef PS_STEP_H
+#define PS_STEP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PS_ABI_VERSION 1u
+/* Largest number of gradient contributions one call can reduce. */
+#define PS_MAX_CONTRIB 16u
+
+/* Placement modes (Definition 1, Eq. 1-5). */
+enum { PS_R = 0, PS_S = 1, PS_SG = 2 /* S*: sharded with gather */, PS_M = 3, PS_O = 4 };
+/* Element type of the gradient contributions. */
+enum { PS_BF16 = 0, PS_F32 = 1 };
+
+typedef enum {
+    PS_OK = 0,
+    PS_EINVAL = 1,       /* NULL pointer, bad enum, count mismatch                 */
+    PS_EUNSUPPORTED = 2, /* placement this path does not execute                   */
+    PS_EALIGN = 3,       /* pointer or offset not 16-byte aligned                  */
+    PS_ERANGE = 4,       /* index/size out of range, or N does not divide a size   */
+    PS_ENODEVICE = 5,    /* no HIP device present                                  */
+    PS_EHIP = 6          /* a HIP call failed; text in ps_last_error()             */
+} ps_status_t;
+
+/* Placement specification Pi = (pi_Theta, pi_Omega, pi_G, pi_A) over N devices
+ * (Definition 2) plus what is needed to turn it into bytes and index ranges. */
+typedef struct ps_spec_t {
+    int32_t theta, omega, grad, act; /* PS_R .. PS_O                                       */
+    uint32_t n_devices;              /* N >= 1                                             */
+    uint32_t shard_index;            /* i in [0, N)                                        */
+    uint64_t psi;                    /* parameter count (the paper's P)                    */
+    uint32_t align_elems;            /* 0/1: Eq. 2 exactly (N must divide psi); k > 1: pad
+                                        psi up to a multiple of N*k, pad at the flat end  */
+    uint32_t reserved;               /* must be 0                                          */
+    uint64_t s_unit_bytes;           /* reconstruction unit (Definition 3); 0 reproduces the
+                                        paper's worked examples, which drop the term      */
+    uint64_t act_bytes;              /* |A| accounted to one device before mu is applied   */
+} ps_spec_t;
+
+/* Result of the derivation rules.  Fields ending in _xN hold bytes * N so that
+ * the (N-1)/N factors of the ring cost models stay exact integers. */
+typedef struct ps_cost_t {
+    /* Theorem 1, Eq. 6-11: persistent GPU bytes per device and state. */
+    uint64_t theta_bytes, omega_bytes, grad_bytes, act_bytes;
+    uint64_t transient_bytes;  /* s_unit terms of S* and M                           */
+    uint64_t persistent_total; /* sum of the four persistent parts                   */
+    uint64_t peak_total;       /* persistent_total + transient_bytes = M(Pi)          */
+    /* Theorem 2, Eq. 12-14: bytes per device per step, times N. */
+    uint64_t comm_grad_sync_xN;    /* 2(N-1)|G| for pi_G=R, (N-1)|G| for pi_G=S      */
+    uint64_t comm_param_gather_xN; /* 2(N-1)|Theta| for pi_Theta=S*, else 0          */
+    double comm_total_bytes;       /* (sum of the two above) / N                     */
+    /* Not a term of Theorem 2: the All-Gather of updated parameters that pi_Theta=R
+     * with pi_Omega=S implies ((N-1)|Theta|).  Never included in comm_total_bytes. */
+    uint64_t implied_update_gather_xN;
+    /* Shard geometry (Eq. 2 with the padding rule of align_elems), in elements. */
+    uint64_t psi_padded, shard_offset, shard_len, valid_len;
+} ps_cost_t;
+
+/* AdamW hyper-parameters.  All scalars the kernels use are formed from these in
+ * binary64 on the host and rounded once to binary32. */
+typedef struct ps_adamw_t {
+    double lr, beta1, beta2, eps, weight_decay;
+    uint64_t step;     /* t >= 1, the step being taken (bias correction 1-beta^t)     */
+    double grad_scale; /* <= 0: 1/N, the mean over devices (proof of Theorem 5)       */
+    double clip_coef;  /* <= 0: 1 (no clipping); else multiplies the mean gradient    */
+} ps_adamw_t;
+
+/* This device's shard of Omega and its output slot.  All DEVICE pointers. */
+typedef struct ps_shard_t {
+    float *master;     /* DEVICE, len floats: FP32 master weights, updated in place   */
+    float *m;          /* DEVICE, len floats: Adam first moment, updated in place     */
+    float *v;          /* DEVICE, len floats: Adam second moment, updated in place    */
+    void *gather_out;  /* DEVICE, bf16.  pi_Theta = S*: the persistent parameter shard
+                          (len elements) that the All-Gather reads.  pi_Theta = R: the
+                          full replicated parameter buffer (psi_padded elements); the
+                          library writes this shard's slice at shard_offset.          */
+    uint64_t len;      /* shard length n = psi_padded / N, in elements                */
+    uint64_t valid_len;/* elements [valid_len, len) are padding and are never written */
+} ps_shard_t;
+
+/* The N gradient contributions for this shard (the inputs of the Reduce-Scatter
+ * whose result device i owns; Section 2.3, Theorem 2 part 2). */
+typedef struct ps_grads_t {
+    const void *const *contrib; /* HOST array of n_contrib DEVICE pointers; contrib[r]
+                                   is element 0 of device r's contribution for the range
+                                   being processed (the shard, or the current bucket)  */
+    uint32_t n_contrib;         /* = n_devices, or 1 for an already reduced gradient   */
+    int32_t dtype;              /* PS_BF16 or PS_F32, one type for all (Theorem 4)     */
+} ps_grads_t;
+
+/* Gradients that arrive in buckets: bucket b of a shard covers elements
+ * [b*bucket_elems, min((b+1)*bucket_elems, len)).  The library copies each
+ * bucket's contributions from `source` into one of two staging slots on
+ * `copy_stream` while `compute_stream` updates the previous bucket. */
+typedef struct ps_bucket_plan_t {
+    const void *const *source;  /* HOST array of n_contrib pointers, each DEVICE or pinned
+                                   HOST memory holding source_buckets consecutive buckets
+                                   of that contribution; bucket b is read from slot
+                                   b % source_buckets                                  */
+    uint32_t n_contrib;
+    int32_t dtype;
+    uint64_t bucket_elems;      /* multiple of 8                                        */
+    uint64_t source_buckets;    /* >= 1                                                 */
+    void *staging[2];           /* DEVICE, each n_contrib * bucket_elems elements       */
+    void *copy_stream;          /* hipStream_t                                          */
+    void *compute_stream;       /* hipStream_t, must differ from copy_stream            */
+    float *kernel_ms;           /* HOST, optional (may be NULL): receives, per bucket,
+                                   the update kernel's duration in ms from HIP events
+                                   on compute_stream.  When non-NULL the call waits for
+                                   the streams to drain before returning.              */
+    uint64_t kernel_ms_len;     /* capacity of kernel_ms                                */
+} ps_bucket_plan_t;
+
+typedef struct ps_device_info_t {
+    char name[128];
+    char arch[64];
+    int32_t compute_units;
+    int32_t wavefront_size;
+    int32_t clock_khz, memory_clock_khz, memory_bus_bits;
+    int32_t l2_bytes;
+    uint64_t total_bytes, free_bytes;
+} ps_device_info_t;
+
+/* ---- host-only calls (no GPU needed) ---- */
+
+uint32_t ps_abi_version(void);
+const char *ps_status_string(ps_status_t st);
+/* Text of the last error on the calling thread ("" if none). */
+const char *ps_last_error(void);
+
+/* Fills *spec with a named row of the paper's Table 2: "dp", "zero1", "zero2",
+ * "zero3" (also "fsdp"), "zero_offload", "tp", "pp".  align_elems, s_unit_bytes
+ * and act_bytes are set to 0.  Unknown name: PS_EINVAL. */
+ps_status_t ps_spec_preset(const char *name, uint32_t n_devices, uint32_t shard_index,
+                           uint64_t psi, ps_spec_t *spec);
+
+/* Derivation rules: per-device memory (Theorem 1), per-step communication
+ * (Theorem 2, with the ring cost models of Section 2.3) and the shard geometry
+ * (Eq. 2), with the byte accounting of Remark 1 (|Theta| = 2 psi, |Omega| =
+ * 12 psi, |G| = 2 psi).  Sizes are taken on psi_padded, the length the flat
+ * buffers hold (= psi whenever N divides psi).  Pure function of *spec.
+ * PS_ERANGE if a division by N is not exact or a result overflows 64 bits. */
+ps_status_t ps_cost_eval(const ps_spec_t *spec, ps_cost_t *cost);
+
+/* Global-norm clip coefficient, in binary64: min(1, max_norm / (sqrt(sumsq_local
+ * + sumsq_others) + 1e-6)), the sums being those of the squared mean gradient
+ * over this device's shard and over all other devices' shards.  A non-finite
+ * or negative sum, or max_norm <= 0, gives NaN (the caller should skip the
+ * step).  Pass the result as ps_adamw_t.clip_coef. */
+double ps_clip_coef(double sumsq_local, double sumsq_others, double max_norm);
+
+/* ---- device calls ---- */
+
+ps_status_t ps_device_info(ps_device_info_t *info);
+
+/* One optimizer step on elements [elem_offset, elem_offset + elem_count) of the
+ * shard (the whole shard, or one bucket of it).
+ *
+ *   acc = ((g_0 + g_1) + g_2) + ...          binary32, contribution index ascending
+ *   g   = (acc * grad_scale) * clip_coef     the global-batch mean (Theorem 3)
+ *   m'  = fma(beta1, m, (1-beta1) * g)
+ *   v'  = fma(beta2, v, ((1-beta2) * g) * g)
+ *   u   = m' / fma(sqrt(v'), 1/sqrt(1-beta2^t), eps)
+ *   th' = fma(-lr/(1-beta1^t), u, fma(-lr*wd, th, th))
+ *   out = bf16 round-to-nearest-even of th'  (NaN -> 0x7FC0 with the sign)
+ *
+ * each line one correctly rounded binary32 operation.  State pointers in *shard
+ * are shard-based (element 0 of the shard); grads->contrib[r] points at element
+ * elem_offset of contribution r.  Only elements below shard->valid_len are read
+ * or written.  Requires omega == PS_S, grad == PS_S, theta in {PS_R, PS_SG};
+ * n_contrib == n_devices, or 1 with PS_F32 for a gradient reduced beforehand.
+ * elem_offset must be a multiple of 8.  Deterministic: no atomics, results do
+ * not depend on launch shape (Theorem 5, assumption 1). */
+ps_status_t ps_step_update(const ps_spec_t *spec, const ps_adamw_t *hp,
+                           const ps_shard_t *shard, const ps_grads_t *grads,
+                           uint64_t elem_offset, uint64_t elem_count, void *stream);
+
+/* The same step over a whole shard whose gradient contributions arrive in
+ * buckets (see ps_bucket_plan_t).  Enqueues every copy and kernel without a
+ * host wait (unless plan->kernel_ms asks for timings). */
+ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
+                                    const ps_shard_t *shard, const ps_bucket_plan_t *plan);
+
+/* Bytes of DEVICE workspace ps_step_reduce_sumsq needs. */
+uint64_t ps_workspace_bytes(void);
+
+/* First phase of a step with global-norm clipping: reduce the contributions
+ * for [elem_offset, elem_offset + elem_count), form the mean g = acc *
+ * grad_scale (grad_scale <= 0: 1/N), store it as FP32 at reduced_out +
+ * elem_offset (reduced_out DEVICE, shard-based, may be NULL), and write the sum
+ * of g*g over the valid elements of the range, accumulated in binary64 in a
+ * fixed tree, to *sumsq_out (DEVICE double).  accumulate != 0 adds to the value
+ * already there, so several buckets called in order give a reproducible total.
+ * The caller combines it with the other devices' sums, forms the clip
+ * coefficient and calls ps_step_update with the reduced gradient as a single
+ * PS_F32 contribution, grad_scale = 1 and that coefficient. */
+ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
+                                 double grad_scale, float *reduced_out, double *sumsq_out,
+                                 int32_t accumulate, void *workspace,
+                                 uint64_t workspace_bytes, uint64_t elem_offset,
+                                 uint64_t elem_count, uint64_t valid_len, void *stream);
+
+/* Plain streaming copy of `bytes` bytes (multiple of 16) between DEVICE buffers
+ * with the same launch shape as the update kernel.  A yardstick for achievable
+ * HBM bandwidth and for calibrating hardware byte counters; not part of the
+ * step. */
+ps_status_t ps_probe_copy(void *dst, const void *src, uint64_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PS_STEP_H */

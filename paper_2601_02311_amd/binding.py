@@ -1,0 +1,226 @@
+"""ctypes mirror of ``include/ps_step.h``.  Argument marshalling only.
+
+Every function has the name and meaning of the C entry point it calls and
+raises :class:`PsError` on a non-zero status.  There is no CPU fallback: if the
+shared library is missing and cannot be built, importing fails.
+"""
+import ctypes as C
+import os
+
+from . import build as _build
+
+__all__ = [
+    "PS_R", "PS_S", "PS_SG", "PS_M", "PS_O", "PS_BF16", "PS_F32", "PS_MAX_CONTRIB",
+    "PS_OK", "PS_EINVAL", "PS_EUNSUPPORTED", "PS_EALIGN", "PS_ERANGE", "PS_ENODEVICE", "PS_EHIP",
+    "PsError", "ps_spec_t", "ps_cost_t", "ps_adamw_t", "ps_shard_t", "ps_grads_t",
+    "ps_bucket_plan_t", "ps_device_info_t", "library", "library_path",
+    "ps_abi_version", "ps_status_string", "ps_last_error", "ps_spec_preset", "ps_cost_eval",
+    "ps_device_info", "ps_step_update", "ps_step_update_bucketed", "ps_workspace_bytes",
+    "ps_step_reduce_sumsq", "ps_probe_copy", "ps_clip_coef", "EXPORTED_SYMBOLS",
+]
+
+PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
+PS_BF16, PS_F32 = 0, 1
+PS_MAX_CONTRIB = 16
+(PS_OK, PS_EINVAL, PS_EUNSUPPORTED, PS_EALIGN, PS_ERANGE, PS_ENODEVICE, PS_EHIP) = range(7)
+
+EXPORTED_SYMBOLS = (
+    "ps_abi_version", "ps_status_string", "ps_last_error", "ps_spec_preset", "ps_cost_eval",
+    "ps_device_info", "ps_step_update", "ps_step_update_bucketed", "ps_workspace_bytes",
+    "ps_step_reduce_sumsq", "ps_probe_copy", "ps_clip_coef",
+)
+
+
+class PsError(RuntimeError):
+    def __init__(self, status, text, detail):
+        super().__init__("ps status %d (%s): %s" % (status, text, detail))
+        self.status = status
+        self.detail = detail
+
+
+class ps_spec_t(C.Structure):
+    _fields_ = [("theta", C.c_int32), ("omega", C.c_int32), ("grad", C.c_int32),
+                ("act", C.c_int32), ("n_devices", C.c_uint32), ("shard_index", C.c_uint32),
+                ("psi", C.c_uint64), ("align_elems", C.c_uint32), ("reserved", C.c_uint32),
+                ("s_unit_bytes", C.c_uint64), ("act_bytes", C.c_uint64)]
+
+
+class ps_cost_t(C.Structure):
+    _fields_ = [("theta_bytes", C.c_uint64), ("omega_bytes", C.c_uint64),
+                ("grad_bytes", C.c_uint64), ("act_bytes", C.c_uint64),
+                ("transient_bytes", C.c_uint64), ("persistent_total", C.c_uint64),
+                ("peak_total", C.c_uint64), ("comm_grad_sync_xN", C.c_uint64),
+                ("comm_param_gather_xN", C.c_uint64), ("comm_total_bytes", C.c_double),
+                ("implied_update_gather_xN", C.c_uint64), ("psi_padded", C.c_uint64),
+                ("shard_offset", C.c_uint64), ("shard_len", C.c_uint64),
+                ("valid_len", C.c_uint64)]
+
+
+class ps_adamw_t(C.Structure):
+    _fields_ = [("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double),
+                ("eps", C.c_double), ("weight_decay", C.c_double), ("step", C.c_uint64),
+                ("grad_scale", C.c_double), ("clip_coef", C.c_double)]
+
+
+class ps_shard_t(C.Structure):
+    _fields_ = [("master", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
+                ("gather_out", C.c_void_p), ("len", C.c_uint64), ("valid_len", C.c_uint64)]
+
+
+class ps_grads_t(C.Structure):
+    _fields_ = [("contrib", C.POINTER(C.c_void_p)), ("n_contrib", C.c_uint32),
+                ("dtype", C.c_int32)]
+
+
+class ps_bucket_plan_t(C.Structure):
+    _fields_ = [("source", C.POINTER(C.c_void_p)), ("n_contrib", C.c_uint32),
+                ("dtype", C.c_int32), ("bucket_elems", C.c_uint64),
+                ("source_buckets", C.c_uint64), ("staging", C.c_void_p * 2),
+                ("copy_stream", C.c_void_p), ("compute_stream", C.c_void_p),
+                ("kernel_ms", C.POINTER(C.c_float)), ("kernel_ms_len", C.c_uint64)]
+
+
+class ps_device_info_t(C.Structure):
+    _fields_ = [("name", C.c_char * 128), ("arch", C.c_char * 64),
+                ("compute_units", C.c_int32), ("wavefront_size", C.c_int32),
+                ("clock_khz", C.c_int32), ("memory_clock_khz", C.c_int32),
+                ("memory_bus_bits", C.c_int32), ("l2_bytes", C.c_int32),
+                ("total_bytes", C.c_uint64), ("free_bytes", C.c_uint64)]
+
+
+_lib = None
+
+
+def library_path():
+    return _build.LIB
+
+
+def library():
+    """The loaded shared library.  Built first only if no build exists."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build()
+        L = C.CDLL(_build.LIB)
+        L.ps_abi_version.restype = C.c_uint32
+        L.ps_status_string.restype = C.c_char_p
+        L.ps_status_string.argtypes = [C.c_int]
+        L.ps_last_error.restype = C.c_char_p
+        L.ps_spec_preset.restype = C.c_int
+        L.ps_spec_preset.argtypes = [C.c_char_p, C.c_uint32, C.c_uint32, C.c_uint64,
+                                     C.POINTER(ps_spec_t)]
+        L.ps_cost_eval.restype = C.c_int
+        L.ps_cost_eval.argtypes = [C.POINTER(ps_spec_t), C.POINTER(ps_cost_t)]
+        L.ps_clip_coef.restype = C.c_double
+        L.ps_clip_coef.argtypes = [C.c_double] * 3
+        L.ps_device_info.restype = C.c_int
+        L.ps_device_info.argtypes = [C.POINTER(ps_device_info_t)]
+        L.ps_step_update.restype = C.c_int
+        L.ps_step_update.argtypes = [C.POINTER(ps_spec_t), C.POINTER(ps_adamw_t),
+                                     C.POINTER(ps_shard_t), C.POINTER(ps_grads_t),
+                                     C.c_uint64, C.c_uint64, C.c_void_p]
+        L.ps_step_update_bucketed.restype = C.c_int
+        L.ps_step_update_bucketed.argtypes = [C.POINTER(ps_spec_t), C.POINTER(ps_adamw_t),
+                                              C.POINTER(ps_shard_t),
+                                              C.POINTER(ps_bucket_plan_t)]
+        L.ps_workspace_bytes.restype = C.c_uint64
+        L.ps_step_reduce_sumsq.restype = C.c_int
+        L.ps_step_reduce_sumsq.argtypes = [C.POINTER(ps_spec_t), C.POINTER(ps_grads_t),
+                                           C.c_double, C.c_void_p, C.c_void_p, C.c_int32,
+                                           C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint64,
+                                           C.c_uint64, C.c_void_p]
+        L.ps_probe_copy.restype = C.c_int
+        L.ps_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
+        if L.ps_abi_version() != 1:
+            raise ImportError("libps_step.so has ABI %d, binding wants 1" % L.ps_abi_version())
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != PS_OK:
+        L = library()
+        raise PsError(status, L.ps_status_string(status).decode(), L.ps_last_error().decode())
+
+
+def _ptr_array(ptrs):
+    return (C.c_void_p * len(ptrs))(*[int(p) for p in ptrs])
+
+
+def _ref(x):
+    return C.byref(x) if x is not None else None
+
+
+def ps_abi_version():
+    return library().ps_abi_version()
+
+
+def ps_status_string(status):
+    return library().ps_status_string(int(status)).decode()
+
+
+def ps_last_error():
+    return library().ps_last_error().decode()
+
+
+def ps_spec_preset(name, n_devices, shard_index, psi, align_elems=0):
+    spec = ps_spec_t()
+    _check(library().ps_spec_preset(name.encode(), n_devices, shard_index, psi, C.byref(spec)))
+    spec.align_elems = align_elems
+    return spec
+
+
+def ps_cost_eval(spec):
+    cost = ps_cost_t()
+    _check(library().ps_cost_eval(_ref(spec), C.byref(cost)))
+    return cost
+
+
+def ps_clip_coef(sumsq_local, sumsq_others, max_norm):
+    return library().ps_clip_coef(sumsq_local, sumsq_others, max_norm)
+
+
+def ps_device_info():
+    info = ps_device_info_t()
+    _check(library().ps_device_info(C.byref(info)))
+    return info
+
+
+def make_grads(contrib_ptrs, dtype):
+    """Build a ps_grads_t; the pointer array is kept alive on the returned object."""
+    g = ps_grads_t()
+    arr = _ptr_array(contrib_ptrs) if contrib_ptrs is not None else None
+    g._keep = arr
+    g.contrib = C.cast(arr, C.POINTER(C.c_void_p)) if arr is not None else None
+    g.n_contrib = len(contrib_ptrs) if contrib_ptrs is not None else 0
+    g.dtype = dtype
+    return g
+
+
+def ps_step_update(spec, hp, shard, grads, elem_offset, elem_count, stream=0):
+    _check(library().ps_step_update(_ref(spec), _ref(hp), _ref(shard), _ref(grads),
+                                    elem_offset, elem_count, stream or None))
+
+
+def ps_step_update_bucketed(spec, hp, shard, plan):
+    _check(library().ps_step_update_bucketed(_ref(spec), _ref(hp), _ref(shard), _ref(plan)))
+
+
+def ps_workspace_bytes():
+    return library().ps_workspace_bytes()
+
+
+def ps_step_reduce_sumsq(spec, grads, grad_scale, reduced_out, sumsq_out, accumulate,
+                         workspace, workspace_bytes, elem_offset, elem_count, valid_len,
+                         stream=0):
+    _check(library().ps_step_reduce_sumsq(_ref(spec), _ref(grads), grad_scale,
+                                          reduced_out or None, sumsq_out or None,
+                                          int(accumulate), workspace or None, workspace_bytes,
+                                          elem_offset, elem_count, valid_len, stream or None))
+
+
+def ps_probe_copy(dst, src, nbytes, stream=0):
+    _check(library().ps_probe_copy(dst or None, src or None, nbytes, stream or None))
+
+
+__all__ += ["make_grads"]

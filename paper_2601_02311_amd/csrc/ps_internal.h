@@ -1,0 +1,50 @@
+// Internal interfaces between the translation units of the library.  Not
+// installed; the public surface is include/ps_step.h.
+#ifndef PS_INTERNAL_H
+#define PS_INTERNAL_H
+
+#include <cstdarg>
+#include <cstdint>
+
+#include "ps_step.h"
+
+namespace ps {
+
+void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+void clear_error();
+ps_status_t check_spec(const ps_spec_t *s);
+ps_status_t shard_geometry(const ps_spec_t *s, uint64_t *psi_padded, uint64_t *offset,
+                           uint64_t *len, uint64_t *valid);
+
+// Scalars of one step, binary32, each rounded once from a binary64 value.
+struct StepScalars {
+    float gs;   // gradient scale (1/N unless the caller overrides it)
+    float cc;   // clip coefficient
+    float b1, omb1, b2, omb2;
+    float ep;
+    float step; // lr / (1 - beta1^t)
+    float isb2; // 1 / sqrt(1 - beta2^t)
+    float lw;   // lr * weight_decay
+};
+
+struct ContribPtrs {
+    const void *p[PS_MAX_CONTRIB];
+};
+
+// Number of per-block partial sums the sum-of-squares pass may produce.  A
+// fixed constant, so that the reduction tree never depends on the device.
+constexpr uint32_t kSumsqMaxBlocks = 4096;
+
+// Launchers, defined in ps_kernels.hip.  All pointers are DEVICE pointers that
+// already point at the first element to process; `count` elements follow.
+// They return the hipError_t of the launch as int (0 = success).
+int launch_update(int dtype, uint32_t n_contrib, const ContribPtrs &g, float *master, float *m,
+                  float *v, uint16_t *out, uint64_t count, const StepScalars &s, void *stream);
+int launch_reduce_sumsq(int dtype, uint32_t n_contrib, const ContribPtrs &g, float gs,
+                        float *reduced_out, uint64_t count, double *partials,
+                        double *sumsq_out, int accumulate, void *stream);
+int launch_copy(void *dst, const void *src, uint64_t bytes, void *stream);
+
+} // namespace ps
+
+#endif

@@ -1,0 +1,363 @@
+// Device code of the sharded optimizer step for gfx950 (CDNA4, wave64).
+//
+// The step is a pure stream: per element it reads N gradient contributions and
+// three FP32 state words, and writes three FP32 state words and one bf16
+// parameter, each byte exactly once.  There is no reuse and no contraction, so
+// nothing here uses LDS (except the sum-of-squares tree) or MFMA; the design
+// goal is to keep as many fully coalesced 128-bit (state) and 64-bit (bf16)
+// accesses in flight per CU as registers allow.
+//
+// Work decomposition.  A *tile* is kThreads * 4 * U consecutive elements.
+// Inside a tile, sub-tile u covers elements [u*1024, (u+1)*1024) and lane t of
+// the block owns elements 4t..4t+3 of each sub-tile, so every wave-level
+// instruction touches one contiguous 1 KiB (FP32) or 512 B (bf16) span.  All
+// loads of a tile are issued before the first arithmetic instruction.  Blocks
+// walk the tiles grid-stride.  Elements past the last whole tile are handled
+// by a bounds-checked one-element-per-lane kernel.
+//
+// Arithmetic.  Every line of step_element() is one correctly rounded binary32
+// operation (the translation unit is compiled with contraction off and with
+// IEEE division and square root), so results do not depend on tile shape,
+// grid size or which kernel (tile or tail) handles an element.
+#ifndef PS_KERNEL_TEMPLATES_H
+#define PS_KERNEL_TEMPLATES_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ps_internal.h"
+
+namespace ps {
+
+constexpr int kThreads = 256;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool NT, typename T>
+__device__ __forceinline__ T load_vec(const T *p)
+{
+    if constexpr (NT)
+        return __builtin_nontemporal_load(p);
+    else
+        return *p;
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ void store_vec(T *p, T x)
+{
+    if constexpr (NT)
+        __builtin_nontemporal_store(x, p);
+    else
+        *p = x;
+}
+
+// bf16 -> binary32 is a 16-bit shift of the pattern (exact).
+__device__ __forceinline__ float widen_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float widen_hi(uint32_t pair)
+{
+    return __uint_as_float(pair & 0xffff0000u);
+}
+
+// binary32 -> bf16, round to nearest, ties to even; NaN -> quiet NaN, sign kept.
+__device__ __forceinline__ uint32_t narrow_bf16(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    uint32_t r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    uint32_t nan = ((u >> 16) & 0x8000u) | 0x7fc0u;
+    return (u & 0x7fffffffu) > 0x7f800000u ? nan : r;
+}
+
+// The per-element update.  acc is the fixed-order sum of the contributions.
+__device__ __forceinline__ void step_element(float acc, float &th, float &m, float &v,
+                                             const StepScalars &s)
+{
+    float g = acc * s.gs;
+    g = g * s.cc;
+    float m1 = __builtin_fmaf(s.b1, m, s.omb1 * g);
+    float v1 = __builtin_fmaf(s.b2, v, (s.omb2 * g) * g);
+    float den = __builtin_fmaf(__builtin_sqrtf(v1), s.isb2, s.ep);
+    float u = m1 / den;
+    float t0 = __builtin_fmaf(-s.lw, th, th);
+    th = __builtin_fmaf(-s.step, u, t0);
+    m = m1;
+    v = v1;
+}
+
+// Four independent elements at once (ext-vector lanes cannot bind to references).
+__device__ __forceinline__ void step_element4(const f32x4 acc, f32x4 &th, f32x4 &m, f32x4 &v,
+                                              const StepScalars &s)
+{
+    float t[4] = {th.x, th.y, th.z, th.w};
+    float mm[4] = {m.x, m.y, m.z, m.w};
+    float vv[4] = {v.x, v.y, v.z, v.w};
+    const float ac[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        step_element(ac[i], t[i], mm[i], vv[i], s);
+    th = f32x4{t[0], t[1], t[2], t[3]};
+    m = f32x4{mm[0], mm[1], mm[2], mm[3]};
+    v = f32x4{vv[0], vv[1], vv[2], vv[3]};
+}
+
+// One contribution's four consecutive elements, widened to binary32.
+template <typename G, bool NT>
+__device__ __forceinline__ f32x4 load_contrib4(const void *base, uint64_t elem)
+{
+    if constexpr (sizeof(G) == 2) {
+        u32x2 w = load_vec<NT>(reinterpret_cast<const u32x2 *>(
+            reinterpret_cast<const uint16_t *>(base) + elem));
+        f32x4 r;
+        r.x = widen_lo(w.x);
+        r.y = widen_hi(w.x);
+        r.z = widen_lo(w.y);
+        r.w = widen_hi(w.y);
+        return r;
+    } else {
+        return load_vec<NT>(
+            reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(base) + elem));
+    }
+}
+
+template <typename G>
+__device__ __forceinline__ float load_contrib1(const void *base, uint64_t elem)
+{
+    if constexpr (sizeof(G) == 2)
+        return __uint_as_float((uint32_t) reinterpret_cast<const uint16_t *>(base)[elem] << 16);
+    else
+        return reinterpret_cast<const float *>(base)[elem];
+}
+
+struct UpdateArgs {
+    ContribPtrs g;
+    float *master, *m, *v;
+    uint16_t *out;
+    uint64_t n_tiles; // whole tiles (tile kernel) or element count (tail kernel)
+    uint32_t n_contrib;
+    StepScalars s;
+};
+
+// Fused reduce + AdamW + bf16 cast over whole tiles.
+//   N  : contribution count known at compile time, 0 = read it from args
+//   G  : uint16_t (bf16 bits) or float
+//   U  : sub-tiles per tile
+//   NTL/NTS : non-temporal hint on loads / stores
+template <int N, typename G, int U, bool NTL, bool NTS>
+__global__ __launch_bounds__(kThreads) void update_tiles(const UpdateArgs a)
+{
+    constexpr uint64_t kTile = (uint64_t)kThreads * 4 * U;
+    const uint32_t n = N ? N : a.n_contrib;
+    for (uint64_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
+        const uint64_t e0 = tile * kTile + (uint64_t)threadIdx.x * 4;
+        f32x4 acc[U], th[U], mm[U], vv[U];
+        if constexpr (N != 0) {
+            f32x4 gr[N][U];
+#pragma unroll
+            for (int r = 0; r < N; ++r)
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    gr[r][u] = load_contrib4<G, NTL>(a.g.p[r], e0 + (uint64_t)u * kThreads * 4);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint64_t e = e0 + (uint64_t)u * kThreads * 4;
+                th[u] = load_vec<NTL>(reinterpret_cast<const f32x4 *>(a.master + e));
+                mm[u] = load_vec<NTL>(reinterpret_cast<const f32x4 *>(a.m + e));
+                vv[u] = load_vec<NTL>(reinterpret_cast<const f32x4 *>(a.v + e));
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                acc[u] = gr[0][u];
+#pragma unroll
+                for (int r = 1; r < N; ++r)
+                    acc[u] = acc[u] + gr[r][u];
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint64_t e = e0 + (uint64_t)u * kThreads * 4;
+                th[u] = load_vec<NTL>(reinterpret_cast<const f32x4 *>(a.master + e));
+                mm[u] = load_vec<NTL>(reinterpret_cast<const f32x4 *>(a.m + e));
+                vv[u] = load_vec<NTL>(reinterpret_cast<const f32x4 *>(a.v + e));
+                acc[u] = load_contrib4<G, NTL>(a.g.p[0], e);
+            }
+            for (uint32_t r = 1; r < n; ++r)
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    acc[u] = acc[u] +
+                             load_contrib4<G, NTL>(a.g.p[r], e0 + (uint64_t)u * kThreads * 4);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t e = e0 + (uint64_t)u * kThreads * 4;
+            step_element4(acc[u], th[u], mm[u], vv[u], a.s);
+            u32x2 pk;
+            pk.x = narrow_bf16(th[u].x) | (narrow_bf16(th[u].y) << 16);
+            pk.y = narrow_bf16(th[u].z) | (narrow_bf16(th[u].w) << 16);
+            store_vec<NTS>(reinterpret_cast<f32x4 *>(a.master + e), th[u]);
+            store_vec<NTS>(reinterpret_cast<f32x4 *>(a.m + e), mm[u]);
+            store_vec<NTS>(reinterpret_cast<f32x4 *>(a.v + e), vv[u]);
+            store_vec<NTS>(reinterpret_cast<u32x2 *>(a.out + e), pk);
+        }
+    }
+}
+
+// Same update, one element per lane with a bounds check; a.n_tiles is the
+// element count here.  Used for what is left after the last whole tile.
+template <typename G>
+__global__ __launch_bounds__(kThreads) void update_tail(const UpdateArgs a)
+{
+    const uint64_t e = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e >= a.n_tiles)
+        return;
+    float acc = load_contrib1<G>(a.g.p[0], e);
+    for (uint32_t r = 1; r < a.n_contrib; ++r)
+        acc = acc + load_contrib1<G>(a.g.p[r], e);
+    float th = a.master[e], m = a.m[e], v = a.v[e];
+    step_element(acc, th, m, v, a.s);
+    a.master[e] = th;
+    a.m[e] = m;
+    a.v[e] = v;
+    a.out[e] = (uint16_t)narrow_bf16(th);
+}
+
+// ---- sum of squares: the only place that needs cross-lane traffic ----
+
+// Fixed-shape tree: butterfly inside the wave, then the four wave sums through
+// LDS, added in wave order.  Every lane must call it.
+__device__ __forceinline__ double block_sum(double x)
+{
+    __shared__ double wave_sum[kThreads / 64];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+        x += __shfl_xor(x, off, 64);
+    if ((threadIdx.x & 63) == 0)
+        wave_sum[threadIdx.x >> 6] = x;
+    __syncthreads();
+    double t = wave_sum[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w)
+        t += wave_sum[w];
+    __syncthreads();
+    return t;
+}
+
+struct ReduceArgs {
+    ContribPtrs g;
+    float *reduced; // may be null
+    double *partials;
+    uint64_t n_tiles; // whole tiles (tile kernel) or element count (tail kernel)
+    uint32_t n_contrib;
+    uint32_t partial_slot; // tail kernel: where its single partial goes
+    float gs;
+};
+
+// Reduce the contributions, scale to the mean, optionally store it, and leave
+// one binary64 partial sum of squares per block in partials[blockIdx.x].
+template <int N, typename G, int U, bool NTL, bool NTS>
+__global__ __launch_bounds__(kThreads) void reduce_sumsq_tiles(const ReduceArgs a)
+{
+    constexpr uint64_t kTile = (uint64_t)kThreads * 4 * U;
+    const uint32_t n = N ? N : a.n_contrib;
+    double ss = 0.0;
+    for (uint64_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
+        const uint64_t e0 = tile * kTile + (uint64_t)threadIdx.x * 4;
+        f32x4 acc[U];
+        if constexpr (N != 0) {
+            f32x4 gr[N][U];
+#pragma unroll
+            for (int r = 0; r < N; ++r)
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    gr[r][u] = load_contrib4<G, NTL>(a.g.p[r], e0 + (uint64_t)u * kThreads * 4);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                acc[u] = gr[0][u];
+#pragma unroll
+                for (int r = 1; r < N; ++r)
+                    acc[u] = acc[u] + gr[r][u];
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                acc[u] = load_contrib4<G, NTL>(a.g.p[0], e0 + (uint64_t)u * kThreads * 4);
+            for (uint32_t r = 1; r < n; ++r)
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    acc[u] = acc[u] +
+                             load_contrib4<G, NTL>(a.g.p[r], e0 + (uint64_t)u * kThreads * 4);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            f32x4 g = acc[u] * a.gs;
+            ss += (double)g.x * (double)g.x;
+            ss += (double)g.y * (double)g.y;
+            ss += (double)g.z * (double)g.z;
+            ss += (double)g.w * (double)g.w;
+            if (a.reduced)
+                store_vec<NTS>(
+                    reinterpret_cast<f32x4 *>(a.reduced + e0 + (uint64_t)u * kThreads * 4), g);
+        }
+    }
+    const double t = block_sum(ss);
+    if (threadIdx.x == 0)
+        a.partials[blockIdx.x] = t;
+}
+
+// Tail: a single block strides over the leftover elements (fewer than one tile).
+template <typename G>
+__global__ __launch_bounds__(kThreads) void reduce_sumsq_tail(const ReduceArgs a)
+{
+    double ss = 0.0;
+    for (uint64_t e = threadIdx.x; e < a.n_tiles; e += kThreads) {
+        float acc = load_contrib1<G>(a.g.p[0], e);
+        for (uint32_t r = 1; r < a.n_contrib; ++r)
+            acc = acc + load_contrib1<G>(a.g.p[r], e);
+        const float g = acc * a.gs;
+        ss += (double)g * (double)g;
+        if (a.reduced)
+            a.reduced[e] = g;
+    }
+    const double t = block_sum(ss);
+    if (threadIdx.x == 0)
+        a.partials[a.partial_slot] = t;
+}
+
+// Sum partials[0 .. n) in a fixed order (lane-strided, then the block tree) and
+// store the total, or add it to what *out already holds.
+__global__ __launch_bounds__(kThreads) void finalize_sumsq(const double *partials, uint32_t n,
+                                                          double *out, int accumulate)
+{
+    double ss = 0.0;
+    for (uint32_t i = threadIdx.x; i < n; i += kThreads)
+        ss += partials[i];
+    const double t = block_sum(ss);
+    if (threadIdx.x == 0)
+        *out = accumulate ? *out + t : t;
+}
+
+// Plain copy with the update kernel's access shape (16 B per lane, grid-stride
+// over 4 KiB * U tiles); bytes beyond the last whole tile go 16 B per lane.
+template <int U, bool NTL, bool NTS>
+__global__ __launch_bounds__(kThreads) void copy_tiles(u32x4 *dst, const u32x4 *src,
+                                                       uint64_t n_tiles, uint64_t n_vec)
+{
+    constexpr uint64_t kTileVec = (uint64_t)kThreads * U;
+    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint64_t i0 = tile * kTileVec + threadIdx.x;
+        u32x4 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            x[u] = load_vec<NTL>(src + i0 + (uint64_t)u * kThreads);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            store_vec<NTS>(dst + i0 + (uint64_t)u * kThreads, x[u]);
+    }
+    if (blockIdx.x == 0)
+        for (uint64_t i = n_tiles * kTileVec + threadIdx.x; i < n_vec; i += kThreads)
+            dst[i] = src[i];
+}
+
+} // namespace ps
+
+#endif

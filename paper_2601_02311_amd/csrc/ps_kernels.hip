@@ -1,0 +1,171 @@
+// Kernel instantiations and launch shapes for gfx950.  The launch shapes are
+// constants of the library, never queried from the device, so that the
+// reduction tree of the sum of squares is the same on every run.
+#include "ps_kernel_templates.h"
+
+namespace ps {
+
+// Tuned on MI355X (256 CUs): see the launch-shape notes next to each constant.
+constexpr int kU = 2;              // sub-tiles per tile -> 2048 elements per tile
+constexpr bool kNTL = false;       // non-temporal hint on loads
+constexpr bool kNTS = false;       // non-temporal hint on stores
+constexpr uint32_t kMaxBlocks = 256 * 8; // grid-stride cap: 8 blocks per CU
+constexpr uint64_t kTileElems = (uint64_t)kThreads * 4 * kU;
+
+static uint32_t grid_for(uint64_t n_tiles, uint32_t cap)
+{
+    return (uint32_t)(n_tiles < cap ? n_tiles : cap);
+}
+
+template <typename G>
+static const void *advance(const void *p, uint64_t elems)
+{
+    return reinterpret_cast<const G *>(p) + elems;
+}
+
+template <int N, typename G>
+static void launch_update_n(const UpdateArgs &a, uint32_t grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((update_tiles<N, G, kU, kNTL, kNTS>), dim3(grid), dim3(kThreads), 0, st, a);
+}
+
+template <typename G>
+static int launch_update_t(uint32_t n_contrib, const ContribPtrs &g, float *master, float *m,
+                           float *v, uint16_t *out, uint64_t count, const StepScalars &s,
+                           hipStream_t st)
+{
+    const uint64_t n_tiles = count / kTileElems;
+    const uint64_t body = n_tiles * kTileElems;
+    UpdateArgs a;
+    a.g = g;
+    a.master = master;
+    a.m = m;
+    a.v = v;
+    a.out = out;
+    a.n_contrib = n_contrib;
+    a.s = s;
+    if (n_tiles) {
+        a.n_tiles = n_tiles;
+        const uint32_t grid = grid_for(n_tiles, kMaxBlocks);
+        switch (n_contrib) {
+        case 1: launch_update_n<1, G>(a, grid, st); break;
+        case 2: launch_update_n<2, G>(a, grid, st); break;
+        case 4: launch_update_n<4, G>(a, grid, st); break;
+        case 6: launch_update_n<6, G>(a, grid, st); break;
+        case 8: launch_update_n<8, G>(a, grid, st); break;
+        default: launch_update_n<0, G>(a, grid, st); break;
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return (int)e;
+    }
+    if (count > body) {
+        const uint64_t rest = count - body;
+        for (uint32_t r = 0; r < n_contrib; ++r)
+            a.g.p[r] = advance<G>(g.p[r], body);
+        a.master = master + body;
+        a.m = m + body;
+        a.v = v + body;
+        a.out = out + body;
+        a.n_tiles = rest;
+        const uint32_t grid = (uint32_t)((rest + kThreads - 1) / kThreads);
+        hipLaunchKernelGGL((update_tail<G>), dim3(grid), dim3(kThreads), 0, st, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return (int)e;
+    }
+    return 0;
+}
+
+int launch_update(int dtype, uint32_t n_contrib, const ContribPtrs &g, float *master, float *m,
+                  float *v, uint16_t *out, uint64_t count, const StepScalars &s, void *stream)
+{
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (dtype == PS_BF16)
+        return launch_update_t<uint16_t>(n_contrib, g, master, m, v, out, count, s, st);
+    return launch_update_t<float>(n_contrib, g, master, m, v, out, count, s, st);
+}
+
+template <int N, typename G>
+static void launch_reduce_n(const ReduceArgs &a, uint32_t grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((reduce_sumsq_tiles<N, G, kU, kNTL, kNTS>), dim3(grid), dim3(kThreads), 0,
+                       st, a);
+}
+
+template <typename G>
+static int launch_reduce_t(uint32_t n_contrib, const ContribPtrs &g, float gs, float *reduced,
+                           uint64_t count, double *partials, double *sumsq_out, int accumulate,
+                           hipStream_t st)
+{
+    const uint64_t n_tiles = count / kTileElems;
+    const uint64_t body = n_tiles * kTileElems;
+    // one block fewer than the partials array holds: the tail owns the last slot
+    const uint32_t grid = grid_for(n_tiles, kSumsqMaxBlocks - 1);
+    uint32_t n_partials = 0;
+    ReduceArgs a;
+    a.g = g;
+    a.reduced = reduced;
+    a.partials = partials;
+    a.n_contrib = n_contrib;
+    a.partial_slot = 0;
+    a.gs = gs;
+    if (n_tiles) {
+        a.n_tiles = n_tiles;
+        switch (n_contrib) {
+        case 1: launch_reduce_n<1, G>(a, grid, st); break;
+        case 2: launch_reduce_n<2, G>(a, grid, st); break;
+        case 4: launch_reduce_n<4, G>(a, grid, st); break;
+        case 6: launch_reduce_n<6, G>(a, grid, st); break;
+        case 8: launch_reduce_n<8, G>(a, grid, st); break;
+        default: launch_reduce_n<0, G>(a, grid, st); break;
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return (int)e;
+        n_partials = grid;
+    }
+    if (count > body) {
+        for (uint32_t r = 0; r < n_contrib; ++r)
+            a.g.p[r] = advance<G>(g.p[r], body);
+        a.reduced = reduced ? reduced + body : nullptr;
+        a.n_tiles = count - body;
+        a.partial_slot = n_partials;
+        hipLaunchKernelGGL((reduce_sumsq_tail<G>), dim3(1), dim3(kThreads), 0, st, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return (int)e;
+        n_partials += 1;
+    }
+    hipLaunchKernelGGL(finalize_sumsq, dim3(1), dim3(kThreads), 0, st, partials, n_partials,
+                       sumsq_out, accumulate);
+    return (int)hipGetLastError();
+}
+
+int launch_reduce_sumsq(int dtype, uint32_t n_contrib, const ContribPtrs &g, float gs,
+                        float *reduced_out, uint64_t count, double *partials, double *sumsq_out,
+                        int accumulate, void *stream)
+{
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (dtype == PS_BF16)
+        return launch_reduce_t<uint16_t>(n_contrib, g, gs, reduced_out, count, partials,
+                                         sumsq_out, accumulate, st);
+    return launch_reduce_t<float>(n_contrib, g, gs, reduced_out, count, partials, sumsq_out,
+                                  accumulate, st);
+}
+
+int launch_copy(void *dst, const void *src, uint64_t bytes, void *stream)
+{
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const uint64_t n_vec = bytes / 16;
+    const uint64_t n_tiles = n_vec / ((uint64_t)kThreads * kU * 2);
+    uint32_t grid = grid_for(n_tiles, kMaxBlocks);
+    if (grid == 0)
+        grid = 1;
+    hipLaunchKernelGGL((copy_tiles<kU * 2, kNTL, kNTS>), dim3(grid), dim3(kThreads), 0, st,
+                       reinterpret_cast<u32x4 *>(dst), reinterpret_cast<const u32x4 *>(src),
+                       n_tiles, n_vec);
+    return (int)hipGetLastError();
+}
+
+} // namespace ps

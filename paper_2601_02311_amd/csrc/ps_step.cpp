@@ -1,0 +1,503 @@
+// Device-facing entry points: argument validation (always before the first HIP
+// call), derivation of the step's binary32 scalars, and the bucket pipeline.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "ps_internal.h"
+
+using namespace ps;
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+ps_status_t hip_fail(hipError_t e, const char *what)
+{
+    if (e == hipErrorNoDevice || e == hipErrorInvalidDevice || e == hipErrorInsufficientDriver) {
+        set_error("%s: %s", what, hipGetErrorString(e));
+        return PS_ENODEVICE;
+    }
+    set_error("%s: %s", what, hipGetErrorString(e));
+    return PS_EHIP;
+}
+
+ps_status_t need_device()
+{
+    int n = 0;
+    hipError_t e = hipGetDeviceCount(&n);
+    if (e != hipSuccess || n <= 0) {
+        (void)hipGetLastError();
+        set_error("no HIP device (%s)", e == hipSuccess ? "count is 0" : hipGetErrorString(e));
+        return PS_ENODEVICE;
+    }
+    return PS_OK;
+}
+
+// beta^t for t up to 2^64-1 through the C library's pow in binary64.
+StepScalars derive_scalars(const ps_adamw_t &hp, uint32_t n_devices)
+{
+    const double bias1 = 1.0 - std::pow(hp.beta1, (double)hp.step);
+    const double bias2 = 1.0 - std::pow(hp.beta2, (double)hp.step);
+    StepScalars s;
+    s.gs = (float)(hp.grad_scale > 0.0 ? hp.grad_scale : 1.0 / (double)n_devices);
+    s.cc = (float)(hp.clip_coef > 0.0 ? hp.clip_coef : 1.0);
+    s.b1 = (float)hp.beta1;
+    s.omb1 = (float)(1.0 - hp.beta1);
+    s.b2 = (float)hp.beta2;
+    s.omb2 = (float)(1.0 - hp.beta2);
+    s.ep = (float)hp.eps;
+    s.step = (float)(hp.lr / bias1);
+    s.isb2 = (float)(1.0 / std::sqrt(bias2));
+    s.lw = (float)(hp.lr * hp.weight_decay);
+    return s;
+}
+
+ps_status_t check_hp(const ps_adamw_t *hp)
+{
+    if (!hp) {
+        set_error("hyper-parameters are NULL");
+        return PS_EINVAL;
+    }
+    if (hp->step == 0) {
+        set_error("step count t must be >= 1");
+        return PS_ERANGE;
+    }
+    if (!(hp->beta1 >= 0.0 && hp->beta1 < 1.0) || !(hp->beta2 >= 0.0 && hp->beta2 < 1.0)) {
+        set_error("beta1 and beta2 must lie in [0, 1)");
+        return PS_ERANGE;
+    }
+    if (!(hp->lr >= 0.0) || !(hp->eps >= 0.0) || !(hp->weight_decay >= 0.0) ||
+        !std::isfinite(hp->lr) || !std::isfinite(hp->eps) || !std::isfinite(hp->weight_decay)) {
+        set_error("lr, eps and weight_decay must be finite and >= 0");
+        return PS_ERANGE;
+    }
+    if (std::isnan(hp->grad_scale) || std::isnan(hp->clip_coef)) {
+        set_error("grad_scale or clip_coef is NaN");
+        return PS_ERANGE;
+    }
+    return PS_OK;
+}
+
+// The placements this path executes: Omega and G sharded, Theta R or S*.
+ps_status_t check_path(const ps_spec_t *spec)
+{
+    ps_status_t st = check_spec(spec);
+    if (st != PS_OK)
+        return st;
+    if (spec->omega != PS_S || spec->grad != PS_S || (spec->theta != PS_R && spec->theta != PS_SG)) {
+        set_error("step needs pi_Omega = S, pi_G = S and pi_Theta in {R, S*}");
+        return PS_EUNSUPPORTED;
+    }
+    return PS_OK;
+}
+
+ps_status_t check_contribs(const void *const *ptrs, uint32_t n_contrib, int32_t dtype,
+                           uint32_t n_devices, const char *what)
+{
+    if (!ptrs) {
+        set_error("%s pointer array is NULL", what);
+        return PS_EINVAL;
+    }
+    if (dtype != PS_BF16 && dtype != PS_F32) {
+        set_error("%s dtype must be PS_BF16 or PS_F32", what);
+        return PS_EINVAL;
+    }
+    if (n_contrib == 0 || n_contrib > PS_MAX_CONTRIB) {
+        set_error("%s count %u outside [1, %u]", what, n_contrib, PS_MAX_CONTRIB);
+        return PS_ERANGE;
+    }
+    if (!(n_contrib == n_devices || (n_contrib == 1 && dtype == PS_F32))) {
+        set_error("%s count %u: want n_devices = %u contributions (a missing or extra one "
+                  "breaks gradient integrity), or one pre-reduced PS_F32 gradient",
+                  what, n_contrib, n_devices);
+        return PS_EINVAL;
+    }
+    for (uint32_t r = 0; r < n_contrib; ++r) {
+        if (!ptrs[r]) {
+            set_error("%s %u is NULL", what, r);
+            return PS_EINVAL;
+        }
+        if (!aligned16(ptrs[r])) {
+            set_error("%s %u is not 16-byte aligned", what, r);
+            return PS_EALIGN;
+        }
+    }
+    return PS_OK;
+}
+
+ps_status_t check_shard(const ps_spec_t *spec, const ps_shard_t *sh, uint64_t *out_offset)
+{
+    if (!sh) {
+        set_error("shard is NULL");
+        return PS_EINVAL;
+    }
+    if (!sh->master || !sh->m || !sh->v || !sh->gather_out) {
+        set_error("shard has a NULL buffer");
+        return PS_EINVAL;
+    }
+    if (!aligned16(sh->master) || !aligned16(sh->m) || !aligned16(sh->v) ||
+        !aligned16(sh->gather_out)) {
+        set_error("shard buffer not 16-byte aligned");
+        return PS_EALIGN;
+    }
+    uint64_t padded, off, len, valid;
+    ps_status_t st = shard_geometry(spec, &padded, &off, &len, &valid);
+    if (st != PS_OK)
+        return st;
+    if (sh->len != len) {
+        set_error("shard.len %llu differs from psi_padded/N = %llu", (unsigned long long)sh->len,
+                  (unsigned long long)len);
+        return PS_ERANGE;
+    }
+    if (sh->valid_len > sh->len) {
+        set_error("shard.valid_len exceeds shard.len");
+        return PS_ERANGE;
+    }
+    // Under R the output buffer is the full replicated parameter tensor.
+    *out_offset = spec->theta == PS_R ? off : 0;
+    if (*out_offset % 8 != 0) {
+        set_error("shard offset %llu into the replicated parameters is not a multiple of 8",
+                  (unsigned long long)*out_offset);
+        return PS_EALIGN;
+    }
+    return PS_OK;
+}
+
+ps_status_t check_range(uint64_t elem_offset, uint64_t elem_count, uint64_t len)
+{
+    if (elem_offset % 8 != 0) {
+        set_error("elem_offset %llu is not a multiple of 8", (unsigned long long)elem_offset);
+        return PS_EALIGN;
+    }
+    if (elem_offset > len || elem_count > len - elem_offset) {
+        set_error("range [%llu, +%llu) leaves the shard of %llu elements",
+                  (unsigned long long)elem_offset, (unsigned long long)elem_count,
+                  (unsigned long long)len);
+        return PS_ERANGE;
+    }
+    return PS_OK;
+}
+
+// Elements of [off, off+count) that lie below valid.
+uint64_t clamp_count(uint64_t off, uint64_t count, uint64_t valid)
+{
+    if (off >= valid)
+        return 0;
+    return count < valid - off ? count : valid - off;
+}
+
+uint64_t elem_bytes(int32_t dtype) { return dtype == PS_BF16 ? 2 : 4; }
+
+} // namespace
+
+extern "C" {
+
+ps_status_t ps_device_info(ps_device_info_t *info)
+{
+    clear_error();
+    if (!info) {
+        set_error("info is NULL");
+        return PS_EINVAL;
+    }
+    ps_status_t st = need_device();
+    if (st != PS_OK)
+        return st;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return hip_fail(e, "hipGetDevice");
+    hipDeviceProp_t p;
+    e = hipGetDeviceProperties(&p, dev);
+    if (e != hipSuccess)
+        return hip_fail(e, "hipGetDeviceProperties");
+    std::memset(info, 0, sizeof *info);
+    std::strncpy(info->name, p.name, sizeof info->name - 1);
+    std::strncpy(info->arch, p.gcnArchName, sizeof info->arch - 1);
+    info->compute_units = p.multiProcessorCount;
+    info->wavefront_size = p.warpSize;
+    info->clock_khz = p.clockRate;
+    info->memory_clock_khz = p.memoryClockRate;
+    info->memory_bus_bits = p.memoryBusWidth;
+    info->l2_bytes = p.l2CacheSize;
+    size_t fr = 0, tot = 0;
+    e = hipMemGetInfo(&fr, &tot);
+    if (e != hipSuccess)
+        return hip_fail(e, "hipMemGetInfo");
+    info->total_bytes = tot;
+    info->free_bytes = fr;
+    return PS_OK;
+}
+
+ps_status_t ps_step_update(const ps_spec_t *spec, const ps_adamw_t *hp, const ps_shard_t *shard,
+                           const ps_grads_t *grads, uint64_t elem_offset, uint64_t elem_count,
+                           void *stream)
+{
+    clear_error();
+    ps_status_t st;
+    if ((st = check_path(spec)) != PS_OK || (st = check_hp(hp)) != PS_OK)
+        return st;
+    uint64_t out_off = 0;
+    if ((st = check_shard(spec, shard, &out_off)) != PS_OK)
+        return st;
+    if (!grads) {
+        set_error("grads is NULL");
+        return PS_EINVAL;
+    }
+    if ((st = check_contribs(grads->contrib, grads->n_contrib, grads->dtype, spec->n_devices,
+                             "contribution")) != PS_OK ||
+        (st = check_range(elem_offset, elem_count, shard->len)) != PS_OK)
+        return st;
+    const uint64_t count = clamp_count(elem_offset, elem_count, shard->valid_len);
+    if (count == 0)
+        return PS_OK;
+    if ((st = need_device()) != PS_OK)
+        return st;
+
+    const StepScalars s = derive_scalars(*hp, spec->n_devices);
+    ContribPtrs g;
+    std::memset(&g, 0, sizeof g);
+    for (uint32_t r = 0; r < grads->n_contrib; ++r)
+        g.p[r] = grads->contrib[r];
+    uint16_t *out = reinterpret_cast<uint16_t *>(shard->gather_out) + out_off + elem_offset;
+    int e = launch_update(grads->dtype, grads->n_contrib, g, shard->master + elem_offset,
+                          shard->m + elem_offset, shard->v + elem_offset, out, count, s, stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "update kernel launch");
+    return PS_OK;
+}
+
+uint64_t ps_workspace_bytes(void) { return (uint64_t)kSumsqMaxBlocks * sizeof(double); }
+
+ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
+                                 double grad_scale, float *reduced_out, double *sumsq_out,
+                                 int32_t accumulate, void *workspace, uint64_t workspace_bytes,
+                                 uint64_t elem_offset, uint64_t elem_count, uint64_t valid_len,
+                                 void *stream)
+{
+    clear_error();
+    ps_status_t st;
+    if ((st = check_path(spec)) != PS_OK)
+        return st;
+    if (!grads || !sumsq_out || !workspace) {
+        set_error("grads, sumsq_out or workspace is NULL");
+        return PS_EINVAL;
+    }
+    if (std::isnan(grad_scale)) {
+        set_error("grad_scale is NaN");
+        return PS_ERANGE;
+    }
+    if (workspace_bytes < ps_workspace_bytes()) {
+        set_error("workspace of %llu bytes is smaller than ps_workspace_bytes()",
+                  (unsigned long long)workspace_bytes);
+        return PS_ERANGE;
+    }
+    if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(sumsq_out) & 7u) ||
+        (reduced_out && !aligned16(reduced_out))) {
+        set_error("workspace, sumsq_out or reduced_out is misaligned");
+        return PS_EALIGN;
+    }
+    if ((st = check_contribs(grads->contrib, grads->n_contrib, grads->dtype, spec->n_devices,
+                             "contribution")) != PS_OK)
+        return st;
+    uint64_t padded, off, len, valid;
+    if ((st = shard_geometry(spec, &padded, &off, &len, &valid)) != PS_OK ||
+        (st = check_range(elem_offset, elem_count, len)) != PS_OK)
+        return st;
+    if (valid_len > len) {
+        set_error("valid_len exceeds the shard length");
+        return PS_ERANGE;
+    }
+    if ((st = need_device()) != PS_OK)
+        return st;
+
+    const uint64_t count = clamp_count(elem_offset, elem_count, valid_len);
+    const float gs = (float)(grad_scale > 0.0 ? grad_scale : 1.0 / (double)spec->n_devices);
+    ContribPtrs g;
+    std::memset(&g, 0, sizeof g);
+    for (uint32_t r = 0; r < grads->n_contrib; ++r)
+        g.p[r] = grads->contrib[r];
+    int e = launch_reduce_sumsq(grads->dtype, grads->n_contrib, g, gs,
+                                reduced_out ? reduced_out + elem_offset : nullptr, count,
+                                reinterpret_cast<double *>(workspace), sumsq_out, accumulate,
+                                stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "reduce kernel launch");
+    return PS_OK;
+}
+
+ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
+                                    const ps_shard_t *shard, const ps_bucket_plan_t *plan)
+{
+    clear_error();
+    ps_status_t st;
+    if ((st = check_path(spec)) != PS_OK || (st = check_hp(hp)) != PS_OK)
+        return st;
+    uint64_t out_off = 0;
+    if ((st = check_shard(spec, shard, &out_off)) != PS_OK)
+        return st;
+    if (!plan) {
+        set_error("plan is NULL");
+        return PS_EINVAL;
+    }
+    if ((st = check_contribs(plan->source, plan->n_contrib, plan->dtype, spec->n_devices,
+                             "bucket source")) != PS_OK)
+        return st;
+    if (plan->bucket_elems == 0 || plan->bucket_elems % 8 != 0) {
+        set_error("bucket_elems must be a positive multiple of 8");
+        return PS_EALIGN;
+    }
+    if (plan->source_buckets == 0) {
+        set_error("source_buckets must be >= 1");
+        return PS_ERANGE;
+    }
+    if (!plan->staging[0] || !plan->staging[1] || plan->staging[0] == plan->staging[1]) {
+        set_error("two distinct staging buffers are required");
+        return PS_EINVAL;
+    }
+    if (!aligned16(plan->staging[0]) || !aligned16(plan->staging[1])) {
+        set_error("staging buffer not 16-byte aligned");
+        return PS_EALIGN;
+    }
+    if (plan->copy_stream == plan->compute_stream) {
+        set_error("copy_stream and compute_stream must differ");
+        return PS_EINVAL;
+    }
+    const uint64_t n_buckets = (shard->len + plan->bucket_elems - 1) / plan->bucket_elems;
+    if (plan->kernel_ms && plan->kernel_ms_len < n_buckets) {
+        set_error("kernel_ms holds %llu entries, %llu buckets", (unsigned long long)plan->kernel_ms_len,
+                  (unsigned long long)n_buckets);
+        return PS_ERANGE;
+    }
+    if (n_buckets == 0)
+        return PS_OK;
+    if ((st = need_device()) != PS_OK)
+        return st;
+
+    hipStream_t copy = reinterpret_cast<hipStream_t>(plan->copy_stream);
+    hipStream_t comp = reinterpret_cast<hipStream_t>(plan->compute_stream);
+    const StepScalars s = derive_scalars(*hp, spec->n_devices);
+    const uint64_t eb = elem_bytes(plan->dtype);
+    const uint64_t slot_stride = plan->bucket_elems * eb; // bytes between contributions in a slot
+    const bool timed = plan->kernel_ms != nullptr;
+
+    // staged[k]: slot k holds a complete bucket; freed[k]: the kernel reading slot k is done.
+    hipEvent_t staged[2] = {nullptr, nullptr}, freed[2] = {nullptr, nullptr};
+    std::vector<hipEvent_t> t0, t1;
+    hipError_t e = hipSuccess;
+    const char *what = "";
+#define PS_TRY(call)                                                                              \
+    do {                                                                                          \
+        if (e == hipSuccess) {                                                                    \
+            e = (call);                                                                           \
+            what = #call;                                                                         \
+        }                                                                                         \
+    } while (0)
+    for (int k = 0; k < 2; ++k) {
+        PS_TRY(hipEventCreateWithFlags(&staged[k], hipEventDisableTiming));
+        PS_TRY(hipEventCreateWithFlags(&freed[k], hipEventDisableTiming));
+    }
+    if (timed) {
+        t0.assign(n_buckets, nullptr);
+        t1.assign(n_buckets, nullptr);
+        for (uint64_t b = 0; b < n_buckets; ++b) {
+            PS_TRY(hipEventCreate(&t0[b]));
+            PS_TRY(hipEventCreate(&t1[b]));
+        }
+    }
+
+    auto stage = [&](uint64_t b) {
+        const int k = (int)(b & 1);
+        const uint64_t lo = b * plan->bucket_elems;
+        const uint64_t cnt = clamp_count(lo, plan->bucket_elems, shard->len);
+        const uint64_t src_off = (b % plan->source_buckets) * plan->bucket_elems * eb;
+        if (b >= 2) // the slot is reused: wait for the kernel that read it
+            PS_TRY(hipStreamWaitEvent(copy, freed[k], 0));
+        for (uint32_t r = 0; r < plan->n_contrib; ++r)
+            PS_TRY(hipMemcpyAsync(reinterpret_cast<char *>(plan->staging[k]) + r * slot_stride,
+                                  reinterpret_cast<const char *>(plan->source[r]) + src_off,
+                                  cnt * eb, hipMemcpyDefault, copy));
+        PS_TRY(hipEventRecord(staged[k], copy));
+    };
+
+    stage(0);
+    for (uint64_t b = 0; b < n_buckets && e == hipSuccess; ++b) {
+        const int k = (int)(b & 1);
+        if (b + 1 < n_buckets)
+            stage(b + 1);
+        const uint64_t lo = b * plan->bucket_elems;
+        const uint64_t cnt = clamp_count(lo, plan->bucket_elems, shard->valid_len);
+        PS_TRY(hipStreamWaitEvent(comp, staged[k], 0));
+        if (timed)
+            PS_TRY(hipEventRecord(t0[b], comp));
+        if (cnt && e == hipSuccess) {
+            ContribPtrs g;
+            std::memset(&g, 0, sizeof g);
+            for (uint32_t r = 0; r < plan->n_contrib; ++r)
+                g.p[r] = reinterpret_cast<const char *>(plan->staging[k]) + r * slot_stride;
+            uint16_t *out = reinterpret_cast<uint16_t *>(shard->gather_out) + out_off + lo;
+            int le = launch_update(plan->dtype, plan->n_contrib, g, shard->master + lo,
+                                   shard->m + lo, shard->v + lo, out, cnt, s, comp);
+            if (le != 0) {
+                e = (hipError_t)le;
+                what = "update kernel launch";
+            }
+        }
+        if (timed)
+            PS_TRY(hipEventRecord(t1[b], comp));
+        PS_TRY(hipEventRecord(freed[k], comp));
+    }
+    // Later work on the copy stream must not overtake the last kernels.
+    PS_TRY(hipStreamWaitEvent(copy, freed[(n_buckets - 1) & 1], 0));
+
+    if (timed) {
+        PS_TRY(hipStreamSynchronize(comp));
+        PS_TRY(hipStreamSynchronize(copy));
+        for (uint64_t b = 0; b < n_buckets; ++b)
+            PS_TRY(hipEventElapsedTime(&plan->kernel_ms[b], t0[b], t1[b]));
+    }
+#undef PS_TRY
+    // Destroying an event that is still pending is allowed: its resources are
+    // released once the recorded work has completed.
+    for (int k = 0; k < 2; ++k) {
+        if (staged[k])
+            (void)hipEventDestroy(staged[k]);
+        if (freed[k])
+            (void)hipEventDestroy(freed[k]);
+    }
+    for (hipEvent_t ev : t0)
+        if (ev)
+            (void)hipEventDestroy(ev);
+    for (hipEvent_t ev : t1)
+        if (ev)
+            (void)hipEventDestroy(ev);
+    if (e != hipSuccess)
+        return hip_fail(e, what);
+    return PS_OK;
+}
+
+ps_status_t ps_probe_copy(void *dst, const void *src, uint64_t bytes, void *stream)
+{
+    clear_error();
+    if (!dst || !src) {
+        set_error("dst or src is NULL");
+        return PS_EINVAL;
+    }
+    if (!aligned16(dst) || !aligned16(src) || bytes % 16 != 0) {
+        set_error("copy needs 16-byte aligned pointers and size");
+        return PS_EALIGN;
+    }
+    if (bytes == 0)
+        return PS_OK;
+    ps_status_t st = need_device();
+    if (st != PS_OK)
+        return st;
+    int e = launch_copy(dst, src, bytes, stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "copy kernel launch");
+    return PS_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,81 @@
+"""Device-side (torch, ROCm) generators for the large workloads.
+
+Buffers are filled in place, chunk by chunk, from a seeded ``torch.Generator``
+so that no temporary larger than a chunk is ever alive.  bf16 data is stored
+in ``torch.bfloat16`` tensors; the step library and the oracle only ever see
+the raw bytes.
+"""
+import torch
+
+CHUNK = 1 << 27
+
+
+def _gen(seed, *stream):
+    g = torch.Generator(device="cuda")
+    s = seed
+    for x in stream:
+        s = (s * 1_000_003 + int(x) + 1) % (2 ** 63 - 1)
+    g.manual_seed(s)
+    return g
+
+
+def fill_normal_(t, std, seed, *stream, absolute=False, square=False):
+    """t <- std * N(0,1), optionally |.| or (.)^2, chunked."""
+    g = _gen(seed, *stream)
+    n = t.numel()
+    for lo in range(0, n, CHUNK):
+        c = t[lo:min(lo + CHUNK, n)]
+        c.normal_(0.0, std, generator=g)
+        if absolute:
+            c.abs_()
+        if square:
+            c.mul_(c)
+    return t
+
+
+def fill_gradient_(t, seed, step, replica, std=1e-3, outlier_frac=0.0, outlier_mult=1.0,
+                   student_t_dof=0):
+    """One device's gradient contribution (bf16 or fp32 tensor), in place."""
+    g = _gen(seed, 4, step, replica)
+    n = t.numel()
+    for lo in range(0, n, CHUNK):
+        c = t[lo:min(lo + CHUNK, n)]
+        if student_t_dof > 0:
+            z = torch.empty(c.numel(), dtype=torch.float32, device=t.device).normal_(generator=g)
+            chi = torch.zeros_like(z)
+            for _ in range(student_t_dof):
+                w = torch.empty_like(z).normal_(generator=g)
+                chi.addcmul_(w, w)
+            z.div_(chi.div_(student_t_dof).sqrt_()).mul_(std)
+            c.copy_(z)
+            del z, chi, w
+        else:
+            c.normal_(0.0, std, generator=g)
+        if outlier_frac > 0.0:
+            mask = torch.empty(c.numel(), dtype=torch.float32, device=t.device).uniform_(generator=g)
+            c.mul_(torch.where(mask < outlier_frac, outlier_mult, 1.0).to(c.dtype))
+            del mask
+    return t
+
+
+def workload_state(w, n=None):
+    """(master, m, v) fp32 device tensors of the workload's shard length."""
+    n = w.shard_len if n is None else n
+    master = fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), w.theta_std, w.seed, 1)
+    if w.warm_moments:
+        m = fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), 1e-3, w.seed, 2,
+                         absolute=True)
+        v = fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), 1e-3, w.seed, 3,
+                         square=True)
+    else:
+        m = torch.zeros(n, dtype=torch.float32, device="cuda")
+        v = torch.zeros(n, dtype=torch.float32, device="cuda")
+    return master, m, v
+
+
+def workload_gradients(w, step, n=None):
+    n = w.shard_len if n is None else n
+    dt = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
+    return [fill_gradient_(torch.empty(n, dtype=dt, device="cuda"), w.seed, step, r, w.grad_std,
+                           w.outlier_frac, w.outlier_mult, w.student_t_dof)
+            for r in range(w.n_devices)]

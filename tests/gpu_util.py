@@ -1,0 +1,69 @@
+"""Helpers for the GPU tests: upload/download and thin call wrappers.  Imports the
+GPU binding only; the oracle is imported by the tests themselves."""
+import ctypes as C
+
+import numpy as np
+import torch
+
+import paper_2601_02311_amd as ps
+
+DT = {"bf16": ps.PS_BF16, "f32": ps.PS_F32}
+
+
+def dev(a):
+    """numpy -> device tensor carrying the same bytes (uint16 travels as int16)."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+def host(t):
+    """device tensor -> numpy with the original byte meaning (2-byte types -> uint16)."""
+    t = t.detach()
+    if t.dtype == torch.bfloat16:
+        t = t.view(torch.int16)
+    a = t.cpu().numpy()
+    return a.view(np.uint16) if a.dtype == np.int16 else a
+
+
+def stream_handle(s=None):
+    return (s or torch.cuda.current_stream()).cuda_stream
+
+
+def hp_of(w=None, t=1, **kw):
+    d = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+    if w is not None:
+        d = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay)
+    d.update({k: v for k, v in kw.items() if k in d})
+    return d, ps.ps_adamw_t(d["lr"], d["beta1"], d["beta2"], d["eps"], d["weight_decay"], t,
+                            kw.get("grad_scale", 0.0), kw.get("clip_coef", 0.0))
+
+
+def shard_of(master, m, v, out, length, valid=None):
+    return ps.ps_shard_t(master.data_ptr(), m.data_ptr(), v.data_ptr(), out.data_ptr(), length,
+                         length if valid is None else valid)
+
+
+def grads_of(tensors, dtype, elem_offset=0):
+    esz = 2 if dtype == "bf16" else 4
+    return ps.make_grads([t.data_ptr() + elem_offset * esz for t in tensors], DT[dtype])
+
+
+def ulp_diff(a, b):
+    def key(x):
+        i = np.ascontiguousarray(x, dtype=np.float32).view(np.int32).astype(np.int64)
+        return np.where(i < 0, -(i & 0x7fffffff), i)
+    return np.abs(key(a) - key(b))
+
+
+def assert_state_parity(got, want, what=""):
+    """got/want: (theta, m, v, p) numpy arrays.  master/m/v within 2 binary32 ulp of the
+    oracle (NaNs must coincide); the bf16 image bit-exact wherever theta' agrees."""
+    for name, g, w in zip(("theta", "m", "v"), got[:3], want[:3]):
+        gn, wn = np.isnan(g), np.isnan(w)
+        assert np.array_equal(gn, wn), "%s %s: NaN pattern differs" % (what, name)
+        d = ulp_diff(g[~gn], w[~wn])
+        assert d.size == 0 or d.max() <= 2, "%s %s: max ulp %d" % (what, name, d.max())
+    same = got[0].view(np.uint32) == want[0].view(np.uint32)
+    assert np.array_equal(got[3][same], want[3][same]), "%s bf16 image differs" % what
+    return int((~same).sum())

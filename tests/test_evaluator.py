@@ -1,0 +1,138 @@
+"""The library's host-side evaluator against the paper's printed figures and
+against the exact-rational closed forms of oracle/placement.py."""
+import random
+import re
+import os
+
+import pytest
+
+import paper_2601_02311_amd as ps
+from oracle import placement as pl
+from synth import WORKLOADS
+
+GB = 10 ** 9
+MODE = {"R": ps.PS_R, "S": ps.PS_S, "S*": ps.PS_SG, "M": ps.PS_M, "O": ps.PS_O}
+
+
+def test_printed_figures(golden):
+    P, N = int(golden["P_70b"]), int(golden["N_example"])
+    dp = ps.ps_cost_eval(ps.ps_spec_preset("dp", N, 0, P))
+    z3 = ps.ps_cost_eval(ps.ps_spec_preset("zero3", N, 0, P))
+    assert dp.theta_bytes == int(golden["theta_GB"]) * GB
+    assert dp.grad_bytes == int(golden["grad_GB"]) * GB
+    assert dp.omega_bytes == (int(golden["master_GB"]) + int(golden["adam_mv_GB"])) * GB
+    assert dp.peak_total == int(golden["model_state_GB"]) * GB == int(golden["bytes_per_param"]) * P
+    assert z3.peak_total == int(golden["zero3_per_device_GB"]) * GB
+    assert dp.peak_total == int(golden["memory_reduction"]) * z3.peak_total
+    assert dp.comm_total_bytes == float(golden["dp_comm_P_times"]) * P
+    assert z3.comm_total_bytes == float(golden["zero3_comm_P_times"]) * P
+    assert round(dp.comm_total_bytes / GB) == int(golden["dp_comm_GB_approx"])
+    assert round(z3.comm_total_bytes / GB) == int(golden["zero3_comm_GB_approx"])
+    # exactly 3/2 on the integer fields
+    assert 2 * (z3.comm_grad_sync_xN + z3.comm_param_gather_xN) == 3 * dp.comm_grad_sync_xN
+
+
+def test_table2_presets_match_closed_forms():
+    P, N = 70 * 10 ** 9, 8
+    for name, modes in pl.STRATEGIES.items():
+        spec = ps.ps_spec_preset(name, N, 3, P)
+        assert (spec.theta, spec.omega, spec.grad, spec.act) == tuple(MODE[m] for m in modes)
+        c = ps.ps_cost_eval(spec)
+        assert c.peak_total == pl.memory(modes, P, N)
+        assert c.comm_grad_sync_xN + c.comm_param_gather_xN == pl.communication(modes, P, N) * N
+    # values derived (not printed) from the paper's rules at 70B, N = 8
+    assert ps.ps_cost_eval(ps.ps_spec_preset("zero1", N, 0, P)).peak_total == 385 * GB
+    z2 = ps.ps_cost_eval(ps.ps_spec_preset("zero2", N, 0, P))
+    assert z2.peak_total == 262.5 * GB and z2.comm_total_bytes == 122.5 * GB
+    assert z2.implied_update_gather_xN == 7 * 140 * GB      # reported, never added in
+    assert ps.ps_cost_eval(ps.ps_spec_preset("zero_offload", N, 0, P)).peak_total == 17.5 * GB
+    assert ps.ps_cost_eval(ps.ps_spec_preset("fsdp", N, 0, P)).peak_total == 140 * GB
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_spec_preset("zero9", N, 0, P)
+    assert e.value.status == ps.PS_EINVAL
+
+
+def test_random_specs_match_closed_forms():
+    rnd = random.Random(5)
+    modes = list(MODE)
+    for _ in range(300):
+        N = rnd.choice([1, 2, 3, 4, 6, 8, 16, 64])
+        P = N * rnd.randrange(1, 10 ** 9)
+        m = [rnd.choice(modes) for _ in range(4)]
+        s_unit = rnd.choice([0, 12 * 8192 * 8192 * 2])
+        act = N * rnd.randrange(0, 10 ** 9)
+        spec = ps.ps_spec_t(MODE[m[0]], MODE[m[1]], MODE[m[2]], MODE[m[3]], N, rnd.randrange(N),
+                            P, 0, 0, s_unit, act)
+        c = ps.ps_cost_eval(spec)
+        assert c.peak_total == pl.memory(tuple(m), P, N, s_unit, act)
+        assert c.persistent_total + c.transient_bytes == c.peak_total
+        assert c.comm_grad_sync_xN + c.comm_param_gather_xN == pl.communication(tuple(m), P, N) * N
+        assert (c.psi_padded, c.shard_offset, c.shard_len, c.valid_len) == \
+            pl.shard_geometry(P, N, spec.shard_index)
+
+
+def test_shard_geometry_with_padding_and_workloads():
+    for psi, N, a in [(25, 4, 8), (1535, 6, 256), (1537, 6, 256), (13_015_864_320 - 1001, 6, 256)]:
+        for i in range(N):
+            spec = ps.ps_spec_preset("zero3", N, i, psi, align_elems=a)
+            c = ps.ps_cost_eval(spec)
+            assert (c.psi_padded, c.shard_offset, c.shard_len, c.valid_len) == \
+                pl.shard_geometry(psi, N, i, a)
+    for w in WORKLOADS.values():
+        c = ps.ps_cost_eval(ps.ps_spec_preset(w.strategy, w.n_devices, w.shard_index, w.psi,
+                                               align_elems=w.align_elems))
+        assert (c.psi_padded, c.shard_offset, c.shard_len, c.valid_len) == \
+            (w.psi_padded, w.shard_offset, w.shard_len, w.valid_len)
+    # the sizes the workload descriptions quote
+    assert WORKLOADS["tiny"].shard_len == 262_144
+    assert WORKLOADS["gpt2s"].shard_len == 15_554_976
+    assert WORKLOADS["7b_zero2"].shard_len == 842_301_952
+    assert WORKLOADS["70b_zero3"].shard_len == 8_750_000_000
+    assert WORKLOADS["13b_clip"].shard_len == 2_169_310_720
+    z = ps.ps_cost_eval(ps.ps_spec_preset("zero2", 8, 0, WORKLOADS["7b_zero2"].psi))
+    assert round(z.omega_bytes / GB, 1) == 10.1
+    z = ps.ps_cost_eval(ps.ps_spec_preset("zero3", 8, 7, WORKLOADS["70b_zero3"].psi))
+    assert z.omega_bytes == 105 * GB and z.theta_bytes == 17.5 * GB
+
+
+def test_errors():
+    def status(fn):
+        with pytest.raises(ps.PsError) as e:
+            fn()
+        return e.value.status
+    assert status(lambda: ps.ps_cost_eval(None)) == ps.PS_EINVAL
+    assert status(lambda: ps.ps_cost_eval(ps.ps_spec_preset("dp", 0, 0, 8))) == ps.PS_EINVAL
+    assert status(lambda: ps.ps_cost_eval(ps.ps_spec_preset("dp", 4, 4, 8))) == ps.PS_ERANGE
+    assert status(lambda: ps.ps_cost_eval(ps.ps_spec_preset("zero3", 4, 0, 10))) == ps.PS_ERANGE
+    bad = ps.ps_spec_preset("dp", 4, 0, 8)
+    bad.theta = 7
+    assert status(lambda: ps.ps_cost_eval(bad)) == ps.PS_EINVAL
+    assert status(lambda: ps.ps_cost_eval(ps.ps_spec_preset("dp", 4, 0, 2 ** 62))) == ps.PS_ERANGE
+    assert "overflow" in ps.ps_last_error()
+    assert ps.ps_cost_eval(ps.ps_spec_preset("zero3", 4, 0, 10, align_elems=2)).psi_padded == 16
+
+
+def test_header_symbols_are_exported_and_bound():
+    """Every function include/ps_step.h declares is exported by the built library."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    text = open(os.path.join(root, "include", "ps_step.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(ps_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(ps.EXPORTED_SYMBOLS)
+    L = ps.library()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert ps.ps_abi_version() == 1
+    assert ps.ps_status_string(ps.PS_EALIGN).startswith("pointer")
+
+
+def test_clip_coef_against_the_oracle():
+    import math
+    from oracle import step as orc
+    for ss, others, mx in [(4.0, 12.0, 1.0), (1e-9, 0.0, 1.0), (3.7, 5 * 3.7, 0.5), (0.0, 0.0, 1.0),
+                           (1e30, 1e30, 1e-3)]:
+        assert ps.ps_clip_coef(ss, others, mx) == orc.clip_coef(ss, others, mx)
+    assert ps.ps_clip_coef(4.0, 12.0, 1.0) == 1.0 / (4.0 + 1e-6)
+    assert ps.ps_clip_coef(1e-12, 0.0, 1.0) == 1.0
+    for bad in [(math.inf, 0.0, 1.0), (math.nan, 0.0, 1.0), (-1.0, 0.0, 1.0), (1.0, 1.0, 0.0)]:
+        assert math.isnan(ps.ps_clip_coef(*bad))

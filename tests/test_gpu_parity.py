@@ -1,0 +1,350 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by
+element, on the same seeded inputs.  Bar: shard indexing, the fixed-order
+reduction and the bf16 cast bit-exact; master/m/v within 2 binary32 ulp."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2601_02311_amd as ps
+from oracle import placement as pl
+from oracle import step as orc
+from synth import WORKLOADS
+from synth import host as gen
+
+from gpu_util import (assert_state_parity, dev, grads_of, host, hp_of, shard_of,
+                      stream_handle, ulp_diff)
+
+pytestmark = pytest.mark.gpu
+
+TILE = 2048  # elements per tile of the update kernel (256 lanes x 4 x 2)
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def _run_gpu(spec, hp, state, grads_np, dtype, n, valid=None, offset=0, count=None, out_len=None):
+    """Upload, run one ps_step_update on [offset, offset+count), download."""
+    th, m, v, p = [dev(a) for a in state]
+    gd = [dev(g) for g in grads_np]
+    shard = shard_of(th, m, v, p, n, valid)
+    count = n - offset if count is None else count
+    ps.ps_step_update(spec, hp, shard, grads_of(gd, dtype, offset), offset, count, stream_handle())
+    torch.cuda.synchronize()
+    return [host(t) for t in (th, m, v, p)]
+
+
+def test_tiny_ten_steps_all_shards_equal_unsharded():
+    w = WORKLOADS["tiny"]
+    _say("tiny: psi=%d N=%d, 10 steps, all shards vs unsharded oracle" % (w.psi, w.n_devices))
+    psi, N = w.psi, w.n_devices
+    full = [gen.master(psi, w.seed), *gen.moments(psi, w.seed, False), np.zeros(psi, np.uint16)]
+    shards = []
+    for i in range(N):
+        spec = ps.ps_spec_preset(w.strategy, N, i, psi)
+        c = ps.ps_cost_eval(spec)
+        assert (c.shard_offset, c.shard_len) == pl.shard_geometry(psi, N, i)[1:3]
+        sl = slice(c.shard_offset, c.shard_offset + c.shard_len)
+        t = [dev(np.ascontiguousarray(a[sl])) for a in full]
+        shards.append((spec, c, sl, t))
+    for t_step in range(w.first_step, w.first_step + w.n_steps):
+        grads = gen.workload_gradients(w, t_step)
+        hpd, hp = hp_of(w, t_step)
+        orc.step_f32(grads, orc.derive_scalars(t=t_step, n_devices=N, **hpd), *full)
+        for spec, c, sl, t in shards:
+            gd = [dev(np.ascontiguousarray(g[sl])) for g in grads]
+            ps.ps_step_update(spec, hp, shard_of(*t, c.shard_len), grads_of(gd, "bf16"), 0,
+                              c.shard_len, stream_handle())
+            torch.cuda.synchronize()
+    mismatched = 0
+    for spec, c, sl, t in shards:
+        got = [host(x) for x in t]
+        mismatched += assert_state_parity(got, [a[sl] for a in full], "shard %d" % spec.shard_index)
+    _say("tiny: elements whose theta differs in the last bits after 10 steps: %d" % mismatched)
+    assert mismatched == 0      # same op order on both sides: expect identical bits
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 5, 6, 8, 16])
+def test_ragged_sizes_every_contribution_count(dtype, N):
+    if N == 1 and dtype == "bf16":
+        pytest.skip("a single contribution is the pre-reduced fp32 gradient")
+    n = 3 * TILE + 1234 + 3           # several tiles and a ragged tail
+    valid = n - 5                      # last five elements are padding
+    _say("ragged n=%d valid=%d N=%d %s" % (n, valid, N, dtype))
+    psi = n * max(N, 1)
+    spec = ps.ps_spec_preset("zero3", max(N, 1), 0, psi)
+    if N == 1:
+        spec = ps.ps_spec_preset("zero3", 4, 0, n * 4)
+    grads = [gen.gradient(n, 77, 3, r, dtype, std=1e-3, outlier_frac=0.01, outlier_mult=100.0)
+             for r in range(N)]
+    th = gen.master(n, 77)
+    m, v = gen.moments(n, 77, True)
+    canary = np.uint16(0xBEEF)
+    state = [th, m, v, np.full(n, canary, np.uint16)]
+    hpd, hp = hp_of(None, 1000, grad_scale=(1.0 if N == 1 else 0.0))
+    want = [a.copy() for a in state]
+    s = orc.derive_scalars(t=1000, n_devices=spec.n_devices, grad_scale=(1.0 if N == 1 else 0.0), **hpd)
+    orc.step_f32(grads, s, *want, lo=0, hi=valid)
+    got = _run_gpu(spec, hp, state, grads, dtype, n, valid)
+    assert assert_state_parity(got, want, "ragged") == 0
+    for g, a in zip(got, state):       # pads untouched, byte for byte
+        assert np.array_equal(g[valid:].view(np.uint8), a[valid:].view(np.uint8))
+    assert (got[3][valid:] == canary).all()
+
+
+def test_bucket_range_inside_a_shard():
+    """Only [offset, offset+count) is touched; gradient pointers are bucket-based."""
+    n, N = 5 * TILE + 40, 4
+    off, cnt = 2 * TILE + 8, 2 * TILE + 17
+    _say("sub-range [%d,+%d) of n=%d" % (off, cnt, n))
+    spec = ps.ps_spec_preset("zero3", N, 2, n * N)
+    grads = [gen.gradient(n, 5, 0, r, "bf16") for r in range(N)]
+    state = [gen.master(n, 5), *gen.moments(n, 5, True), np.full(n, 0x1234, np.uint16)]
+    hpd, hp = hp_of(None, 17)
+    want = [a.copy() for a in state]
+    orc.step_f32(grads, orc.derive_scalars(t=17, n_devices=N, **hpd), *want, lo=off, hi=off + cnt)
+    got = _run_gpu(spec, hp, state, grads, "bf16", n, None, off, cnt)
+    for g, w_ in zip(got, want):
+        assert np.array_equal(g.view(np.uint8), w_.view(np.uint8))
+
+
+def test_zero2_writes_its_slice_of_the_replicated_parameters():
+    n, N, i = TILE + 24, 4, 2
+    _say("zero2 output slice, n=%d shard %d" % (n, i))
+    spec = ps.ps_spec_preset("zero2", N, i, n * N)
+    c = ps.ps_cost_eval(spec)
+    grads = [gen.gradient(n, 8, 0, r, "bf16") for r in range(N)]
+    state = [gen.master(n, 8), *gen.moments(n, 8, False), np.zeros(n, np.uint16)]
+    hpd, hp = hp_of(None, 1)
+    want = [a.copy() for a in state]
+    orc.step_f32(grads, orc.derive_scalars(t=1, n_devices=N, **hpd), *want)
+    th, m, v = [dev(a) for a in state[:3]]
+    full_p = dev(np.full(n * N, 0xCAFE, np.uint16))
+    gd = [dev(g) for g in grads]
+    ps.ps_step_update(spec, hp, shard_of(th, m, v, full_p, n), grads_of(gd, "bf16"), 0, n,
+                      stream_handle())
+    torch.cuda.synchronize()
+    p = host(full_p)
+    assert np.array_equal(p[c.shard_offset:c.shard_offset + n], want[3])
+    assert (p[:c.shard_offset] == 0xCAFE).all() and (p[c.shard_offset + n:] == 0xCAFE).all()
+    assert np.array_equal(host(th).view(np.uint32), want[0].view(np.uint32))
+
+
+def test_gpt2s_shard_full_size():
+    w = WORKLOADS["gpt2s"]
+    n, N, t = w.shard_len, w.n_devices, w.first_step
+    _say("gpt2s: n=%d N=%d t=%d (not a multiple of the tile)" % (n, N, t))
+    assert n % TILE != 0
+    grads = [gen.gradient(n, w.seed, t, r, "bf16", w.grad_std) for r in range(N)]
+    state = [gen.master(n, w.seed), *gen.moments(n, w.seed, True), np.zeros(n, np.uint16)]
+    hpd, hp = hp_of(w, t)
+    want = [a.copy() for a in state]
+    orc.step_f32(grads, orc.derive_scalars(t=t, n_devices=N, **hpd), *want)
+    spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi)
+    got = _run_gpu(spec, hp, state, grads, "bf16", n)
+    assert assert_state_parity(got, want, "gpt2s") == 0
+    assert np.array_equal(got[3], want[3])
+
+
+def test_special_values_propagate():
+    """Inf/NaN/huge/subnormal/zero gradients and states: no special casing, same as the oracle."""
+    n, N = TILE + 64, 2
+    _say("special values n=%d" % n)
+    spec = ps.ps_spec_preset("zero3", N, 0, n * N)
+    g0 = gen.gradient(n, 3, 0, 0, "f32")
+    g1 = gen.gradient(n, 3, 0, 1, "f32")
+    g0[:8] = [np.inf, -np.inf, np.nan, 3e38, 1e-45, 0.0, -0.0, 1e-30]
+    g1[:8] = [1.0, 1.0, 1.0, 3e38, 1e-45, 0.0, -0.0, -1e-30]
+    g0[8:16] = [np.inf] * 8
+    g1[8:16] = [-np.inf] * 8                      # inf - inf
+    th = gen.master(n, 3)
+    m, v = gen.moments(n, 3, True)
+    th[16:24] = [0.0, -0.0, 1e-42, 3.3e38, -3.3e38, np.inf, 1.0, 1.0]
+    v[22] = 0.0; m[22] = 0.0; g0[22] = 0.0; g1[22] = 0.0       # 0/eps
+    v[23] = 1e-45                                               # subnormal second moment
+    state = [th, m, v, np.zeros(n, np.uint16)]
+    hpd, hp = hp_of(None, 2)
+    want = [a.copy() for a in state]
+    orc.step_f32([g0, g1], orc.derive_scalars(t=2, n_devices=N, **hpd), *want)
+    got = _run_gpu(spec, hp, state, [g0, g1], "f32", n)
+    assert_state_parity(got, want, "specials")
+    nan = np.isnan(want[0])
+    assert nan[:3].all() and nan[8:16].all()
+    assert ((got[3][nan] & 0x7fff) == 0x7fc0).all()             # canonical quiet NaN
+    assert np.array_equal(got[3][~nan], want[3][~nan])
+
+
+def test_run_twice_is_bitwise_identical():
+    n, N = 7 * TILE + 99, 8
+    _say("determinism n=%d" % n)
+    spec = ps.ps_spec_preset("zero3", N, 1, n * N)
+    grads = [gen.gradient(n, 13, 0, r, "bf16") for r in range(N)]
+    state = [gen.master(n, 13), *gen.moments(n, 13, True), np.zeros(n, np.uint16)]
+    _, hp = hp_of(None, 5)
+    a = _run_gpu(spec, hp, state, grads, "bf16", n)
+    b = _run_gpu(spec, hp, state, grads, "bf16", n)
+    for x, y in zip(a, b):
+        assert np.array_equal(x.view(np.uint8), y.view(np.uint8))
+
+
+# ---- sum of squares and the clipped two-phase step ----
+
+def _reduce_gpu(spec, grads_np, dtype, n, valid, gs=0.0, want_reduced=True, buckets=None):
+    gd = [dev(g) for g in grads_np]
+    red = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+    ss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ws = torch.empty(ps.ps_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    ranges = buckets or [(0, n)]
+    for k, (lo, cnt) in enumerate(ranges):
+        ps.ps_step_reduce_sumsq(spec, grads_of(gd, dtype, lo), gs,
+                                red.data_ptr() if want_reduced else 0, ss.data_ptr(), int(k > 0),
+                                ws.data_ptr(), ws.numel(), lo, cnt, valid, stream_handle())
+    torch.cuda.synchronize()
+    return host(red), float(ss.item())
+
+
+@pytest.mark.parametrize("dtype,N", [("f32", 6), ("bf16", 8), ("f32", 3), ("bf16", 4), ("f32", 16)])
+def test_reduce_sumsq_matches_oracle(dtype, N):
+    n = 9 * TILE + 777
+    valid = n - 1001
+    _say("reduce+sumsq n=%d valid=%d N=%d %s" % (n, valid, N, dtype))
+    spec = ps.ps_spec_preset("zero3", N, N - 1, n * N)
+    grads = [gen.gradient(n, 31, 0, r, dtype, std=1e-4, student_t_dof=3) for r in range(N)]
+    gm, ss = orc.mean_sumsq(grads, 1.0 / N, 0, valid)
+    red, ss_gpu = _reduce_gpu(spec, grads, dtype, n, valid)
+    assert np.array_equal(red[:valid].view(np.uint32), gm[:valid].view(np.uint32))   # bit-exact mean
+    assert np.isnan(red[valid:]).all()                                              # pad untouched
+    assert abs(ss_gpu - ss) <= 1e-12 * ss            # binary64 tree vs sequential binary64 sum
+    # reproducible bit for bit, with or without storing the mean
+    _, again = _reduce_gpu(spec, grads, dtype, n, valid, want_reduced=False)
+    assert again == ss_gpu
+    # the same total when the range arrives as buckets in order (accumulate flag)
+    b = 4 * TILE + 8
+    buckets = [(lo, min(b, n - lo)) for lo in range(0, n, b)]
+    red2, ss_b = _reduce_gpu(spec, grads, dtype, n, valid, buckets=buckets)
+    assert np.array_equal(red2[:valid].view(np.uint32), gm[:valid].view(np.uint32))
+    assert abs(ss_b - ss) <= 1e-12 * ss
+    assert _reduce_gpu(spec, grads, dtype, n, valid, buckets=buckets)[1] == ss_b
+
+
+def test_reduce_sumsq_degenerate_ranges():
+    n, N = 64, 4
+    _say("reduce+sumsq degenerate: tiny n, empty valid range, inf")
+    spec = ps.ps_spec_preset("zero3", N, 0, n * N)
+    grads = [gen.gradient(n, 1, 0, r, "f32") for r in range(N)]
+    _, ss = orc.mean_sumsq(grads, 1.0 / N)
+    assert abs(_reduce_gpu(spec, grads, "f32", n, n)[1] - ss) <= 1e-12 * ss
+    assert _reduce_gpu(spec, grads, "f32", n, 0)[1] == 0.0           # all padding
+    grads[1][5] = np.inf
+    assert np.isinf(_reduce_gpu(spec, grads, "f32", n, n)[1])         # caller sees it and may skip
+
+
+def test_clipped_two_phase_step_matches_oracle():
+    """Ragged fp32 shard with global-norm clipping: phase 1 reduces and sums squares,
+    the host forms the coefficient, phase 2 updates from the reduced gradient."""
+    w = WORKLOADS["13b_clip"]
+    N = w.n_devices
+    n = 11 * TILE + 1536 + 8
+    valid = n - 1001
+    _say("clip two-phase n=%d valid=%d N=%d" % (n, valid, N))
+    spec = ps.ps_spec_preset(w.strategy, N, N - 1, n * N - 1001, align_elems=8)
+    c = ps.ps_cost_eval(spec)
+    assert (c.shard_len, c.valid_len) == (n, valid)
+    grads = [gen.gradient(n, w.seed, 1, r, "f32", 1e-2, student_t_dof=3) for r in range(N)]
+    state = [gen.master(n, w.seed), *gen.moments(n, w.seed, True), np.full(n, 0xD00D, np.uint16)]
+    t = w.first_step
+    # oracle: unclipped norm -> coefficient -> step (clip applied after the mean)
+    _, ss = orc.mean_sumsq(grads, 1.0 / N, 0, valid)
+    coef = orc.clip_coef(ss, 5 * ss, w.max_grad_norm)
+    assert coef < 1.0
+    hpd, _ = hp_of(w, t)
+    want = [a.copy() for a in state]
+    orc.step_f32(grads, orc.derive_scalars(t=t, n_devices=N, clip_coef=coef, **hpd), *want, lo=0, hi=valid)
+    # GPU: phase 1
+    gd = [dev(g) for g in grads]
+    red = torch.zeros(n, dtype=torch.float32, device="cuda")
+    ssd = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ws = torch.empty(ps.ps_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    ps.ps_step_reduce_sumsq(spec, grads_of(gd, "f32"), 0.0, red.data_ptr(), ssd.data_ptr(), 0,
+                            ws.data_ptr(), ws.numel(), 0, n, valid, stream_handle())
+    ss_gpu = float(ssd.item())
+    assert abs(ss_gpu - ss) <= 1e-12 * ss
+    # phase 2 with the SAME coefficient as the oracle, so a last-bit difference in the
+    # sum cannot leak into the state comparison
+    _, hp = hp_of(w, t, grad_scale=1.0, clip_coef=coef)
+    th, m, v, p = [dev(a) for a in state]
+    ps.ps_step_update(spec, hp, shard_of(th, m, v, p, n, valid), grads_of([red], "f32"), 0, n,
+                      stream_handle())
+    torch.cuda.synchronize()
+    got = [host(x) for x in (th, m, v, p)]
+    assert assert_state_parity(got, want, "clip") == 0
+    for g, a in zip(got, state):
+        assert np.array_equal(g[valid:].view(np.uint8), a[valid:].view(np.uint8))
+    # the coefficient formed from the GPU's own sum is the same binary32 scalar here
+    assert np.float32(ps.ps_clip_coef(ss_gpu, 5 * ss_gpu, w.max_grad_norm)) == np.float32(coef)
+
+
+# ---- bucket pipeline ----
+
+def _bucketed(spec, hp, state, grads_np, dtype, n, valid, bucket, source_buckets, timed=False):
+    th, m, v, p = [dev(a) for a in state]
+    esz = 2 if dtype == "bf16" else 4
+    N = len(grads_np)
+    src = [dev(g) for g in grads_np]
+    staging = [torch.zeros(N * bucket * esz, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    copy, comp = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    plan = ps.ps_bucket_plan_t()
+    arr = (C.c_void_p * N)(*[s.data_ptr() for s in src])
+    plan.source = C.cast(arr, C.POINTER(C.c_void_p))
+    plan.n_contrib, plan.dtype = N, (ps.PS_BF16 if dtype == "bf16" else ps.PS_F32)
+    plan.bucket_elems, plan.source_buckets = bucket, source_buckets
+    plan.staging[0], plan.staging[1] = staging[0].data_ptr(), staging[1].data_ptr()
+    plan.copy_stream, plan.compute_stream = copy.cuda_stream, comp.cuda_stream
+    n_b = -(-n // bucket)
+    ms = (C.c_float * n_b)()
+    if timed:
+        plan.kernel_ms, plan.kernel_ms_len = ms, n_b
+    ps.ps_step_update_bucketed(spec, hp, shard_of(th, m, v, p, n, valid), plan)
+    torch.cuda.synchronize()
+    return [host(x) for x in (th, m, v, p)], list(ms)
+
+
+@pytest.mark.parametrize("timed", [False, True])
+def test_bucketed_step_matches_oracle(timed):
+    n, N, bucket = 9 * TILE + 520, 8, 2 * TILE + 8     # 5 buckets, the last one short
+    valid = n - 3
+    n_b = -(-n // bucket)
+    _say("bucketed n=%d bucket=%d (%d buckets) timed=%s" % (n, bucket, n_b, timed))
+    spec = ps.ps_spec_preset("zero3", N, 7, n * N)
+    # the source holds every bucket, padded to whole buckets
+    grads = [gen.gradient(n_b * bucket, 41, 0, r, "bf16", 1e-4) for r in range(N)]
+    state = [gen.master(n, 41), *gen.moments(n, 41, True), np.full(n, 0xABCD, np.uint16)]
+    hpd, hp = hp_of(None, 1000)
+    want = [a.copy() for a in state]
+    orc.step_f32([np.ascontiguousarray(g[:n]) for g in grads],
+                 orc.derive_scalars(t=1000, n_devices=N, **hpd), *want, lo=0, hi=valid)
+    got, ms = _bucketed(spec, hp, state, grads, "bf16", n, valid, bucket, n_b, timed)
+    assert assert_state_parity(got, want, "bucketed") == 0
+    for g, a in zip(got, state):
+        assert np.array_equal(g[valid:].view(np.uint8), a[valid:].view(np.uint8))
+    if timed:
+        assert all(x > 0 for x in ms)
+
+
+def test_bucketed_step_with_a_cycling_source_pool():
+    """source_buckets = 2: bucket b reads pool slot b % 2 (how the benchmark feeds 33 buckets)."""
+    n, N, bucket = 6 * TILE, 4, TILE
+    _say("bucketed with pool of 2, n=%d" % n)
+    spec = ps.ps_spec_preset("zero3", N, 0, n * N)
+    pool = [gen.gradient(2 * bucket, 43, 0, r, "f32", 1e-3) for r in range(N)]
+    tiled = [np.tile(g, n // (2 * bucket)) for g in pool]
+    state = [gen.master(n, 43), *gen.moments(n, 43, False), np.zeros(n, np.uint16)]
+    hpd, hp = hp_of(None, 1)
+    want = [a.copy() for a in state]
+    orc.step_f32(tiled, orc.derive_scalars(t=1, n_devices=N, **hpd), *want)
+    got, _ = _bucketed(spec, hp, state, pool, "f32", n, n, bucket, 2)
+    assert assert_state_parity(got, want, "pool") == 0

@@ -1,0 +1,166 @@
+"""Argument validation of the device entry points.  Every case here is rejected
+before the first HIP call, so fake (never dereferenced) addresses are safe and
+the results are the same with or without a GPU."""
+import ctypes as C
+
+import pytest
+import torch
+
+import paper_2601_02311_amd as ps
+
+FAKE = 0x10000  # 16-byte aligned, never dereferenced
+
+
+def _valid(n=1024, N=4, theta="zero3"):
+    spec = ps.ps_spec_preset(theta, N, 1, n * N)
+    hp = ps.ps_adamw_t(1e-4, 0.9, 0.999, 1e-8, 0.01, 1, 0.0, 0.0)
+    shard = ps.ps_shard_t(FAKE, FAKE * 2, FAKE * 3, FAKE * 4, n, n)
+    grads = ps.make_grads([FAKE * (5 + r) for r in range(N)], ps.PS_BF16)
+    return spec, hp, shard, grads
+
+
+def _status(fn):
+    with pytest.raises(ps.PsError) as e:
+        fn()
+    assert e.value.detail
+    return e.value.status
+
+
+def test_update_rejects_bad_arguments():
+    spec, hp, shard, grads = _valid()
+    upd = ps.ps_step_update
+    assert _status(lambda: upd(None, hp, shard, grads, 0, 8)) == ps.PS_EINVAL
+    assert _status(lambda: upd(spec, None, shard, grads, 0, 8)) == ps.PS_EINVAL
+    assert _status(lambda: upd(spec, hp, None, grads, 0, 8)) == ps.PS_EINVAL
+    assert _status(lambda: upd(spec, hp, shard, None, 0, 8)) == ps.PS_EINVAL
+    # placements this path does not execute
+    for name in ("dp", "zero1", "zero_offload", "tp"):
+        other = ps.ps_spec_preset(name, 4, 1, 4096)
+        assert _status(lambda: upd(other, hp, shard, grads, 0, 8)) == ps.PS_EUNSUPPORTED
+    # step count, betas
+    bad = ps.ps_adamw_t(1e-4, 0.9, 0.999, 1e-8, 0.01, 0, 0.0, 0.0)
+    assert _status(lambda: upd(spec, bad, shard, grads, 0, 8)) == ps.PS_ERANGE
+    bad = ps.ps_adamw_t(1e-4, 1.0, 0.999, 1e-8, 0.01, 1, 0.0, 0.0)
+    assert _status(lambda: upd(spec, bad, shard, grads, 0, 8)) == ps.PS_ERANGE
+    bad = ps.ps_adamw_t(float("nan"), 0.9, 0.999, 1e-8, 0.01, 1, 0.0, 0.0)
+    assert _status(lambda: upd(spec, bad, shard, grads, 0, 8)) == ps.PS_ERANGE
+    # shard buffers
+    s2 = ps.ps_shard_t(0, FAKE, FAKE, FAKE, 1024, 1024)
+    assert _status(lambda: upd(spec, hp, s2, grads, 0, 8)) == ps.PS_EINVAL
+    s2 = ps.ps_shard_t(FAKE + 4, FAKE, FAKE, FAKE, 1024, 1024)
+    assert _status(lambda: upd(spec, hp, s2, grads, 0, 8)) == ps.PS_EALIGN
+    s2 = ps.ps_shard_t(FAKE, FAKE, FAKE, FAKE, 1000, 1000)
+    assert _status(lambda: upd(spec, hp, s2, grads, 0, 8)) == ps.PS_ERANGE
+    s2 = ps.ps_shard_t(FAKE, FAKE, FAKE, FAKE, 1024, 1025)
+    assert _status(lambda: upd(spec, hp, s2, grads, 0, 8)) == ps.PS_ERANGE
+    # ranges
+    assert _status(lambda: upd(spec, hp, shard, grads, 4, 8)) == ps.PS_EALIGN
+    assert _status(lambda: upd(spec, hp, shard, grads, 1024, 8)) == ps.PS_ERANGE
+    assert _status(lambda: upd(spec, hp, shard, grads, 8, 1024)) == ps.PS_ERANGE
+    assert _status(lambda: upd(spec, hp, shard, grads, 2 ** 63, 2 ** 63)) == ps.PS_ERANGE
+
+
+def test_update_rejects_integrity_violations():
+    """A missing or surplus contribution, a NULL one, or mixed element types are
+    refused: they are the paper's gradient-integrity / type-mismatch violations."""
+    spec, hp, shard, _ = _valid()
+    upd = ps.ps_step_update
+    missing = ps.make_grads([FAKE] * 3, ps.PS_BF16)
+    assert _status(lambda: upd(spec, hp, shard, missing, 0, 8)) == ps.PS_EINVAL
+    extra = ps.make_grads([FAKE] * 5, ps.PS_BF16)
+    assert _status(lambda: upd(spec, hp, shard, extra, 0, 8)) == ps.PS_EINVAL
+    null = ps.make_grads([FAKE, 0, FAKE, FAKE], ps.PS_BF16)
+    assert _status(lambda: upd(spec, hp, shard, null, 0, 8)) == ps.PS_EINVAL
+    odd = ps.make_grads([FAKE, FAKE + 2, FAKE, FAKE], ps.PS_BF16)
+    assert _status(lambda: upd(spec, hp, shard, odd, 0, 8)) == ps.PS_EALIGN
+    badtype = ps.make_grads([FAKE] * 4, 2)
+    assert _status(lambda: upd(spec, hp, shard, badtype, 0, 8)) == ps.PS_EINVAL
+    one_bf16 = ps.make_grads([FAKE], ps.PS_BF16)       # a single pre-reduced gradient is fp32 only
+    assert _status(lambda: upd(spec, hp, shard, one_bf16, 0, 8)) == ps.PS_EINVAL
+    none = ps.make_grads([], ps.PS_BF16)
+    assert _status(lambda: upd(spec, hp, shard, none, 0, 8)) == ps.PS_ERANGE
+    spec17 = ps.ps_spec_preset("zero3", 17, 0, 17 * 1024)
+    many = ps.make_grads([FAKE] * 17, ps.PS_BF16)
+    assert _status(lambda: upd(spec17, hp, shard, many, 0, 8)) == ps.PS_ERANGE
+
+
+def test_zero2_output_offset_must_keep_alignment():
+    spec = ps.ps_spec_preset("zero2", 4, 1, 4 * 1028)     # shard offset 1028, not a multiple of 8
+    _, hp, _, grads = _valid()
+    shard = ps.ps_shard_t(FAKE, FAKE, FAKE, FAKE, 1028, 1028)
+    assert _status(lambda: ps.ps_step_update(spec, hp, shard, grads, 0, 8)) == ps.PS_EALIGN
+
+
+def test_empty_ranges_are_ok_without_a_device():
+    spec, hp, shard, grads = _valid()
+    ps.ps_step_update(spec, hp, shard, grads, 0, 0)
+    ps.ps_step_update(spec, hp, shard, grads, 1024, 0)
+    pad_only = ps.ps_shard_t(FAKE, FAKE, FAKE, FAKE, 1024, 512)
+    ps.ps_step_update(spec, hp, pad_only, grads, 512, 512)      # range lies entirely in the pad
+    ps.ps_probe_copy(FAKE, FAKE * 2, 0)
+
+
+def test_reduce_sumsq_rejects_bad_arguments():
+    spec, _, _, grads = _valid()
+    ws = ps.ps_workspace_bytes()
+    assert ws >= 8 * 4096
+    red = ps.ps_step_reduce_sumsq
+    ok = dict(spec=spec, grads=grads, grad_scale=0.0, reduced_out=FAKE, sumsq_out=FAKE,
+              accumulate=0, workspace=FAKE, workspace_bytes=ws, elem_offset=0, elem_count=8,
+              valid_len=1024)
+    assert _status(lambda: red(**dict(ok, spec=None))) == ps.PS_EINVAL
+    assert _status(lambda: red(**dict(ok, grads=None))) == ps.PS_EINVAL
+    assert _status(lambda: red(**dict(ok, sumsq_out=0))) == ps.PS_EINVAL
+    assert _status(lambda: red(**dict(ok, workspace=0))) == ps.PS_EINVAL
+    assert _status(lambda: red(**dict(ok, workspace_bytes=ws - 1))) == ps.PS_ERANGE
+    assert _status(lambda: red(**dict(ok, sumsq_out=FAKE + 4))) == ps.PS_EALIGN
+    assert _status(lambda: red(**dict(ok, reduced_out=FAKE + 8))) == ps.PS_EALIGN
+    assert _status(lambda: red(**dict(ok, elem_offset=4))) == ps.PS_EALIGN
+    assert _status(lambda: red(**dict(ok, elem_offset=1024, elem_count=8))) == ps.PS_ERANGE
+    assert _status(lambda: red(**dict(ok, valid_len=1025))) == ps.PS_ERANGE
+    assert _status(lambda: red(**dict(ok, grad_scale=float("nan")))) == ps.PS_ERANGE
+
+
+def test_bucketed_rejects_bad_arguments():
+    spec, hp, shard, _ = _valid()
+    src = (C.c_void_p * 4)(*[FAKE] * 4)
+
+    def plan(**kw):
+        p = ps.ps_bucket_plan_t()
+        p.source = C.cast(src, C.POINTER(C.c_void_p))
+        p.n_contrib, p.dtype, p.bucket_elems, p.source_buckets = 4, ps.PS_BF16, 256, 1
+        p.staging[0], p.staging[1] = FAKE * 2, FAKE * 3
+        p.copy_stream, p.compute_stream = 0x100, 0x200
+        for k, v in kw.items():
+            if k == "staging":
+                p.staging[0], p.staging[1] = v
+            else:
+                setattr(p, k, v)
+        return p
+    run = ps.ps_step_update_bucketed
+    assert _status(lambda: run(spec, hp, shard, None)) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, shard, plan(bucket_elems=0))) == ps.PS_EALIGN
+    assert _status(lambda: run(spec, hp, shard, plan(bucket_elems=100))) == ps.PS_EALIGN
+    assert _status(lambda: run(spec, hp, shard, plan(source_buckets=0))) == ps.PS_ERANGE
+    assert _status(lambda: run(spec, hp, shard, plan(staging=(FAKE, FAKE)))) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, shard, plan(staging=(FAKE, 0)))) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, shard, plan(compute_stream=0x100))) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, shard, plan(n_contrib=3))) == ps.PS_EINVAL
+    ms = (C.c_float * 2)()
+    assert _status(lambda: run(spec, hp, shard, plan(kernel_ms=ms, kernel_ms_len=2))) == ps.PS_ERANGE
+
+
+def test_copy_probe_validation():
+    assert _status(lambda: ps.ps_probe_copy(0, FAKE, 16)) == ps.PS_EINVAL
+    assert _status(lambda: ps.ps_probe_copy(FAKE, FAKE + 8, 16)) == ps.PS_EALIGN
+    assert _status(lambda: ps.ps_probe_copy(FAKE, FAKE, 24)) == ps.PS_EALIGN
+
+
+@pytest.mark.skipif(torch.cuda.device_count() > 0, reason="a device is present")
+def test_valid_calls_report_no_device():
+    spec, hp, shard, grads = _valid()
+    assert _status(lambda: ps.ps_step_update(spec, hp, shard, grads, 0, 1024)) == ps.PS_ENODEVICE
+    assert _status(lambda: ps.ps_device_info()) == ps.PS_ENODEVICE
+    assert _status(lambda: ps.ps_probe_copy(FAKE, FAKE * 2, 4096)) == ps.PS_ENODEVICE
+    assert _status(lambda: ps.ps_step_reduce_sumsq(
+        spec, grads, 0.0, FAKE, FAKE, 0, FAKE, ps.ps_workspace_bytes(), 0, 8, 1024)) == ps.PS_ENODEVICE
