@@ -7,6 +7,11 @@ shared library is missing and cannot be built, importing fails.
 import ctypes as C
 import os
 
+# The caller's device buffers and streams come from PyTorch, so the library must
+# bind to the HIP runtime instance PyTorch has loaded (same SONAME; whichever is
+# loaded first serves both).  Importing torch first guarantees that order.
+import torch  # noqa: F401
+
 from . import build as _build
 
 __all__ = [

@@ -247,10 +247,10 @@ def test_clipped_two_phase_step_matches_oracle():
     the host forms the coefficient, phase 2 updates from the reduced gradient."""
     w = WORKLOADS["13b_clip"]
     N = w.n_devices
-    n = 11 * TILE + 1536 + 8
+    n = 11 * TILE + 1536            # a multiple of 256, not of the tile
     valid = n - 1001
     _say("clip two-phase n=%d valid=%d N=%d" % (n, valid, N))
-    spec = ps.ps_spec_preset(w.strategy, N, N - 1, n * N - 1001, align_elems=8)
+    spec = ps.ps_spec_preset(w.strategy, N, N - 1, n * N - 1001, align_elems=w.align_elems)
     c = ps.ps_cost_eval(spec)
     assert (c.shard_len, c.valid_len) == (n, valid)
     grads = [gen.gradient(n, w.seed, 1, r, "f32", 1e-2, student_t_dof=3) for r in range(N)]
