@@ -124,7 +124,7 @@ def main():
         if clip:
             red = torch.empty(n, dtype=torch.float32, device="cuda")
             ssd = torch.zeros(1, dtype=torch.float64, device="cuda")
-            ws = torch.empty(ps.ps_workspace_bytes(), dtype=torch.uint8, device="cuda")
+            ws = torch.empty(ps.ps_workspace_bytes(n), dtype=torch.uint8, device="cuda")
             gred = ps.make_grads([red.data_ptr()], ps.PS_F32)
         rec = [0]
 

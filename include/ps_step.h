@@ -213,8 +213,9 @@ ps_status_t ps_step_update(const ps_spec_t *spec, const ps_adamw_t *hp,
 ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
                                     const ps_shard_t *shard, const ps_bucket_plan_t *plan);
 
-/* Bytes of DEVICE workspace ps_step_reduce_sumsq needs. */
-uint64_t ps_workspace_bytes(void);
+/* Bytes of DEVICE workspace ps_step_reduce_sumsq needs for a call over
+ * elem_count elements (about elem_count / 128 bytes; host-only query). */
+uint64_t ps_workspace_bytes(uint64_t elem_count);
 
 /* First phase of a step with global-norm clipping: reduce the contributions
  * for [elem_offset, elem_offset + elem_count), form the mean g = acc *

@@ -129,6 +129,7 @@ def library():
                                               C.POINTER(ps_shard_t),
                                               C.POINTER(ps_bucket_plan_t)]
         L.ps_workspace_bytes.restype = C.c_uint64
+        L.ps_workspace_bytes.argtypes = [C.c_uint64]
         L.ps_step_reduce_sumsq.restype = C.c_int
         L.ps_step_reduce_sumsq.argtypes = [C.POINTER(ps_spec_t), C.POINTER(ps_grads_t),
                                            C.c_double, C.c_void_p, C.c_void_p, C.c_int32,
@@ -211,8 +212,8 @@ def ps_step_update_bucketed(spec, hp, shard, plan):
     _check(library().ps_step_update_bucketed(_ref(spec), _ref(hp), _ref(shard), _ref(plan)))
 
 
-def ps_workspace_bytes():
-    return library().ps_workspace_bytes()
+def ps_workspace_bytes(elem_count):
+    return library().ps_workspace_bytes(elem_count)
 
 
 def ps_step_reduce_sumsq(spec, grads, grad_scale, reduced_out, sumsq_out, accumulate,

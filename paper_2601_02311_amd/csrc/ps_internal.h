@@ -31,9 +31,10 @@ struct ContribPtrs {
     const void *p[PS_MAX_CONTRIB];
 };
 
-// Number of per-block partial sums the sum-of-squares pass may produce.  A
-// fixed constant, so that the reduction tree never depends on the device.
-constexpr uint32_t kSumsqMaxBlocks = 4096;
+// Doubles of workspace the sum-of-squares pass needs for `count` elements: one
+// partial per workgroup of the reduce kernel plus a fixed second level.  A pure
+// function of the count, so that the reduction tree never depends on the device.
+uint64_t reduce_workspace_doubles(uint64_t count);
 
 // Launchers, defined in ps_kernels.hip.  All pointers are DEVICE pointers that
 // already point at the first element to process; `count` elements follow.

@@ -3,22 +3,30 @@
 // The step is a pure stream: per element it reads N gradient contributions and
 // three FP32 state words, and writes three FP32 state words and one bf16
 // parameter, each byte exactly once.  There is no reuse and no contraction, so
-// nothing here uses LDS (except the sum-of-squares tree) or MFMA; the design
-// goal is to keep as many fully coalesced 128-bit (state) and 64-bit (bf16)
-// accesses in flight per CU as registers allow.
+// nothing here uses MFMA, and LDS only serves the sum-of-squares tree.  What
+// decides the speed is how the request stream looks to the HBM controllers.
+// Measured on MI355X, in this order of importance:
+//   - one wavefront per workgroup, one 256-element tile per workgroup, and a
+//     grid with one workgroup per tile: the dispatcher hands tiles out in
+//     address order, so the whole device sweeps each of the 12-15 streams as
+//     one narrow moving window (persistent grid-stride grids lose ~10 %);
+//   - only about eight such waves resident per CU (the launch asks for dynamic
+//     LDS it never touches, purely to cap residency): more waves in flight
+//     widen the window and cost another ~8 %;
+//   - the non-temporal hint on every load and store (nothing is reused);
+//   - every wave-level access one contiguous 1 KiB (FP32, 16 B per lane) or
+//     512 B (bf16, 8 B per lane) span, so each store instruction fills whole
+//     128-byte lines by itself.
 //
-// Work decomposition.  A *tile* is kThreads * 4 * U consecutive elements.
-// Inside a tile, sub-tile u covers elements [u*1024, (u+1)*1024) and lane t of
-// the block owns elements 4t..4t+3 of each sub-tile, so every wave-level
-// instruction touches one contiguous 1 KiB (FP32) or 512 B (bf16) span.  All
-// loads of a tile are issued before the first arithmetic instruction.  Blocks
-// walk the tiles grid-stride.  Elements past the last whole tile are handled
-// by a bounds-checked one-element-per-lane kernel.
+// Work decomposition.  A tile is 256 consecutive elements; lane t owns
+// elements 4t..4t+3.  All loads of a tile are issued before the first
+// arithmetic instruction.  Elements past the last whole tile are handled by a
+// bounds-checked one-element-per-lane kernel.
 //
 // Arithmetic.  Every line of step_element() is one correctly rounded binary32
 // operation (the translation unit is compiled with contraction off and with
-// IEEE division and square root), so results do not depend on tile shape,
-// grid size or which kernel (tile or tail) handles an element.
+// IEEE division and square root), so results do not depend on launch shape or
+// on which kernel (tile or tail) handles an element.
 #ifndef PS_KERNEL_TEMPLATES_H
 #define PS_KERNEL_TEMPLATES_H
 
@@ -29,7 +37,9 @@
 
 namespace ps {
 
-constexpr int kThreads = 256;
+constexpr int kWave = 64;               // threads per workgroup of the streaming kernels
+constexpr int kTileElems = kWave * 4;    // elements per tile
+constexpr int kThreads = 256;            // threads per workgroup of the small helper kernels
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -138,76 +148,54 @@ struct UpdateArgs {
     StepScalars s;
 };
 
-// Fused reduce + AdamW + bf16 cast over whole tiles.
-//   N  : contribution count known at compile time, 0 = read it from args
-//   G  : uint16_t (bf16 bits) or float
-//   U  : sub-tiles per tile
-//   NTL/NTS : non-temporal hint on loads / stores
-template <int N, typename G, int U, bool NTL, bool NTS>
-__global__ __launch_bounds__(kThreads) void update_tiles(const UpdateArgs a)
+// Fused reduce + AdamW + bf16 cast over whole tiles, one wave per tile.
+//   N : contribution count known at compile time, 0 = read it from args
+//   G : uint16_t (bf16 bits) or float
+// The loop only repeats when there are more tiles than the grid can hold.
+template <int N, typename G>
+__global__ __launch_bounds__(kWave) void update_tiles(const UpdateArgs a)
 {
-    constexpr uint64_t kTile = (uint64_t)kThreads * 4 * U;
     const uint32_t n = N ? N : a.n_contrib;
     for (uint64_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
-        const uint64_t e0 = tile * kTile + (uint64_t)threadIdx.x * 4;
-        f32x4 acc[U], th[U], mm[U], vv[U];
+        const uint64_t e = tile * kTileElems + (uint64_t)threadIdx.x * 4;
+        f32x4 acc, th, mm, vv;
         if constexpr (N != 0) {
-            f32x4 gr[N][U];
+            f32x4 gr[N];
 #pragma unroll
             for (int r = 0; r < N; ++r)
+                gr[r] = load_contrib4<G, true>(a.g.p[r], e);
+            th = load_vec<true>(reinterpret_cast<const f32x4 *>(a.master + e));
+            mm = load_vec<true>(reinterpret_cast<const f32x4 *>(a.m + e));
+            vv = load_vec<true>(reinterpret_cast<const f32x4 *>(a.v + e));
+            acc = gr[0];
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    gr[r][u] = load_contrib4<G, NTL>(a.g.p[r], e0 + (uint64_t)u * kThreads * 4);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint64_t e = e0 + (uint64_t)u * kThreads * 4;
-                th[u] = load_vec<NTL>(reinterpret_cast<const f32x4 *>(a.master + e));
-                mm[u] = load_vec<NTL>(reinterpret_cast<const f32x4 *>(a.m + e));
-                vv[u] = load_vec<NTL>(reinterpret_cast<const f32x4 *>(a.v + e));
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                acc[u] = gr[0][u];
-#pragma unroll
-                for (int r = 1; r < N; ++r)
-                    acc[u] = acc[u] + gr[r][u];
-            }
+            for (int r = 1; r < N; ++r)
+                acc = acc + gr[r];
         } else {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint64_t e = e0 + (uint64_t)u * kThreads * 4;
-                th[u] = load_vec<NTL>(reinterpret_cast<const f32x4 *>(a.master + e));
-                mm[u] = load_vec<NTL>(reinterpret_cast<const f32x4 *>(a.m + e));
-                vv[u] = load_vec<NTL>(reinterpret_cast<const f32x4 *>(a.v + e));
-                acc[u] = load_contrib4<G, NTL>(a.g.p[0], e);
-            }
+            th = load_vec<true>(reinterpret_cast<const f32x4 *>(a.master + e));
+            mm = load_vec<true>(reinterpret_cast<const f32x4 *>(a.m + e));
+            vv = load_vec<true>(reinterpret_cast<const f32x4 *>(a.v + e));
+            acc = load_contrib4<G, true>(a.g.p[0], e);
             for (uint32_t r = 1; r < n; ++r)
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    acc[u] = acc[u] +
-                             load_contrib4<G, NTL>(a.g.p[r], e0 + (uint64_t)u * kThreads * 4);
+                acc = acc + load_contrib4<G, true>(a.g.p[r], e);
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint64_t e = e0 + (uint64_t)u * kThreads * 4;
-            step_element4(acc[u], th[u], mm[u], vv[u], a.s);
-            u32x2 pk;
-            pk.x = narrow_bf16(th[u].x) | (narrow_bf16(th[u].y) << 16);
-            pk.y = narrow_bf16(th[u].z) | (narrow_bf16(th[u].w) << 16);
-            store_vec<NTS>(reinterpret_cast<f32x4 *>(a.master + e), th[u]);
-            store_vec<NTS>(reinterpret_cast<f32x4 *>(a.m + e), mm[u]);
-            store_vec<NTS>(reinterpret_cast<f32x4 *>(a.v + e), vv[u]);
-            store_vec<NTS>(reinterpret_cast<u32x2 *>(a.out + e), pk);
-        }
+        step_element4(acc, th, mm, vv, a.s);
+        u32x2 pk;
+        pk.x = narrow_bf16(th.x) | (narrow_bf16(th.y) << 16);
+        pk.y = narrow_bf16(th.z) | (narrow_bf16(th.w) << 16);
+        store_vec<true>(reinterpret_cast<f32x4 *>(a.master + e), th);
+        store_vec<true>(reinterpret_cast<f32x4 *>(a.m + e), mm);
+        store_vec<true>(reinterpret_cast<f32x4 *>(a.v + e), vv);
+        store_vec<true>(reinterpret_cast<u32x2 *>(a.out + e), pk);
     }
 }
 
 // Same update, one element per lane with a bounds check; a.n_tiles is the
 // element count here.  Used for what is left after the last whole tile.
 template <typename G>
-__global__ __launch_bounds__(kThreads) void update_tail(const UpdateArgs a)
+__global__ __launch_bounds__(kWave) void update_tail(const UpdateArgs a)
 {
-    const uint64_t e = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    const uint64_t e = (uint64_t)blockIdx.x * kWave + threadIdx.x;
     if (e >= a.n_tiles)
         return;
     float acc = load_contrib1<G>(a.g.p[0], e);
@@ -223,24 +211,34 @@ __global__ __launch_bounds__(kThreads) void update_tail(const UpdateArgs a)
 
 // ---- sum of squares: the only place that needs cross-lane traffic ----
 
-// Fixed-shape tree: butterfly inside the wave, then the four wave sums through
-// LDS, added in wave order.  Every lane must call it.
-__device__ __forceinline__ double block_sum(double x)
+// Butterfly over the 64 lanes; every lane ends with the same bits.
+__device__ __forceinline__ double wave_sum(double x)
 {
-    __shared__ double wave_sum[kThreads / 64];
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1)
         x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+// Fixed-shape tree for a kThreads-wide workgroup: butterfly inside each wave,
+// then the wave sums through LDS, added in wave order.  Every lane must call it.
+__device__ __forceinline__ double block_sum(double x)
+{
+    __shared__ double partial[kThreads / 64];
+    x = wave_sum(x);
     if ((threadIdx.x & 63) == 0)
-        wave_sum[threadIdx.x >> 6] = x;
+        partial[threadIdx.x >> 6] = x;
     __syncthreads();
-    double t = wave_sum[0];
+    double t = partial[0];
 #pragma unroll
     for (int w = 1; w < kThreads / 64; ++w)
-        t += wave_sum[w];
+        t += partial[w];
     __syncthreads();
     return t;
 }
+
+// Tiles each workgroup of the reduce pass walks, one after the other.
+constexpr uint32_t kReduceTilesPerGroup = 4;
 
 struct ReduceArgs {
     ContribPtrs g;
@@ -253,63 +251,51 @@ struct ReduceArgs {
 };
 
 // Reduce the contributions, scale to the mean, optionally store it, and leave
-// one binary64 partial sum of squares per block in partials[blockIdx.x].
-template <int N, typename G, int U, bool NTL, bool NTS>
-__global__ __launch_bounds__(kThreads) void reduce_sumsq_tiles(const ReduceArgs a)
+// one binary64 partial sum of squares per workgroup in partials[blockIdx.x].
+// Workgroup b owns tiles [4b, 4b+4); the grid covers all tiles.
+template <int N, typename G>
+__global__ __launch_bounds__(kWave) void reduce_sumsq_tiles(const ReduceArgs a)
 {
-    constexpr uint64_t kTile = (uint64_t)kThreads * 4 * U;
     const uint32_t n = N ? N : a.n_contrib;
     double ss = 0.0;
-    for (uint64_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
-        const uint64_t e0 = tile * kTile + (uint64_t)threadIdx.x * 4;
-        f32x4 acc[U];
+    const uint64_t t0 = (uint64_t)blockIdx.x * kReduceTilesPerGroup;
+    const uint64_t t1 = t0 + kReduceTilesPerGroup < a.n_tiles ? t0 + kReduceTilesPerGroup : a.n_tiles;
+    for (uint64_t tile = t0; tile < t1; ++tile) {
+        const uint64_t e = tile * kTileElems + (uint64_t)threadIdx.x * 4;
+        f32x4 acc;
         if constexpr (N != 0) {
-            f32x4 gr[N][U];
+            f32x4 gr[N];
 #pragma unroll
             for (int r = 0; r < N; ++r)
+                gr[r] = load_contrib4<G, true>(a.g.p[r], e);
+            acc = gr[0];
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    gr[r][u] = load_contrib4<G, NTL>(a.g.p[r], e0 + (uint64_t)u * kThreads * 4);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                acc[u] = gr[0][u];
-#pragma unroll
-                for (int r = 1; r < N; ++r)
-                    acc[u] = acc[u] + gr[r][u];
-            }
+            for (int r = 1; r < N; ++r)
+                acc = acc + gr[r];
         } else {
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                acc[u] = load_contrib4<G, NTL>(a.g.p[0], e0 + (uint64_t)u * kThreads * 4);
+            acc = load_contrib4<G, true>(a.g.p[0], e);
             for (uint32_t r = 1; r < n; ++r)
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    acc[u] = acc[u] +
-                             load_contrib4<G, NTL>(a.g.p[r], e0 + (uint64_t)u * kThreads * 4);
+                acc = acc + load_contrib4<G, true>(a.g.p[r], e);
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            f32x4 g = acc[u] * a.gs;
-            ss += (double)g.x * (double)g.x;
-            ss += (double)g.y * (double)g.y;
-            ss += (double)g.z * (double)g.z;
-            ss += (double)g.w * (double)g.w;
-            if (a.reduced)
-                store_vec<NTS>(
-                    reinterpret_cast<f32x4 *>(a.reduced + e0 + (uint64_t)u * kThreads * 4), g);
-        }
+        const f32x4 g = acc * a.gs;
+        ss += (double)g.x * (double)g.x;
+        ss += (double)g.y * (double)g.y;
+        ss += (double)g.z * (double)g.z;
+        ss += (double)g.w * (double)g.w;
+        if (a.reduced)
+            store_vec<true>(reinterpret_cast<f32x4 *>(a.reduced + e), g);
     }
-    const double t = block_sum(ss);
+    const double t = wave_sum(ss);
     if (threadIdx.x == 0)
         a.partials[blockIdx.x] = t;
 }
 
-// Tail: a single block strides over the leftover elements (fewer than one tile).
+// Tail: a single wave strides over the leftover elements (fewer than one tile).
 template <typename G>
-__global__ __launch_bounds__(kThreads) void reduce_sumsq_tail(const ReduceArgs a)
+__global__ __launch_bounds__(kWave) void reduce_sumsq_tail(const ReduceArgs a)
 {
     double ss = 0.0;
-    for (uint64_t e = threadIdx.x; e < a.n_tiles; e += kThreads) {
+    for (uint64_t e = threadIdx.x; e < a.n_tiles; e += kWave) {
         float acc = load_contrib1<G>(a.g.p[0], e);
         for (uint32_t r = 1; r < a.n_contrib; ++r)
             acc = acc + load_contrib1<G>(a.g.p[r], e);
@@ -318,13 +304,28 @@ __global__ __launch_bounds__(kThreads) void reduce_sumsq_tail(const ReduceArgs a
         if (a.reduced)
             a.reduced[e] = g;
     }
-    const double t = block_sum(ss);
+    const double t = wave_sum(ss);
     if (threadIdx.x == 0)
         a.partials[a.partial_slot] = t;
 }
 
-// Sum partials[0 .. n) in a fixed order (lane-strided, then the block tree) and
-// store the total, or add it to what *out already holds.
+// First stage of the final sum: workgroup b adds the contiguous slice
+// [b*per, min((b+1)*per, n)) of `in` in a fixed order into out[b].
+__global__ __launch_bounds__(kThreads) void fold_partials(const double *in, uint64_t n,
+                                                          uint64_t per, double *out)
+{
+    const uint64_t lo = (uint64_t)blockIdx.x * per;
+    const uint64_t hi = lo + per < n ? lo + per : n;
+    double ss = 0.0;
+    for (uint64_t i = lo + threadIdx.x; i < hi; i += kThreads)
+        ss += in[i];
+    const double t = block_sum(ss);
+    if (threadIdx.x == 0)
+        out[blockIdx.x] = t;
+}
+
+// Last stage: sum partials[0 .. n) in a fixed order (lane-strided, then the
+// block tree) and store the total, or add it to what *out already holds.
 __global__ __launch_bounds__(kThreads) void finalize_sumsq(const double *partials, uint32_t n,
                                                           double *out, int accumulate)
 {
@@ -336,25 +337,17 @@ __global__ __launch_bounds__(kThreads) void finalize_sumsq(const double *partial
         *out = accumulate ? *out + t : t;
 }
 
-// Plain copy with the update kernel's access shape (16 B per lane, grid-stride
-// over 4 KiB * U tiles); bytes beyond the last whole tile go 16 B per lane.
-template <int U, bool NTL, bool NTS>
-__global__ __launch_bounds__(kThreads) void copy_tiles(u32x4 *dst, const u32x4 *src,
-                                                       uint64_t n_tiles, uint64_t n_vec)
+// Plain copy with the update kernel's access shape: one wave per 1 KiB, 16 B
+// per lane; what is left beyond whole KiB goes 16 B per lane in group 0.
+__global__ __launch_bounds__(kWave) void copy_tiles(u32x4 *dst, const u32x4 *src,
+                                                    uint64_t n_tiles, uint64_t n_vec)
 {
-    constexpr uint64_t kTileVec = (uint64_t)kThreads * U;
     for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const uint64_t i0 = tile * kTileVec + threadIdx.x;
-        u32x4 x[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            x[u] = load_vec<NTL>(src + i0 + (uint64_t)u * kThreads);
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            store_vec<NTS>(dst + i0 + (uint64_t)u * kThreads, x[u]);
+        const uint64_t i = tile * kWave + threadIdx.x;
+        store_vec<true>(dst + i, load_vec<true>(src + i));
     }
     if (blockIdx.x == 0)
-        for (uint64_t i = n_tiles * kTileVec + threadIdx.x; i < n_vec; i += kThreads)
+        for (uint64_t i = n_tiles * kWave + threadIdx.x; i < n_vec; i += kWave)
             dst[i] = src[i];
 }
 

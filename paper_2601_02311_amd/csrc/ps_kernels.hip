@@ -5,16 +5,20 @@
 
 namespace ps {
 
-// Tuned on MI355X (256 CUs): see the launch-shape notes next to each constant.
-constexpr int kU = 2;              // sub-tiles per tile -> 2048 elements per tile
-constexpr bool kNTL = false;       // non-temporal hint on loads
-constexpr bool kNTS = false;       // non-temporal hint on stores
-constexpr uint32_t kMaxBlocks = 256 * 8; // grid-stride cap: 8 blocks per CU
-constexpr uint64_t kTileElems = (uint64_t)kThreads * 4 * kU;
+// Dynamic LDS requested by the streaming launches.  The kernels never touch it:
+// with 160 KiB of LDS per CU it holds residency at 8 single-wave workgroups per
+// CU (4 for the reduce pass, whose groups walk four tiles each), which is where
+// the HBM request stream stays narrow enough to run at ~6.6 TB/s on MI355X.
+constexpr uint32_t kUpdateLdsBytes = 20480;
+constexpr uint32_t kReduceLdsBytes = 40960;
+// Largest grid used; beyond it the kernels loop (never reached below 5e11 elements).
+constexpr uint64_t kMaxGrid = 0x7fffffffull;
+// Second level of the sum-of-squares tree.
+constexpr uint32_t kFoldBlocks = 1024;
 
-static uint32_t grid_for(uint64_t n_tiles, uint32_t cap)
+static uint32_t grid_for(uint64_t n)
 {
-    return (uint32_t)(n_tiles < cap ? n_tiles : cap);
+    return (uint32_t)(n < kMaxGrid ? n : kMaxGrid);
 }
 
 template <typename G>
@@ -26,7 +30,7 @@ static const void *advance(const void *p, uint64_t elems)
 template <int N, typename G>
 static void launch_update_n(const UpdateArgs &a, uint32_t grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((update_tiles<N, G, kU, kNTL, kNTS>), dim3(grid), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((update_tiles<N, G>), dim3(grid), dim3(kWave), kUpdateLdsBytes, st, a);
 }
 
 template <typename G>
@@ -46,7 +50,7 @@ static int launch_update_t(uint32_t n_contrib, const ContribPtrs &g, float *mast
     a.s = s;
     if (n_tiles) {
         a.n_tiles = n_tiles;
-        const uint32_t grid = grid_for(n_tiles, kMaxBlocks);
+        const uint32_t grid = grid_for(n_tiles);
         switch (n_contrib) {
         case 1: launch_update_n<1, G>(a, grid, st); break;
         case 2: launch_update_n<2, G>(a, grid, st); break;
@@ -68,8 +72,8 @@ static int launch_update_t(uint32_t n_contrib, const ContribPtrs &g, float *mast
         a.v = v + body;
         a.out = out + body;
         a.n_tiles = rest;
-        const uint32_t grid = (uint32_t)((rest + kThreads - 1) / kThreads);
-        hipLaunchKernelGGL((update_tail<G>), dim3(grid), dim3(kThreads), 0, st, a);
+        const uint32_t grid = (uint32_t)((rest + kWave - 1) / kWave);
+        hipLaunchKernelGGL((update_tail<G>), dim3(grid), dim3(kWave), 0, st, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return (int)e;
@@ -86,32 +90,46 @@ int launch_update(int dtype, uint32_t n_contrib, const ContribPtrs &g, float *ma
     return launch_update_t<float>(n_contrib, g, master, m, v, out, count, s, st);
 }
 
+static uint64_t reduce_groups(uint64_t count)
+{
+    const uint64_t n_tiles = count / kTileElems;
+    return (n_tiles + kReduceTilesPerGroup - 1) / kReduceTilesPerGroup;
+}
+
+uint64_t reduce_workspace_doubles(uint64_t count)
+{
+    return kFoldBlocks + reduce_groups(count) + 1; // second level, groups, tail
+}
+
 template <int N, typename G>
 static void launch_reduce_n(const ReduceArgs &a, uint32_t grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((reduce_sumsq_tiles<N, G, kU, kNTL, kNTS>), dim3(grid), dim3(kThreads), 0,
-                       st, a);
+    hipLaunchKernelGGL((reduce_sumsq_tiles<N, G>), dim3(grid), dim3(kWave), kReduceLdsBytes, st, a);
 }
 
 template <typename G>
 static int launch_reduce_t(uint32_t n_contrib, const ContribPtrs &g, float gs, float *reduced,
-                           uint64_t count, double *partials, double *sumsq_out, int accumulate,
+                           uint64_t count, double *workspace, double *sumsq_out, int accumulate,
                            hipStream_t st)
 {
     const uint64_t n_tiles = count / kTileElems;
     const uint64_t body = n_tiles * kTileElems;
-    // one block fewer than the partials array holds: the tail owns the last slot
-    const uint32_t grid = grid_for(n_tiles, kSumsqMaxBlocks - 1);
-    uint32_t n_partials = 0;
+    const uint64_t groups = reduce_groups(count);
+    if (groups > kMaxGrid)
+        return (int)hipErrorInvalidConfiguration;
+    double *level2 = workspace;
+    double *level1 = workspace + kFoldBlocks;
+    uint64_t n_partials = 0;
     ReduceArgs a;
     a.g = g;
     a.reduced = reduced;
-    a.partials = partials;
+    a.partials = level1;
     a.n_contrib = n_contrib;
     a.partial_slot = 0;
     a.gs = gs;
     if (n_tiles) {
         a.n_tiles = n_tiles;
+        const uint32_t grid = (uint32_t)groups;
         switch (n_contrib) {
         case 1: launch_reduce_n<1, G>(a, grid, st); break;
         case 2: launch_reduce_n<2, G>(a, grid, st); break;
@@ -123,22 +141,36 @@ static int launch_reduce_t(uint32_t n_contrib, const ContribPtrs &g, float gs, f
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return (int)e;
-        n_partials = grid;
+        n_partials = groups;
     }
     if (count > body) {
         for (uint32_t r = 0; r < n_contrib; ++r)
             a.g.p[r] = advance<G>(g.p[r], body);
         a.reduced = reduced ? reduced + body : nullptr;
         a.n_tiles = count - body;
-        a.partial_slot = n_partials;
-        hipLaunchKernelGGL((reduce_sumsq_tail<G>), dim3(1), dim3(kThreads), 0, st, a);
+        a.partial_slot = (uint32_t)n_partials;
+        hipLaunchKernelGGL((reduce_sumsq_tail<G>), dim3(1), dim3(kWave), 0, st, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return (int)e;
         n_partials += 1;
     }
-    hipLaunchKernelGGL(finalize_sumsq, dim3(1), dim3(kThreads), 0, st, partials, n_partials,
-                       sumsq_out, accumulate);
+    // Fold the first level into at most kFoldBlocks sums, then into one.
+    const double *last = level1;
+    uint32_t n_last = (uint32_t)n_partials;
+    if (n_partials > kFoldBlocks) {
+        const uint64_t per = (n_partials + kFoldBlocks - 1) / kFoldBlocks;
+        const uint32_t blocks = (uint32_t)((n_partials + per - 1) / per);
+        hipLaunchKernelGGL(fold_partials, dim3(blocks), dim3(kThreads), 0, st, level1, n_partials,
+                           per, level2);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return (int)e;
+        last = level2;
+        n_last = blocks;
+    }
+    hipLaunchKernelGGL(finalize_sumsq, dim3(1), dim3(kThreads), 0, st, last, n_last, sumsq_out,
+                       accumulate);
     return (int)hipGetLastError();
 }
 
@@ -158,11 +190,12 @@ int launch_copy(void *dst, const void *src, uint64_t bytes, void *stream)
 {
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const uint64_t n_vec = bytes / 16;
-    const uint64_t n_tiles = n_vec / ((uint64_t)kThreads * kU * 2);
-    uint32_t grid = grid_for(n_tiles, kMaxBlocks);
+    const uint64_t n_tiles = n_vec / kWave;
+    uint32_t grid = grid_for(n_tiles);
     if (grid == 0)
         grid = 1;
-    hipLaunchKernelGGL((copy_tiles<kU * 2, kNTL, kNTS>), dim3(grid), dim3(kThreads), 0, st,
+    // one 16-B access per lane in flight: leave residency uncapped
+    hipLaunchKernelGGL(copy_tiles, dim3(grid), dim3(kWave), 0, st,
                        reinterpret_cast<u32x4 *>(dst), reinterpret_cast<const u32x4 *>(src),
                        n_tiles, n_vec);
     return (int)hipGetLastError();

@@ -269,7 +269,10 @@ ps_status_t ps_step_update(const ps_spec_t *spec, const ps_adamw_t *hp, const ps
     return PS_OK;
 }
 
-uint64_t ps_workspace_bytes(void) { return (uint64_t)kSumsqMaxBlocks * sizeof(double); }
+uint64_t ps_workspace_bytes(uint64_t elem_count)
+{
+    return reduce_workspace_doubles(elem_count) * sizeof(double);
+}
 
 ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
                                  double grad_scale, float *reduced_out, double *sumsq_out,
@@ -289,9 +292,10 @@ ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
         set_error("grad_scale is NaN");
         return PS_ERANGE;
     }
-    if (workspace_bytes < ps_workspace_bytes()) {
-        set_error("workspace of %llu bytes is smaller than ps_workspace_bytes()",
-                  (unsigned long long)workspace_bytes);
+    if (workspace_bytes < ps_workspace_bytes(elem_count)) {
+        set_error("workspace of %llu bytes is smaller than ps_workspace_bytes(%llu) = %llu",
+                  (unsigned long long)workspace_bytes, (unsigned long long)elem_count,
+                  (unsigned long long)ps_workspace_bytes(elem_count));
         return PS_ERANGE;
     }
     if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(sumsq_out) & 7u) ||

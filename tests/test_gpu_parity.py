@@ -18,7 +18,7 @@ from gpu_util import (assert_state_parity, dev, grads_of, host, hp_of, shard_of,
 
 pytestmark = pytest.mark.gpu
 
-TILE = 2048  # elements per tile of the update kernel (256 lanes x 4 x 2)
+TILE = 2048  # eight of the update kernel's 256-element tiles (one wave x 4 elements per lane)
 
 
 def _say(msg):
@@ -196,7 +196,7 @@ def _reduce_gpu(spec, grads_np, dtype, n, valid, gs=0.0, want_reduced=True, buck
     gd = [dev(g) for g in grads_np]
     red = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
     ss = torch.zeros(1, dtype=torch.float64, device="cuda")
-    ws = torch.empty(ps.ps_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(ps.ps_workspace_bytes(n), dtype=torch.uint8, device="cuda")
     ranges = buckets or [(0, n)]
     for k, (lo, cnt) in enumerate(ranges):
         ps.ps_step_reduce_sumsq(spec, grads_of(gd, dtype, lo), gs,
@@ -206,9 +206,11 @@ def _reduce_gpu(spec, grads_np, dtype, n, valid, gs=0.0, want_reduced=True, buck
     return host(red), float(ss.item())
 
 
-@pytest.mark.parametrize("dtype,N", [("f32", 6), ("bf16", 8), ("f32", 3), ("bf16", 4), ("f32", 16)])
-def test_reduce_sumsq_matches_oracle(dtype, N):
-    n = 9 * TILE + 777
+@pytest.mark.parametrize("dtype,N,n", [("f32", 6, 9 * TILE + 777), ("bf16", 8, 9 * TILE + 777),
+                                       ("f32", 3, 9 * TILE + 777), ("bf16", 4, 9 * TILE + 777),
+                                       ("f32", 16, 9 * TILE + 777),
+                                       ("f32", 6, 1500 * TILE + 1255)])   # two-level final sum
+def test_reduce_sumsq_matches_oracle(dtype, N, n):
     valid = n - 1001
     _say("reduce+sumsq n=%d valid=%d N=%d %s" % (n, valid, N, dtype))
     spec = ps.ps_spec_preset("zero3", N, N - 1, n * N)
@@ -222,7 +224,7 @@ def test_reduce_sumsq_matches_oracle(dtype, N):
     _, again = _reduce_gpu(spec, grads, dtype, n, valid, want_reduced=False)
     assert again == ss_gpu
     # the same total when the range arrives as buckets in order (accumulate flag)
-    b = 4 * TILE + 8
+    b = (n // 5) // 8 * 8 + 8
     buckets = [(lo, min(b, n - lo)) for lo in range(0, n, b)]
     red2, ss_b = _reduce_gpu(spec, grads, dtype, n, valid, buckets=buckets)
     assert np.array_equal(red2[:valid].view(np.uint32), gm[:valid].view(np.uint32))
@@ -267,7 +269,7 @@ def test_clipped_two_phase_step_matches_oracle():
     gd = [dev(g) for g in grads]
     red = torch.zeros(n, dtype=torch.float32, device="cuda")
     ssd = torch.zeros(1, dtype=torch.float64, device="cuda")
-    ws = torch.empty(ps.ps_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(ps.ps_workspace_bytes(n), dtype=torch.uint8, device="cuda")
     ps.ps_step_reduce_sumsq(spec, grads_of(gd, "f32"), 0.0, red.data_ptr(), ssd.data_ptr(), 0,
                             ws.data_ptr(), ws.numel(), 0, n, valid, stream_handle())
     ss_gpu = float(ssd.item())

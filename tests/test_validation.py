@@ -102,8 +102,8 @@ def test_empty_ranges_are_ok_without_a_device():
 
 def test_reduce_sumsq_rejects_bad_arguments():
     spec, _, _, grads = _valid()
-    ws = ps.ps_workspace_bytes()
-    assert ws >= 8 * 4096
+    ws = ps.ps_workspace_bytes(8)
+    assert ws >= 8 * 1024 and ps.ps_workspace_bytes(1 << 30) >= (1 << 30) // 128
     red = ps.ps_step_reduce_sumsq
     ok = dict(spec=spec, grads=grads, grad_scale=0.0, reduced_out=FAKE, sumsq_out=FAKE,
               accumulate=0, workspace=FAKE, workspace_bytes=ws, elem_offset=0, elem_count=8,
@@ -163,4 +163,4 @@ def test_valid_calls_report_no_device():
     assert _status(lambda: ps.ps_device_info()) == ps.PS_ENODEVICE
     assert _status(lambda: ps.ps_probe_copy(FAKE, FAKE * 2, 4096)) == ps.PS_ENODEVICE
     assert _status(lambda: ps.ps_step_reduce_sumsq(
-        spec, grads, 0.0, FAKE, FAKE, 0, FAKE, ps.ps_workspace_bytes(), 0, 8, 1024)) == ps.PS_ENODEVICE
+        spec, grads, 0.0, FAKE, FAKE, 0, FAKE, ps.ps_workspace_bytes(8), 0, 8, 1024)) == ps.PS_ENODEVICE
