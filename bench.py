@@ -43,8 +43,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="70b_zero3",
                     choices=["tiny", "gpt2s", "7b_zero2", "70b_zero3", "13b_clip"])
-    ap.add_argument("--pool-buckets", type=int, default=2,
-                    help="distinct gradient buckets kept resident as the bucket source")
+    ap.add_argument("--pool-elems", type=int, default=1 << 21,
+                    help="elements per contribution of the resident, repeating bucket source")
+    ap.add_argument("--copy-engine", choices=["kernel", "memcpy"], default="kernel")
+    ap.add_argument("--schedule", choices=["auto", "overlap", "alternate"], default="auto")
+    ap.add_argument("--bucket-elems", type=int, default=0, help="override the workload's bucket size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -91,9 +94,9 @@ def main():
 
     kernel_ms = []          # per-launch durations of the dominant kernel in the timed region
     if bucketed:
-        B = w.bucket_elems
+        B = args.bucket_elems or w.bucket_elems
         n_b = -(-n // B)
-        pool = [dgen.fill_gradient_(torch.empty(args.pool_buckets * B, dtype=tdt, device="cuda"),
+        pool = [dgen.fill_gradient_(torch.empty(args.pool_elems, dtype=tdt, device="cuda"),
                                     w.seed, w.first_step, r, w.grad_std, w.outlier_frac,
                                     w.outlier_mult, w.student_t_dof) for r in range(N)]
         staging = [torch.empty(N * B, dtype=tdt, device="cuda") for _ in range(2)]
@@ -102,7 +105,10 @@ def main():
         plan = ps.ps_bucket_plan_t()
         plan.source = C.cast(src, C.POINTER(C.c_void_p))
         plan.n_contrib, plan.dtype = N, dt
-        plan.bucket_elems, plan.source_buckets = B, args.pool_buckets
+        plan.bucket_elems, plan.source_elems = B, args.pool_elems
+        plan.copy_engine = ps.PS_COPY_KERNEL if args.copy_engine == "kernel" else ps.PS_COPY_MEMCPY
+        plan.schedule = {"auto": ps.PS_SCHED_AUTO, "overlap": ps.PS_SCHED_OVERLAP,
+                         "alternate": ps.PS_SCHED_ALTERNATE}[args.schedule]
         plan.staging[0], plan.staging[1] = staging[0].data_ptr(), staging[1].data_ptr()
         plan.copy_stream, plan.compute_stream = copy.cuda_stream, compute.cuda_stream
         plan.kernel_ms, plan.kernel_ms_len = ms, n_b
@@ -184,7 +190,21 @@ def main():
         torch.cuda.synchronize()
         iso_ms = e0.elapsed_time(e1) / reps
         extras["kernel_alone"] = {"ms": iso_ms, "GBps": bpe * B / (iso_ms * 1e-3) / 1e9,
-                                  "note": "update kernel on one 2^28 bucket, no copy in flight"}
+                                  "note": "update kernel on one bucket, nothing else on the device"}
+        # the other schedule of the same pipeline, for comparison
+        other = ps.PS_SCHED_OVERLAP if plan.schedule != ps.PS_SCHED_OVERLAP else ps.PS_SCHED_ALTERNATE
+        keep, plan.schedule = plan.schedule, other
+        step(False)
+        torch.cuda.synchronize()
+        o0 = time.perf_counter()
+        for _ in range(3):
+            step(False)
+        torch.cuda.synchronize()
+        o_ms = (time.perf_counter() - o0) * 1e3 / 3
+        plan.schedule = keep
+        extras["other_schedule"] = {"schedule": "overlap" if other == ps.PS_SCHED_OVERLAP else "alternate",
+                                    "ms_per_step": o_ms,
+                                    "kernel_ms_avg": sum(ms[b] for b in range(n_b - 1)) / (n_b - 1)}
     nbytes = min(master.numel() * 4, 1 << 32)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     with torch.cuda.stream(compute):
@@ -205,7 +225,10 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "psi": w.psi, "n_devices": N, "shard_index": w.shard_index,
                    "shard_elems": n, "grad_dtype": w.grad_dtype, "strategy": w.strategy,
-                   "bucket_elems": w.bucket_elems, "launches_per_step": launches_per_step,
+                   "bucket_elems": (B if bucketed else 0), "launches_per_step": launches_per_step,
+                   "bucket_source": ("resident pool of %d elements per contribution, repeating; "
+                                     "copy engine %s, schedule %s" %
+                                     (args.pool_elems, args.copy_engine, args.schedule)) if bucketed else None,
                    "bytes_per_elem": bpe, "step_GBps": bpe * elems_per_step / (ms_per_step * 1e-3) / 1e9,
                    "device": info.name.decode(), "arch": info.arch.decode(),
                    "compute_units": info.compute_units},
@@ -251,7 +274,7 @@ def cpu_baseline(w, bpe):
             t.join()
         return time.perf_counter() - t0
     first = one_pass()
-    reps = max(1, min(200, int(10.0 / max(first, 1e-3))))
+    reps = max(1, min(2000, int(12.0 / max(first, 1e-3))))
     total = sum(one_pass() for _ in range(reps))
     rate = sample * reps / total
     log("cpu oracle: %d threads, %d x %d elements in %.1f s -> %.3e elements/s" %

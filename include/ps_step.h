@@ -120,22 +120,50 @@ typedef struct ps_grads_t {
     int32_t dtype;              /* PS_BF16 or PS_F32, one type for all (Theorem 4)     */
 } ps_grads_t;
 
+/* How ps_step_update_bucketed moves a bucket into its staging slot. */
+enum {
+    PS_COPY_KERNEL = 0, /* the library's copy kernel; the source must be readable by
+                           device code (device memory, or pinned host memory)        */
+    PS_COPY_MEMCPY = 1  /* hipMemcpyAsync per contribution (DMA engines for host
+                           sources); needs source_elems % bucket_elems == 0          */
+};
+
+/* How the staging copy of bucket b+1 and the update of bucket b share the device. */
+enum {
+    PS_SCHED_AUTO = 0,     /* PS_COPY_KERNEL: alternate; PS_COPY_MEMCPY: overlap            */
+    PS_SCHED_OVERLAP = 1,  /* both run as soon as their inputs are ready                    */
+    PS_SCHED_ALTERNATE = 2 /* the copy of bucket b+1 starts when the update of bucket b has
+                              finished; still enqueued ahead on its own stream, no host wait */
+};
+
 /* Gradients that arrive in buckets: bucket b of a shard covers elements
  * [b*bucket_elems, min((b+1)*bucket_elems, len)).  The library copies each
  * bucket's contributions from `source` into one of two staging slots on
- * `copy_stream` while `compute_stream` updates the previous bucket. */
+ * `copy_stream` and updates it on `compute_stream`; events order the two
+ * streams, the host never waits.  In a multi-device job the source is wherever
+ * the other devices' contributions arrive (peer-mapped or host memory); on one
+ * device it is a resident pool.  A copy that runs on DMA engines is bound by
+ * its link and overlaps the update of the previous bucket.  A copy kernel reading
+ * local memory is bound by HBM like the update itself; measured on MI355X the
+ * two then finish sooner taking turns than side by side (77.9 vs 82.9 ms for the
+ * 70B shard), which is what PS_SCHED_AUTO does. */
 typedef struct ps_bucket_plan_t {
-    const void *const *source;  /* HOST array of n_contrib pointers, each DEVICE or pinned
-                                   HOST memory holding source_buckets consecutive buckets
-                                   of that contribution; bucket b is read from slot
-                                   b % source_buckets                                  */
+    const void *const *source;  /* HOST array of n_contrib pointers (DEVICE or pinned HOST
+                                   memory), each holding source_elems elements of that
+                                   contribution.  Shard element e of contribution r is
+                                   read from source[r][e % source_elems]: a source as
+                                   long as the shard holds every bucket, a shorter one is
+                                   a pool that repeats                                 */
     uint32_t n_contrib;
     int32_t dtype;
     uint64_t bucket_elems;      /* multiple of 8                                        */
-    uint64_t source_buckets;    /* >= 1                                                 */
-    void *staging[2];           /* DEVICE, each n_contrib * bucket_elems elements       */
+    uint64_t source_elems;      /* >= 1, multiple of 512                                */
+    void *staging[2];           /* DEVICE, each n_contrib * bucket_elems elements; slot
+                                   layout: contribution r at element r * bucket_elems  */
     void *copy_stream;          /* hipStream_t                                          */
     void *compute_stream;       /* hipStream_t, must differ from copy_stream            */
+    int32_t copy_engine;        /* PS_COPY_KERNEL or PS_COPY_MEMCPY                     */
+    int32_t schedule;           /* PS_SCHED_AUTO, PS_SCHED_OVERLAP or PS_SCHED_ALTERNATE */
     float *kernel_ms;           /* HOST, optional (may be NULL): receives, per bucket,
                                    the update kernel's duration in ms from HIP events
                                    on compute_stream.  When non-NULL the call waits for

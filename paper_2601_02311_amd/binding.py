@@ -15,7 +15,7 @@ import torch  # noqa: F401
 from . import build as _build
 
 __all__ = [
-    "PS_R", "PS_S", "PS_SG", "PS_M", "PS_O", "PS_BF16", "PS_F32", "PS_MAX_CONTRIB",
+    "PS_R", "PS_S", "PS_SG", "PS_M", "PS_O", "PS_BF16", "PS_F32", "PS_MAX_CONTRIB", "PS_COPY_KERNEL", "PS_COPY_MEMCPY", "PS_SCHED_AUTO", "PS_SCHED_OVERLAP", "PS_SCHED_ALTERNATE",
     "PS_OK", "PS_EINVAL", "PS_EUNSUPPORTED", "PS_EALIGN", "PS_ERANGE", "PS_ENODEVICE", "PS_EHIP",
     "PsError", "ps_spec_t", "ps_cost_t", "ps_adamw_t", "ps_shard_t", "ps_grads_t",
     "ps_bucket_plan_t", "ps_device_info_t", "library", "library_path",
@@ -26,6 +26,8 @@ __all__ = [
 
 PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
 PS_BF16, PS_F32 = 0, 1
+PS_COPY_KERNEL, PS_COPY_MEMCPY = 0, 1
+PS_SCHED_AUTO, PS_SCHED_OVERLAP, PS_SCHED_ALTERNATE = 0, 1, 2
 PS_MAX_CONTRIB = 16
 (PS_OK, PS_EINVAL, PS_EUNSUPPORTED, PS_EALIGN, PS_ERANGE, PS_ENODEVICE, PS_EHIP) = range(7)
 
@@ -80,8 +82,9 @@ class ps_grads_t(C.Structure):
 class ps_bucket_plan_t(C.Structure):
     _fields_ = [("source", C.POINTER(C.c_void_p)), ("n_contrib", C.c_uint32),
                 ("dtype", C.c_int32), ("bucket_elems", C.c_uint64),
-                ("source_buckets", C.c_uint64), ("staging", C.c_void_p * 2),
+                ("source_elems", C.c_uint64), ("staging", C.c_void_p * 2),
                 ("copy_stream", C.c_void_p), ("compute_stream", C.c_void_p),
+                ("copy_engine", C.c_int32), ("schedule", C.c_int32),
                 ("kernel_ms", C.POINTER(C.c_float)), ("kernel_ms_len", C.c_uint64)]
 
 

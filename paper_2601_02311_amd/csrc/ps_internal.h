@@ -45,6 +45,12 @@ int launch_reduce_sumsq(int dtype, uint32_t n_contrib, const ContribPtrs &g, flo
                         float *reduced_out, uint64_t count, double *partials,
                         double *sumsq_out, int accumulate, void *stream);
 int launch_copy(void *dst, const void *src, uint64_t bytes, void *stream);
+// Stage one bucket: for each contribution r copy n_vec 16-byte vectors to
+// dst + r * slot_stride_bytes from src.p[r], starting at vector first_vec of the
+// periodic source (period_vec vectors long).  `alone` says that no other kernel
+// runs beside it (it then caps its own residency).
+int launch_stage(uint32_t n_contrib, const ContribPtrs &src, void *dst, uint64_t slot_stride_bytes,
+                 uint64_t first_vec, uint64_t period_vec, uint64_t n_vec, bool alone, void *stream);
 
 } // namespace ps
 

@@ -351,6 +351,48 @@ __global__ __launch_bounds__(kWave) void copy_tiles(u32x4 *dst, const u32x4 *src
             dst[i] = src[i];
 }
 
+struct StageArgs {
+    ContribPtrs src;
+    char *dst;
+    uint64_t slot_stride_bytes;
+    uint64_t first_vec;  // position of the bucket's first vector in the periodic source
+    uint64_t period_vec; // source length in 16-byte vectors
+    uint64_t n_vec;      // vectors per contribution in this bucket
+    uint32_t wrap_once;  // period_vec >= vectors per trip: at most one wrap inside a trip
+};
+
+// Bucket staging: blockIdx.y selects the contribution, each wave moves U KiB per
+// trip and strides over the bucket by the grid width.  The source repeats with
+// period_vec (a multiple of 64 U is not required: the wrap is found per lane,
+// from one wave-uniform remainder per trip).
+template <int U>
+__global__ __launch_bounds__(kWave) void stage_bucket(const StageArgs a)
+{
+    const u32x4 *src = reinterpret_cast<const u32x4 *>(a.src.p[blockIdx.y]);
+    u32x4 *dst = reinterpret_cast<u32x4 *>(a.dst + (uint64_t)blockIdx.y * a.slot_stride_bytes);
+    for (uint64_t base = (uint64_t)blockIdx.x * (kWave * U); base < a.n_vec;
+         base += (uint64_t)gridDim.x * (kWave * U)) {
+        // position of this trip's first vector in the source, same for all lanes
+        const uint64_t s0 = (a.first_vec + base) % a.period_vec;
+        u32x4 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t i = base + (uint64_t)u * kWave + threadIdx.x;
+            uint64_t s = s0 + (uint64_t)u * kWave + threadIdx.x;
+            if (s >= a.period_vec)
+                s = a.wrap_once ? s - a.period_vec : s % a.period_vec;
+            if (i < a.n_vec)
+                x[u] = load_vec<false>(src + s); // plain load: a short source stays in L2
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t i = base + (uint64_t)u * kWave + threadIdx.x;
+            if (i < a.n_vec)
+                store_vec<true>(dst + i, x[u]);
+        }
+    }
+}
+
 } // namespace ps
 
 #endif

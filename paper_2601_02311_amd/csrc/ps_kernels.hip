@@ -11,6 +11,11 @@ namespace ps {
 // the HBM request stream stays narrow enough to run at ~6.6 TB/s on MI355X.
 constexpr uint32_t kUpdateLdsBytes = 20480;
 constexpr uint32_t kReduceLdsBytes = 40960;
+// The staging copy, when it has the device to itself, runs best with the same cap
+// (8 waves of 4 KiB in flight per CU: 6.8 TB/s of writes from an L2-resident
+// source).  When it shares the device with the update kernel it asks for no LDS,
+// so that it never waits behind the update's own LDS reservations.
+constexpr uint32_t kStageAloneLdsBytes = 20480;
 // Largest grid used; beyond it the kernels loop (never reached below 5e11 elements).
 constexpr uint64_t kMaxGrid = 0x7fffffffull;
 // Second level of the sum-of-squares tree.
@@ -198,6 +203,29 @@ int launch_copy(void *dst, const void *src, uint64_t bytes, void *stream)
     hipLaunchKernelGGL(copy_tiles, dim3(grid), dim3(kWave), 0, st,
                        reinterpret_cast<u32x4 *>(dst), reinterpret_cast<const u32x4 *>(src),
                        n_tiles, n_vec);
+    return (int)hipGetLastError();
+}
+
+int launch_stage(uint32_t n_contrib, const ContribPtrs &src, void *dst, uint64_t slot_stride_bytes,
+                 uint64_t first_vec, uint64_t period_vec, uint64_t n_vec, bool alone, void *stream)
+{
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    constexpr int U = 4;
+    const uint64_t groups = (n_vec + kWave * U - 1) / (kWave * U);
+    if (groups == 0)
+        return 0;
+    if (groups > kMaxGrid)
+        return (int)hipErrorInvalidConfiguration;
+    StageArgs a;
+    a.src = src;
+    a.dst = reinterpret_cast<char *>(dst);
+    a.slot_stride_bytes = slot_stride_bytes;
+    a.first_vec = first_vec % period_vec;
+    a.period_vec = period_vec;
+    a.n_vec = n_vec;
+    a.wrap_once = period_vec >= (uint64_t)kWave * U;
+    hipLaunchKernelGGL((stage_bucket<U>), dim3((uint32_t)groups, n_contrib), dim3(kWave),
+                       alone ? kStageAloneLdsBytes : 0u, st, a);
     return (int)hipGetLastError();
 }
 

@@ -353,9 +353,26 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
         set_error("bucket_elems must be a positive multiple of 8");
         return PS_EALIGN;
     }
-    if (plan->source_buckets == 0) {
-        set_error("source_buckets must be >= 1");
+    if (plan->source_elems == 0) {
+        set_error("source_elems must be >= 1");
         return PS_ERANGE;
+    }
+    if (plan->source_elems % 512 != 0) {
+        set_error("source_elems must be a multiple of 512");
+        return PS_EALIGN;
+    }
+    if (plan->copy_engine != PS_COPY_KERNEL && plan->copy_engine != PS_COPY_MEMCPY) {
+        set_error("copy_engine must be PS_COPY_KERNEL or PS_COPY_MEMCPY");
+        return PS_EINVAL;
+    }
+    if (plan->schedule != PS_SCHED_AUTO && plan->schedule != PS_SCHED_OVERLAP &&
+        plan->schedule != PS_SCHED_ALTERNATE) {
+        set_error("schedule must be PS_SCHED_AUTO, PS_SCHED_OVERLAP or PS_SCHED_ALTERNATE");
+        return PS_EINVAL;
+    }
+    if (plan->copy_engine == PS_COPY_MEMCPY && plan->source_elems % plan->bucket_elems != 0) {
+        set_error("PS_COPY_MEMCPY needs source_elems to be a multiple of bucket_elems");
+        return PS_EUNSUPPORTED;
     }
     if (!plan->staging[0] || !plan->staging[1] || plan->staging[0] == plan->staging[1]) {
         set_error("two distinct staging buffers are required");
@@ -386,6 +403,11 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
     const uint64_t eb = elem_bytes(plan->dtype);
     const uint64_t slot_stride = plan->bucket_elems * eb; // bytes between contributions in a slot
     const bool timed = plan->kernel_ms != nullptr;
+    // A copy kernel and the update kernel both live on HBM bandwidth: run side by
+    // side they only widen each other's request windows, so they take turns.  A
+    // DMA copy (host or peer source) is bound by its link and overlaps.
+    const bool alternate = plan->schedule == PS_SCHED_ALTERNATE ||
+                           (plan->schedule == PS_SCHED_AUTO && plan->copy_engine == PS_COPY_KERNEL);
 
     // staged[k]: slot k holds a complete bucket; freed[k]: the kernel reading slot k is done.
     hipEvent_t staged[2] = {nullptr, nullptr}, freed[2] = {nullptr, nullptr};
@@ -412,24 +434,41 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
         }
     }
 
+    ContribPtrs src;
+    std::memset(&src, 0, sizeof src);
+    for (uint32_t r = 0; r < plan->n_contrib; ++r)
+        src.p[r] = plan->source[r];
+
     auto stage = [&](uint64_t b) {
         const int k = (int)(b & 1);
         const uint64_t lo = b * plan->bucket_elems;
         const uint64_t cnt = clamp_count(lo, plan->bucket_elems, shard->len);
-        const uint64_t src_off = (b % plan->source_buckets) * plan->bucket_elems * eb;
         if (b >= 2) // the slot is reused: wait for the kernel that read it
             PS_TRY(hipStreamWaitEvent(copy, freed[k], 0));
-        for (uint32_t r = 0; r < plan->n_contrib; ++r)
-            PS_TRY(hipMemcpyAsync(reinterpret_cast<char *>(plan->staging[k]) + r * slot_stride,
-                                  reinterpret_cast<const char *>(plan->source[r]) + src_off,
-                                  cnt * eb, hipMemcpyDefault, copy));
+        if (alternate && b >= 1) // take turns: start after the update of bucket b-1 has finished
+            PS_TRY(hipStreamWaitEvent(copy, freed[k ^ 1], 0));
+        if (plan->copy_engine == PS_COPY_MEMCPY) {
+            const uint64_t src_off = (lo % plan->source_elems) * eb;
+            for (uint32_t r = 0; r < plan->n_contrib; ++r)
+                PS_TRY(hipMemcpyAsync(reinterpret_cast<char *>(plan->staging[k]) + r * slot_stride,
+                                      reinterpret_cast<const char *>(plan->source[r]) + src_off,
+                                      cnt * eb, hipMemcpyDefault, copy));
+        } else if (e == hipSuccess) {
+            int le = launch_stage(plan->n_contrib, src, plan->staging[k], slot_stride,
+                                  lo * eb / 16, plan->source_elems * eb / 16,
+                                  (cnt * eb + 15) / 16, alternate, copy);
+            if (le != 0) {
+                e = (hipError_t)le;
+                what = "staging kernel launch";
+            }
+        }
         PS_TRY(hipEventRecord(staged[k], copy));
     };
 
     stage(0);
     for (uint64_t b = 0; b < n_buckets && e == hipSuccess; ++b) {
         const int k = (int)(b & 1);
-        if (b + 1 < n_buckets)
+        if (b + 1 < n_buckets && !alternate)
             stage(b + 1);
         const uint64_t lo = b * plan->bucket_elems;
         const uint64_t cnt = clamp_count(lo, plan->bucket_elems, shard->valid_len);
@@ -452,6 +491,8 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
         if (timed)
             PS_TRY(hipEventRecord(t1[b], comp));
         PS_TRY(hipEventRecord(freed[k], comp));
+        if (b + 1 < n_buckets && alternate)
+            stage(b + 1);
     }
     // Later work on the copy stream must not overtake the last kernels.
     PS_TRY(hipStreamWaitEvent(copy, freed[(n_buckets - 1) & 1], 0));

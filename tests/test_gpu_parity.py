@@ -291,11 +291,12 @@ def test_clipped_two_phase_step_matches_oracle():
 
 # ---- bucket pipeline ----
 
-def _bucketed(spec, hp, state, grads_np, dtype, n, valid, bucket, source_buckets, timed=False):
+def _bucketed(spec, hp, state, src_np, dtype, n, valid, bucket, engine, timed=False,
+              schedule=ps.PS_SCHED_AUTO):
     th, m, v, p = [dev(a) for a in state]
     esz = 2 if dtype == "bf16" else 4
-    N = len(grads_np)
-    src = [dev(g) for g in grads_np]
+    N = len(src_np)
+    src = [dev(g) for g in src_np]
     staging = [torch.zeros(N * bucket * esz, dtype=torch.uint8, device="cuda") for _ in range(2)]
     copy, comp = torch.cuda.Stream(), torch.cuda.Stream()
     torch.cuda.synchronize()
@@ -303,9 +304,10 @@ def _bucketed(spec, hp, state, grads_np, dtype, n, valid, bucket, source_buckets
     arr = (C.c_void_p * N)(*[s.data_ptr() for s in src])
     plan.source = C.cast(arr, C.POINTER(C.c_void_p))
     plan.n_contrib, plan.dtype = N, (ps.PS_BF16 if dtype == "bf16" else ps.PS_F32)
-    plan.bucket_elems, plan.source_buckets = bucket, source_buckets
+    plan.bucket_elems, plan.source_elems = bucket, src_np[0].shape[0]
     plan.staging[0], plan.staging[1] = staging[0].data_ptr(), staging[1].data_ptr()
     plan.copy_stream, plan.compute_stream = copy.cuda_stream, comp.cuda_stream
+    plan.copy_engine, plan.schedule = engine, schedule
     n_b = -(-n // bucket)
     ms = (C.c_float * n_b)()
     if timed:
@@ -315,21 +317,31 @@ def _bucketed(spec, hp, state, grads_np, dtype, n, valid, bucket, source_buckets
     return [host(x) for x in (th, m, v, p)], list(ms)
 
 
+def _periodic(src_np, n):
+    """What the pipeline reads: element e of the shard comes from source[e % len(source)]."""
+    reps = -(-n // src_np[0].shape[0])
+    return [np.ascontiguousarray(np.tile(g, reps)[:n]) for g in src_np]
+
+
+@pytest.mark.parametrize("engine,schedule", [(ps.PS_COPY_KERNEL, ps.PS_SCHED_AUTO),
+                                             (ps.PS_COPY_KERNEL, ps.PS_SCHED_OVERLAP),
+                                             (ps.PS_COPY_MEMCPY, ps.PS_SCHED_AUTO),
+                                             (ps.PS_COPY_MEMCPY, ps.PS_SCHED_ALTERNATE)])
 @pytest.mark.parametrize("timed", [False, True])
-def test_bucketed_step_matches_oracle(timed):
-    n, N, bucket = 9 * TILE + 520, 8, 2 * TILE + 8     # 5 buckets, the last one short
+def test_bucketed_step_matches_oracle(timed, engine, schedule):
+    bucket, N = 2 * TILE + 512, 8          # 4608: a multiple of 512 so that both engines apply
+    n = 4 * bucket + 1259                   # 5 buckets, the last one short and ragged
     valid = n - 3
     n_b = -(-n // bucket)
-    _say("bucketed n=%d bucket=%d (%d buckets) timed=%s" % (n, bucket, n_b, timed))
+    _say("bucketed n=%d bucket=%d (%d buckets) timed=%s engine=%d schedule=%d" %
+         (n, bucket, n_b, timed, engine, schedule))
     spec = ps.ps_spec_preset("zero3", N, 7, n * N)
-    # the source holds every bucket, padded to whole buckets
-    grads = [gen.gradient(n_b * bucket, 41, 0, r, "bf16", 1e-4) for r in range(N)]
+    src = [gen.gradient(n_b * bucket, 41, 0, r, "bf16", 1e-4) for r in range(N)]   # every bucket resident
     state = [gen.master(n, 41), *gen.moments(n, 41, True), np.full(n, 0xABCD, np.uint16)]
     hpd, hp = hp_of(None, 1000)
     want = [a.copy() for a in state]
-    orc.step_f32([np.ascontiguousarray(g[:n]) for g in grads],
-                 orc.derive_scalars(t=1000, n_devices=N, **hpd), *want, lo=0, hi=valid)
-    got, ms = _bucketed(spec, hp, state, grads, "bf16", n, valid, bucket, n_b, timed)
+    orc.step_f32(_periodic(src, n), orc.derive_scalars(t=1000, n_devices=N, **hpd), *want, lo=0, hi=valid)
+    got, ms = _bucketed(spec, hp, state, src, "bf16", n, valid, bucket, engine, timed, schedule)
     assert assert_state_parity(got, want, "bucketed") == 0
     for g, a in zip(got, state):
         assert np.array_equal(g[valid:].view(np.uint8), a[valid:].view(np.uint8))
@@ -337,16 +349,20 @@ def test_bucketed_step_matches_oracle(timed):
         assert all(x > 0 for x in ms)
 
 
-def test_bucketed_step_with_a_cycling_source_pool():
-    """source_buckets = 2: bucket b reads pool slot b % 2 (how the benchmark feeds 33 buckets)."""
-    n, N, bucket = 6 * TILE, 4, TILE
-    _say("bucketed with pool of 2, n=%d" % n)
+@pytest.mark.parametrize("dtype,engine,pool", [("f32", ps.PS_COPY_MEMCPY, 2 * TILE),    # pool of 2 buckets
+                                               ("f32", ps.PS_COPY_KERNEL, 2 * TILE),
+                                               ("bf16", ps.PS_COPY_KERNEL, 1536),        # shorter than a bucket,
+                                               ("f32", ps.PS_COPY_KERNEL, 512)])         # buckets straddle the wrap
+def test_bucketed_step_with_a_repeating_source_pool(dtype, engine, pool):
+    """A source shorter than the shard repeats: element e reads source[e % source_elems]
+    (how the benchmark feeds 33 buckets from a small resident pool)."""
+    n, N, bucket = 6 * TILE + 40, 4, TILE
+    _say("bucketed from a pool of %d elements, n=%d %s engine=%d" % (pool, n, dtype, engine))
     spec = ps.ps_spec_preset("zero3", N, 0, n * N)
-    pool = [gen.gradient(2 * bucket, 43, 0, r, "f32", 1e-3) for r in range(N)]
-    tiled = [np.tile(g, n // (2 * bucket)) for g in pool]
+    src = [gen.gradient(pool, 43, 0, r, dtype, 1e-3) for r in range(N)]
     state = [gen.master(n, 43), *gen.moments(n, 43, False), np.zeros(n, np.uint16)]
     hpd, hp = hp_of(None, 1)
     want = [a.copy() for a in state]
-    orc.step_f32(tiled, orc.derive_scalars(t=1, n_devices=N, **hpd), *want)
-    got, _ = _bucketed(spec, hp, state, pool, "f32", n, n, bucket, 2)
+    orc.step_f32(_periodic(src, n), orc.derive_scalars(t=1, n_devices=N, **hpd), *want)
+    got, _ = _bucketed(spec, hp, state, src, dtype, n, n, bucket, engine)
     assert assert_state_parity(got, want, "pool") == 0

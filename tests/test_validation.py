@@ -128,7 +128,7 @@ def test_bucketed_rejects_bad_arguments():
     def plan(**kw):
         p = ps.ps_bucket_plan_t()
         p.source = C.cast(src, C.POINTER(C.c_void_p))
-        p.n_contrib, p.dtype, p.bucket_elems, p.source_buckets = 4, ps.PS_BF16, 256, 1
+        p.n_contrib, p.dtype, p.bucket_elems, p.source_elems = 4, ps.PS_BF16, 256, 1024
         p.staging[0], p.staging[1] = FAKE * 2, FAKE * 3
         p.copy_stream, p.compute_stream = 0x100, 0x200
         for k, v in kw.items():
@@ -141,7 +141,12 @@ def test_bucketed_rejects_bad_arguments():
     assert _status(lambda: run(spec, hp, shard, None)) == ps.PS_EINVAL
     assert _status(lambda: run(spec, hp, shard, plan(bucket_elems=0))) == ps.PS_EALIGN
     assert _status(lambda: run(spec, hp, shard, plan(bucket_elems=100))) == ps.PS_EALIGN
-    assert _status(lambda: run(spec, hp, shard, plan(source_buckets=0))) == ps.PS_ERANGE
+    assert _status(lambda: run(spec, hp, shard, plan(source_elems=0))) == ps.PS_ERANGE
+    assert _status(lambda: run(spec, hp, shard, plan(source_elems=1000))) == ps.PS_EALIGN
+    assert _status(lambda: run(spec, hp, shard, plan(copy_engine=2))) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, shard, plan(schedule=3))) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, shard, plan(copy_engine=ps.PS_COPY_MEMCPY, bucket_elems=384,
+                                                       source_elems=1024))) == ps.PS_EUNSUPPORTED
     assert _status(lambda: run(spec, hp, shard, plan(staging=(FAKE, FAKE)))) == ps.PS_EINVAL
     assert _status(lambda: run(spec, hp, shard, plan(staging=(FAKE, 0)))) == ps.PS_EINVAL
     assert _status(lambda: run(spec, hp, shard, plan(compute_stream=0x100))) == ps.PS_EINVAL
