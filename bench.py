@@ -49,6 +49,8 @@ def main():
     ap.add_argument("--schedule", choices=["auto", "overlap", "alternate"], default="auto")
     ap.add_argument("--bucket-elems", type=int, default=0, help="override the workload's bucket size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the update kernel alone, the other pipeline schedule and a plain copy")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the other N-1 devices of the placement are "
@@ -117,9 +119,9 @@ def main():
         def step(record):
             ps.ps_step_update_bucketed(spec, hp(), shard, plan)
             if record:
-                kernel_ms.extend(ms[b] for b in range(n_b - 1))   # full buckets only
+                kernel_ms.extend(ms[b] for b in range(n_b))   # every launch, the short last bucket too
             step_no[0] += 1
-        elems_per_launch = B
+        elems_per_launch = cost.valid_len / n_b               # average over the launches of a step
     else:
         grads = dgen.workload_gradients(w, w.first_step)
         g = ps.make_grads([t.data_ptr() for t in grads], dt)
@@ -177,7 +179,7 @@ def main():
     # The same kernel alone on the device (no staging copy in flight) and a plain copy
     # of equal footprint, as yardsticks; neither is the headline value.
     extras = {}
-    if bucketed:
+    if bucketed and args.extras:
         gs = ps.make_grads([staging[0].data_ptr() + r * B * esz for r in range(N)], dt)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         reps = 8
@@ -205,16 +207,17 @@ def main():
         extras["other_schedule"] = {"schedule": "overlap" if other == ps.PS_SCHED_OVERLAP else "alternate",
                                     "ms_per_step": o_ms,
                                     "kernel_ms_avg": sum(ms[b] for b in range(n_b - 1)) / (n_b - 1)}
+    # One plain copy of known size: the yardstick that hardware byte counters are scaled by.
     nbytes = min(master.numel() * 4, 1 << 32)
+    reps = 5 if args.extras else 1
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     with torch.cuda.stream(compute):
-        ps.ps_probe_copy(m.data_ptr(), v.data_ptr(), nbytes, compute.cuda_stream)
         e0.record(compute)
-        for _ in range(5):
+        for _ in range(reps):
             ps.ps_probe_copy(m.data_ptr(), v.data_ptr(), nbytes, compute.cuda_stream)
         e1.record(compute)
     torch.cuda.synchronize()
-    cp_ms = e0.elapsed_time(e1) / 5
+    cp_ms = e0.elapsed_time(e1) / reps
     extras["copy_probe"] = {"bytes": nbytes, "ms": cp_ms, "GBps": 2 * nbytes / (cp_ms * 1e-3) / 1e9}
     log("extras: %s" % json.dumps(extras))
 
@@ -233,7 +236,8 @@ def main():
                    "device": info.name.decode(), "arch": info.arch.decode(),
                    "compute_units": info.compute_units},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                     "frac": achieved / PEAK_HBM_GBS,
+                     "traffic": measured_traffic(w, elems_per_launch),
                      "kernel": "update_tiles" if not clip else "reduce_sumsq_tiles+update_tiles",
                      "elems_per_launch": elems_per_launch, "avg_launch_ms": avg_ms,
                      "launches_timed": len(kernel_ms)},
@@ -242,6 +246,27 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, bpe)
     print(json.dumps(result), flush=True)
+
+
+def measured_traffic(w, elems_per_launch):
+    """HBM bytes per launch of the dominant kernel from the committed hardware-counter summary
+    (profiles/update_tiles_hbm_traffic.txt).  None when there is no summary for this workload
+    or when the kernel sources have changed since the counters were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "update_tiles_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    kv = {}
+    for line in open(path):
+        if "=" in line and not line.lstrip().startswith("#"):
+            k, v = line.split("=", 1)
+            kv[k.strip()] = v.split("#", 1)[0].strip()
+    h = hashlib.sha256()
+    for f in ("ps_kernel_templates.h", "ps_kernels.hip"):
+        h.update(open(os.path.join(ROOT, "paper_2601_02311_amd", "csrc", f), "rb").read())
+    if kv.get("kernel_sources_sha256") != h.hexdigest() or kv.get("workload") != w.name:
+        return None
+    return float(kv["hbm_bytes_per_element"]) * elems_per_launch
 
 
 def cpu_baseline(w, bpe):
