@@ -366,3 +366,92 @@ def test_bucketed_step_with_a_repeating_source_pool(dtype, engine, pool):
     orc.step_f32(_periodic(src, n), orc.derive_scalars(t=1, n_devices=N, **hpd), *want)
     got, _ = _bucketed(spec, hp, state, src, dtype, n, n, bucket, engine)
     assert assert_state_parity(got, want, "pool") == 0
+
+
+# ---- memory safety and statelessness ----
+
+GUARD = 4096  # bytes of guard band on each side of every device buffer
+
+
+def _guarded(a):
+    """Upload `a` into the middle of a larger byte buffer filled with 0xA5; return
+    (whole, view-of-payload)."""
+    raw = np.full(a.nbytes + 2 * GUARD, 0xA5, np.uint8)
+    raw[GUARD:GUARD + a.nbytes] = a.view(np.uint8)
+    whole = torch.from_numpy(raw).cuda()
+    return whole, whole[GUARD:GUARD + a.nbytes]
+
+
+def _guards_intact(whole, nbytes):
+    h = whole.cpu().numpy()
+    return (h[:GUARD] == 0xA5).all() and (h[GUARD + nbytes:] == 0xA5).all()
+
+
+@pytest.mark.parametrize("dtype,N", [("bf16", 8), ("f32", 6), ("bf16", 3)])
+def test_no_write_outside_the_buffers(dtype, N):
+    n = 5 * TILE + 250 + 3
+    valid = n - 2
+    _say("guard bands n=%d N=%d %s: update, reduce+sumsq, bucketed" % (n, N, dtype))
+    spec = ps.ps_spec_preset("zero3", N, 0, n * N)
+    grads = [gen.gradient(n, 61, 0, r, dtype) for r in range(N)]
+    state = [gen.master(n, 61), *gen.moments(n, 61, True), np.zeros(n, np.uint16)]
+    bufs = [_guarded(a) for a in state]
+    gbufs = [_guarded(g) for g in grads]
+    _, hp = hp_of(None, 3)
+    shard = ps.ps_shard_t(*[v.data_ptr() for _, v in bufs], n, valid)
+    g = ps.make_grads([v.data_ptr() for _, v in gbufs], ps.PS_BF16 if dtype == "bf16" else ps.PS_F32)
+    ps.ps_step_update(spec, hp, shard, g, 0, n, stream_handle())
+    red_w, red = _guarded(np.zeros(n, np.float32))
+    ss_w, ss = _guarded(np.zeros(1, np.float64))
+    ws_w, ws = _guarded(np.zeros(ps.ps_workspace_bytes(n), np.uint8))
+    ps.ps_step_reduce_sumsq(spec, g, 0.0, red.data_ptr(), ss.data_ptr(), 0, ws.data_ptr(),
+                            ws.numel(), 0, n, valid, stream_handle())
+    bucket = TILE + 8
+    esz = 2 if dtype == "bf16" else 4
+    st = [_guarded(np.zeros(N * bucket * esz, np.uint8)) for _ in range(2)]
+    plan = ps.ps_bucket_plan_t()
+    src_np = [gen.gradient(1024, 62, 0, r, dtype) for r in range(N)]
+    src = [_guarded(a) for a in src_np]
+    arr = (C.c_void_p * N)(*[v.data_ptr() for _, v in src])
+    plan.source = C.cast(arr, C.POINTER(C.c_void_p))
+    plan.n_contrib, plan.dtype = N, (ps.PS_BF16 if dtype == "bf16" else ps.PS_F32)
+    plan.bucket_elems, plan.source_elems = bucket, 1024
+    plan.staging[0], plan.staging[1] = st[0][1].data_ptr(), st[1][1].data_ptr()
+    c1, c2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    plan.copy_stream, plan.compute_stream = c1.cuda_stream, c2.cuda_stream
+    ps.ps_step_update_bucketed(spec, hp, shard, plan)
+    torch.cuda.synchronize()
+    for (whole, _), a in zip(bufs + gbufs + src, state + grads + src_np):
+        assert _guards_intact(whole, a.nbytes)
+    assert _guards_intact(red_w, n * 4) and _guards_intact(ss_w, 8)
+    assert _guards_intact(ws_w, ps.ps_workspace_bytes(n))
+    assert all(_guards_intact(w_, N * bucket * esz) for w_, _ in st)
+    for (_, v), a in zip(gbufs + src, grads + src_np):                    # inputs are read-only
+        assert np.array_equal(v.cpu().numpy(), a.view(np.uint8))
+
+
+def test_checkpoint_and_resume_is_bit_identical():
+    """The library keeps no state: 10 steps equal 5 steps, a copy of the flat buffers to
+    the host and into fresh device buffers, and 5 more steps."""
+    n, N = 3 * TILE + 77, 4
+    _say("checkpoint/resume n=%d" % n)
+    spec = ps.ps_spec_preset("zero3", N, 1, n * N)
+    state = [gen.master(n, 71), *gen.moments(n, 71, False), np.zeros(n, np.uint16)]
+
+    def run(bufs, steps):
+        for t in steps:
+            gd = [dev(gen.gradient(n, 71, t, r, "bf16")) for r in range(N)]
+            _, hp = hp_of(None, t)
+            ps.ps_step_update(spec, hp, shard_of(*bufs, n), grads_of(gd, "bf16"), 0, n, stream_handle())
+            torch.cuda.synchronize()
+    a = [dev(x) for x in state]
+    run(a, range(1, 11))
+    b = [dev(x) for x in state]
+    run(b, range(1, 6))
+    saved = [host(x).copy() for x in b]
+    del b
+    c = [dev(x) for x in saved]
+    run(c, range(6, 11))
+    for x, y in zip(a, c):
+        assert np.array_equal(host(x).view(np.uint8), host(y).view(np.uint8))
