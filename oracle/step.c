@@ -135,6 +135,21 @@ void oracle_reduce_sum(const void *const *g, uint32_t n_contrib, int is_f32,
     }
 }
 
+/* Gradient accumulation over micro-batches (Limitations: several micro-batches
+ * before one synchronisation).  Each call adds one micro-batch: its N
+ * contributions are summed in the fixed order, then that sum is added to the
+ * running binary32 total; the first micro-batch (overwrite != 0) stores its sum. */
+void oracle_accumulate(const void *const *g, uint32_t n_contrib, int is_f32,
+                       float *accum, int overwrite, uint64_t lo, uint64_t hi)
+{
+    for (uint64_t e = lo; e < hi; ++e) {
+        float acc = contribution(g, is_f32, 0, e);
+        for (uint32_t r = 1; r < n_contrib; ++r)
+            acc = acc + contribution(g, is_f32, r, e);
+        accum[e] = overwrite ? acc : accum[e] + acc;
+    }
+}
+
 /* Mean gradient g = acc * gs and the sum of its squares, the latter summed
  * sequentially in binary64 (each product of two widened binary32 values is
  * exact in binary64).  g_out may be NULL.  Returns the sum over [lo, hi). */

@@ -43,6 +43,9 @@ def lib():
         L.oracle_reduce_sum.restype = None
         L.oracle_reduce_sum.argtypes = [pp, C.c_uint32, C.c_int, C.c_void_p,
                                         C.c_uint64, C.c_uint64]
+        L.oracle_accumulate.restype = None
+        L.oracle_accumulate.argtypes = [pp, C.c_uint32, C.c_int, C.c_void_p, C.c_int,
+                                        C.c_uint64, C.c_uint64]
         L.oracle_mean_sumsq.restype = C.c_double
         L.oracle_mean_sumsq.argtypes = [pp, C.c_uint32, C.c_int, C.c_float, C.c_void_p,
                                         C.c_uint64, C.c_uint64]
@@ -110,6 +113,14 @@ def reduce_sum(grads, lo=0, hi=None):
     acc = np.zeros(n, dtype=np.float32)
     lib().oracle_reduce_sum(ptrs, n_c, is_f32, acc.ctypes.data, lo, hi)
     return acc
+
+
+def accumulate(grads, accum, overwrite, lo=0, hi=None):
+    """accum[lo:hi] (+)= fixed-order sum of one micro-batch's contributions, in place."""
+    ptrs, n_c, is_f32, n = _contrib_ptrs(grads)
+    hi = n if hi is None else hi
+    _check(accum, np.float32, n)
+    lib().oracle_accumulate(ptrs, n_c, is_f32, accum.ctypes.data, int(bool(overwrite)), lo, hi)
 
 
 def mean_sumsq(grads, gs, lo=0, hi=None, want_mean=True):

@@ -161,6 +161,31 @@ def test_integrity_violations_are_visible():
     assert rel(orc.mean_sumsq(grads, 1.0 / N)[0]) == 0.0
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_accumulate_micro_batches(dtype):
+    """k micro-batches: running = running + ((g0+g1)+...), against a numpy scalar loop;
+    one micro-batch with overwrite equals the plain reduce; untouched outside the range."""
+    n, N, k = 3001, 4, 5
+    accum = np.full(n, np.float32(123.0))
+    want = None
+    for j in range(k):
+        grads = [gen.gradient(n, 91, j, r, dtype, std=1.0) for r in range(N)]
+        micro = _np_fixed_order_sum(grads)
+        want = micro if j == 0 else (want + micro).astype(np.float32)
+        orc.accumulate(grads, accum, overwrite=(j == 0), lo=7, hi=n - 5)
+        if j == 0:
+            assert np.array_equal(accum[7:n - 5].view(np.uint32), orc.reduce_sum(grads)[7:n - 5].view(np.uint32))
+    assert np.array_equal(accum[7:n - 5].view(np.uint32), want[7:n - 5].view(np.uint32))
+    assert (accum[:7] == 123.0).all() and (accum[n - 5:] == 123.0).all()
+    # the mean over N*k contributions then feeds the step as one fp32 contribution
+    gm, _ = orc.mean_sumsq([accum], 1.0 / (N * k), 7, n - 5)
+    exact = sum(sum((g.astype(np.uint32) << 16).view(np.float32).astype(np.float64) if g.dtype == np.uint16
+                    else g.astype(np.float64)
+                    for g in [gen.gradient(n, 91, j, r, dtype, std=1.0) for r in range(N)])
+                for j in range(k)) / (N * k)
+    assert np.allclose(gm[7:n - 5], exact[7:n - 5], rtol=0, atol=2e-6)
+
+
 def test_sumsq_and_clip():
     n = 10007
     grads = [gen.gradient(n, 3, 0, r, "f32", std=1e-2, student_t_dof=3) for r in range(6)]
