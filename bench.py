@@ -29,10 +29,15 @@ def log(msg):
 
 
 def bytes_per_elem(w, clip=False):
-    """Algorithmic bytes per element: every byte touched once."""
+    """Algorithmic bytes per element of one step: every byte touched once."""
     g = 2 if w.grad_dtype == "bf16" else 4
     if clip:   # phase 1: N reads + fp32 spill; phase 2: spill + state in, state + bf16 out
         return g * w.n_devices + 4 + 4 + 12 + 14
+    if w.strategy == "zero1":          # one all-reduced gradient
+        return g + 12 + 12 + 2
+    if w.micro_batches > 1:            # k accumulations (the first only writes), then the update
+        k = w.micro_batches
+        return k * (g * w.n_devices + 4) + (k - 1) * 4 + 4 + 12 + 14
     return g * w.n_devices + 12 + 12 + 2
 
 
@@ -42,7 +47,8 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="70b_zero3",
-                    choices=["tiny", "gpt2s", "7b_zero2", "70b_zero3", "13b_clip"])
+                    choices=["tiny", "gpt2s", "7b_zero2", "70b_zero3", "13b_clip", "7b_zero1",
+                             "7b_accum4"])
     ap.add_argument("--pool-elems", type=int, default=1 << 21,
                     help="elements per contribution of the resident, repeating bucket source")
     ap.add_argument("--copy-engine", choices=["kernel", "memcpy"], default="kernel")
@@ -123,8 +129,16 @@ def main():
             step_no[0] += 1
         elems_per_launch = cost.valid_len / n_b               # average over the launches of a step
     else:
-        grads = dgen.workload_gradients(w, w.first_step)
+        zero1, k_mb = w.strategy == "zero1", w.micro_batches
+        if zero1:      # the all-reduced gradient: one replicated buffer of psi_padded elements
+            grads = [dgen.fill_gradient_(torch.empty(cost.psi_padded, dtype=tdt, device="cuda"),
+                                         w.seed, w.first_step, 0, w.grad_std)]
+        else:
+            grads = dgen.workload_gradients(w, w.first_step)
         g = ps.make_grads([t.data_ptr() for t in grads], dt)
+        if k_mb > 1:
+            accum = torch.empty(n, dtype=torch.float32, device="cuda")
+            gacc = ps.make_grads([accum.data_ptr()], ps.PS_F32)
         launches_per_step = 1
         elems_per_launch = cost.valid_len
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
@@ -147,6 +161,11 @@ def main():
                     ss = float(ssd.item())      # the one device->host sync of a clipped step
                     coef = ps.ps_clip_coef(ss, 5.0 * ss, w.max_grad_norm)   # five iid peer shards
                     ps.ps_step_update(spec, hp(coef, 1.0), shard, gred, 0, n, s)
+                elif k_mb > 1:
+                    for j in range(k_mb):   # the same resident contributions stand for each micro-batch
+                        ps.ps_step_accumulate(spec, g, accum.data_ptr(), j == 0, 0, n,
+                                              cost.valid_len, s)
+                    ps.ps_step_update(spec, hp(0.0, 1.0 / (N * k_mb)), shard, gacc, 0, n, s)
                 else:
                     ps.ps_step_update(spec, hp(), shard, g, 0, n, s)
                 if record:
@@ -238,7 +257,9 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBS,
                      "traffic": measured_traffic(w, elems_per_launch),
-                     "kernel": "update_tiles" if not clip else "reduce_sumsq_tiles+update_tiles",
+                     "kernel": ("reduce_sumsq_tiles+update_tiles" if clip else
+                                "accumulate_tiles x%d + update_tiles" % w.micro_batches
+                                if w.micro_batches > 1 else "update_tiles"),
                      "elems_per_launch": elems_per_launch, "avg_launch_ms": avg_ms,
                      "launches_timed": len(kernel_ms)},
         "extras": extras,

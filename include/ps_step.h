@@ -227,10 +227,17 @@ ps_status_t ps_device_info(ps_device_info_t *info);
  * each line one correctly rounded binary32 operation.  State pointers in *shard
  * are shard-based (element 0 of the shard); grads->contrib[r] points at element
  * elem_offset of contribution r.  Only elements below shard->valid_len are read
- * or written.  Requires omega == PS_S, grad == PS_S, theta in {PS_R, PS_SG};
- * n_contrib == n_devices, or 1 with PS_F32 for a gradient reduced beforehand.
- * elem_offset must be a multiple of 8.  Deterministic: no atomics, results do
- * not depend on launch shape (Theorem 5, assumption 1). */
+ * or written.  Placements executed (rows of Table 2):
+ *   ZeRO-2 / ZeRO-3 (omega S, grad S, theta R or S*): n_contrib == n_devices, or
+ *     1 with PS_F32 for a gradient reduced (or accumulated) beforehand;
+ *   ZeRO-1 (omega S, grad R, theta R): the gradient has already been all-reduced
+ *     into one full-length replicated buffer (psi_padded elements, PS_BF16 or
+ *     PS_F32); n_contrib == 1, contrib[0] points at element 0 of that buffer and
+ *     the library reads this shard's slice at shard_offset, as it writes the
+ *     parameters' slice.  grad_scale <= 0 still means 1/N: the all-reduce sums.
+ * Anything else: PS_EUNSUPPORTED.  elem_offset must be a multiple of 8.
+ * Deterministic: no atomics, results do not depend on launch shape (Theorem 5,
+ * assumption 1). */
 ps_status_t ps_step_update(const ps_spec_t *spec, const ps_adamw_t *hp,
                            const ps_shard_t *shard, const ps_grads_t *grads,
                            uint64_t elem_offset, uint64_t elem_count, void *stream);
@@ -240,6 +247,18 @@ ps_status_t ps_step_update(const ps_spec_t *spec, const ps_adamw_t *hp,
  * host wait (unless plan->kernel_ms asks for timings). */
 ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
                                     const ps_shard_t *shard, const ps_bucket_plan_t *plan);
+
+/* Gradient accumulation (Limitations: several micro-batches per synchronisation,
+ * communication amortised by their number).  Adds one micro-batch to this
+ * shard's FP32 accumulator: accum[e] = accum[e] + ((g_0[e] + g_1[e]) + ...), the
+ * contributions summed first in the fixed order, each `+` one binary32
+ * operation; overwrite != 0 stores the sum instead (first micro-batch).  accum
+ * is DEVICE, shard-based, 16-byte aligned; contrib[r] points at element
+ * elem_offset.  After k micro-batches pass accum to ps_step_update as a single
+ * PS_F32 contribution with grad_scale = 1 / (N k).  Requires omega S, grad S. */
+ps_status_t ps_step_accumulate(const ps_spec_t *spec, const ps_grads_t *grads, float *accum,
+                               int32_t overwrite, uint64_t elem_offset, uint64_t elem_count,
+                               uint64_t valid_len, void *stream);
 
 /* Bytes of DEVICE workspace ps_step_reduce_sumsq needs for a call over
  * elem_count elements (about elem_count / 128 bytes; host-only query). */

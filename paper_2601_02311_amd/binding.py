@@ -21,7 +21,8 @@ __all__ = [
     "ps_bucket_plan_t", "ps_device_info_t", "library", "library_path",
     "ps_abi_version", "ps_status_string", "ps_last_error", "ps_spec_preset", "ps_cost_eval",
     "ps_device_info", "ps_step_update", "ps_step_update_bucketed", "ps_workspace_bytes",
-    "ps_step_reduce_sumsq", "ps_probe_copy", "ps_clip_coef", "EXPORTED_SYMBOLS",
+    "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
+    "EXPORTED_SYMBOLS",
 ]
 
 PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
@@ -34,7 +35,7 @@ PS_MAX_CONTRIB = 16
 EXPORTED_SYMBOLS = (
     "ps_abi_version", "ps_status_string", "ps_last_error", "ps_spec_preset", "ps_cost_eval",
     "ps_device_info", "ps_step_update", "ps_step_update_bucketed", "ps_workspace_bytes",
-    "ps_step_reduce_sumsq", "ps_probe_copy", "ps_clip_coef",
+    "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
 )
 
 
@@ -138,6 +139,10 @@ def library():
                                            C.c_double, C.c_void_p, C.c_void_p, C.c_int32,
                                            C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint64,
                                            C.c_uint64, C.c_void_p]
+        L.ps_step_accumulate.restype = C.c_int
+        L.ps_step_accumulate.argtypes = [C.POINTER(ps_spec_t), C.POINTER(ps_grads_t), C.c_void_p,
+                                         C.c_int32, C.c_uint64, C.c_uint64, C.c_uint64,
+                                         C.c_void_p]
         L.ps_probe_copy.restype = C.c_int
         L.ps_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
         if L.ps_abi_version() != 1:
@@ -226,6 +231,12 @@ def ps_step_reduce_sumsq(spec, grads, grad_scale, reduced_out, sumsq_out, accumu
                                           reduced_out or None, sumsq_out or None,
                                           int(accumulate), workspace or None, workspace_bytes,
                                           elem_offset, elem_count, valid_len, stream or None))
+
+
+def ps_step_accumulate(spec, grads, accum, overwrite, elem_offset, elem_count, valid_len,
+                       stream=0):
+    _check(library().ps_step_accumulate(_ref(spec), _ref(grads), accum or None, int(overwrite),
+                                        elem_offset, elem_count, valid_len, stream or None))
 
 
 def ps_probe_copy(dst, src, nbytes, stream=0):

@@ -44,6 +44,8 @@ int launch_update(int dtype, uint32_t n_contrib, const ContribPtrs &g, float *ma
 int launch_reduce_sumsq(int dtype, uint32_t n_contrib, const ContribPtrs &g, float gs,
                         float *reduced_out, uint64_t count, double *partials,
                         double *sumsq_out, int accumulate, void *stream);
+int launch_accumulate(int dtype, uint32_t n_contrib, const ContribPtrs &g, float *accum,
+                      int overwrite, uint64_t count, void *stream);
 int launch_copy(void *dst, const void *src, uint64_t bytes, void *stream);
 // Stage one bucket: for each contribution r copy n_vec 16-byte vectors to
 // dst + r * slot_stride_bytes from src.p[r], starting at vector first_vec of the

@@ -209,6 +209,59 @@ __global__ __launch_bounds__(kWave) void update_tail(const UpdateArgs a)
     a.out[e] = (uint16_t)narrow_bf16(th);
 }
 
+struct AccumArgs {
+    ContribPtrs g;
+    float *accum;
+    uint64_t n_tiles; // whole tiles (tile kernel) or element count (tail kernel)
+    uint32_t n_contrib;
+    uint32_t overwrite; // first micro-batch: store the sum instead of adding it
+};
+
+// Gradient accumulation: accum (+)= fixed-order sum of one micro-batch's
+// contributions.  Same launch shape as the update.
+template <int N, typename G, bool OVERWRITE>
+__global__ __launch_bounds__(kWave) void accumulate_tiles(const AccumArgs a)
+{
+    const uint32_t n = N ? N : a.n_contrib;
+    for (uint64_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
+        const uint64_t e = tile * kTileElems + (uint64_t)threadIdx.x * 4;
+        f32x4 acc, run;
+        if constexpr (N != 0) {
+            f32x4 gr[N];
+#pragma unroll
+            for (int r = 0; r < N; ++r)
+                gr[r] = load_contrib4<G, true>(a.g.p[r], e);
+            if constexpr (!OVERWRITE)
+                run = load_vec<true>(reinterpret_cast<const f32x4 *>(a.accum + e));
+            acc = gr[0];
+#pragma unroll
+            for (int r = 1; r < N; ++r)
+                acc = acc + gr[r];
+        } else {
+            if constexpr (!OVERWRITE)
+                run = load_vec<true>(reinterpret_cast<const f32x4 *>(a.accum + e));
+            acc = load_contrib4<G, true>(a.g.p[0], e);
+            for (uint32_t r = 1; r < n; ++r)
+                acc = acc + load_contrib4<G, true>(a.g.p[r], e);
+        }
+        if constexpr (!OVERWRITE)
+            acc = run + acc;
+        store_vec<true>(reinterpret_cast<f32x4 *>(a.accum + e), acc);
+    }
+}
+
+template <typename G>
+__global__ __launch_bounds__(kWave) void accumulate_tail(const AccumArgs a)
+{
+    const uint64_t e = (uint64_t)blockIdx.x * kWave + threadIdx.x;
+    if (e >= a.n_tiles)
+        return;
+    float acc = load_contrib1<G>(a.g.p[0], e);
+    for (uint32_t r = 1; r < a.n_contrib; ++r)
+        acc = acc + load_contrib1<G>(a.g.p[r], e);
+    a.accum[e] = a.overwrite ? acc : a.accum[e] + acc;
+}
+
 // ---- sum of squares: the only place that needs cross-lane traffic ----
 
 // Butterfly over the 64 lanes; every lane ends with the same bits.

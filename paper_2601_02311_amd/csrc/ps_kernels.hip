@@ -95,6 +95,65 @@ int launch_update(int dtype, uint32_t n_contrib, const ContribPtrs &g, float *ma
     return launch_update_t<float>(n_contrib, g, master, m, v, out, count, s, st);
 }
 
+template <int N, typename G>
+static void launch_accum_n(const AccumArgs &a, uint32_t grid, hipStream_t st)
+{
+    if (a.overwrite)
+        hipLaunchKernelGGL((accumulate_tiles<N, G, true>), dim3(grid), dim3(kWave), kUpdateLdsBytes, st, a);
+    else
+        hipLaunchKernelGGL((accumulate_tiles<N, G, false>), dim3(grid), dim3(kWave), kUpdateLdsBytes, st, a);
+}
+
+template <typename G>
+static int launch_accum_t(uint32_t n_contrib, const ContribPtrs &g, float *accum, int overwrite,
+                          uint64_t count, hipStream_t st)
+{
+    const uint64_t n_tiles = count / kTileElems;
+    const uint64_t body = n_tiles * kTileElems;
+    AccumArgs a;
+    a.g = g;
+    a.accum = accum;
+    a.n_contrib = n_contrib;
+    a.overwrite = overwrite ? 1u : 0u;
+    if (n_tiles) {
+        a.n_tiles = n_tiles;
+        const uint32_t grid = grid_for(n_tiles);
+        switch (n_contrib) {
+        case 1: launch_accum_n<1, G>(a, grid, st); break;
+        case 2: launch_accum_n<2, G>(a, grid, st); break;
+        case 4: launch_accum_n<4, G>(a, grid, st); break;
+        case 6: launch_accum_n<6, G>(a, grid, st); break;
+        case 8: launch_accum_n<8, G>(a, grid, st); break;
+        default: launch_accum_n<0, G>(a, grid, st); break;
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return (int)e;
+    }
+    if (count > body) {
+        const uint64_t rest = count - body;
+        for (uint32_t r = 0; r < n_contrib; ++r)
+            a.g.p[r] = advance<G>(g.p[r], body);
+        a.accum = accum + body;
+        a.n_tiles = rest;
+        hipLaunchKernelGGL((accumulate_tail<G>), dim3((uint32_t)((rest + kWave - 1) / kWave)),
+                           dim3(kWave), 0, st, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return (int)e;
+    }
+    return 0;
+}
+
+int launch_accumulate(int dtype, uint32_t n_contrib, const ContribPtrs &g, float *accum,
+                      int overwrite, uint64_t count, void *stream)
+{
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (dtype == PS_BF16)
+        return launch_accum_t<uint16_t>(n_contrib, g, accum, overwrite, count, st);
+    return launch_accum_t<float>(n_contrib, g, accum, overwrite, count, st);
+}
+
 static uint64_t reduce_groups(uint64_t count)
 {
     const uint64_t n_tiles = count / kTileElems;

@@ -81,21 +81,30 @@ ps_status_t check_hp(const ps_adamw_t *hp)
     return PS_OK;
 }
 
-// The placements this path executes: Omega and G sharded, Theta R or S*.
+// The placements this path executes: Omega sharded; G sharded with Theta R or S*
+// (ZeRO-2, ZeRO-3), or G and Theta both replicated (ZeRO-1).
+bool is_zero1(const ps_spec_t *spec)
+{
+    return spec->omega == PS_S && spec->grad == PS_R && spec->theta == PS_R;
+}
+
 ps_status_t check_path(const ps_spec_t *spec)
 {
     ps_status_t st = check_spec(spec);
     if (st != PS_OK)
         return st;
-    if (spec->omega != PS_S || spec->grad != PS_S || (spec->theta != PS_R && spec->theta != PS_SG)) {
-        set_error("step needs pi_Omega = S, pi_G = S and pi_Theta in {R, S*}");
+    const bool sharded_g = spec->omega == PS_S && spec->grad == PS_S &&
+                           (spec->theta == PS_R || spec->theta == PS_SG);
+    if (!sharded_g && !is_zero1(spec)) {
+        set_error("step needs pi_Omega = S with (pi_G = S, pi_Theta in {R, S*}) or "
+                  "(pi_G = R, pi_Theta = R)");
         return PS_EUNSUPPORTED;
     }
     return PS_OK;
 }
 
 ps_status_t check_contribs(const void *const *ptrs, uint32_t n_contrib, int32_t dtype,
-                           uint32_t n_devices, const char *what)
+                           uint32_t n_devices, const char *what, bool replicated_grad = false)
 {
     if (!ptrs) {
         set_error("%s pointer array is NULL", what);
@@ -109,7 +118,13 @@ ps_status_t check_contribs(const void *const *ptrs, uint32_t n_contrib, int32_t 
         set_error("%s count %u outside [1, %u]", what, n_contrib, PS_MAX_CONTRIB);
         return PS_ERANGE;
     }
-    if (!(n_contrib == n_devices || (n_contrib == 1 && dtype == PS_F32))) {
+    if (replicated_grad) {
+        if (n_contrib != 1) {
+            set_error("%s count %u: under pi_G = R the gradient is one all-reduced buffer", what,
+                      n_contrib);
+            return PS_EINVAL;
+        }
+    } else if (!(n_contrib == n_devices || (n_contrib == 1 && dtype == PS_F32))) {
         set_error("%s count %u: want n_devices = %u contributions (a missing or extra one "
                   "breaks gradient integrity), or one pre-reduced PS_F32 gradient",
                   what, n_contrib, n_devices);
@@ -246,8 +261,9 @@ ps_status_t ps_step_update(const ps_spec_t *spec, const ps_adamw_t *hp, const ps
         set_error("grads is NULL");
         return PS_EINVAL;
     }
+    const bool z1 = is_zero1(spec);
     if ((st = check_contribs(grads->contrib, grads->n_contrib, grads->dtype, spec->n_devices,
-                             "contribution")) != PS_OK ||
+                             "contribution", z1)) != PS_OK ||
         (st = check_range(elem_offset, elem_count, shard->len)) != PS_OK)
         return st;
     const uint64_t count = clamp_count(elem_offset, elem_count, shard->valid_len);
@@ -261,11 +277,62 @@ ps_status_t ps_step_update(const ps_spec_t *spec, const ps_adamw_t *hp, const ps
     std::memset(&g, 0, sizeof g);
     for (uint32_t r = 0; r < grads->n_contrib; ++r)
         g.p[r] = grads->contrib[r];
+    if (z1) // the replicated gradient is full length: this shard's slice starts at its offset
+        g.p[0] = reinterpret_cast<const char *>(g.p[0]) +
+                 (out_off + elem_offset) * elem_bytes(grads->dtype);
     uint16_t *out = reinterpret_cast<uint16_t *>(shard->gather_out) + out_off + elem_offset;
     int e = launch_update(grads->dtype, grads->n_contrib, g, shard->master + elem_offset,
                           shard->m + elem_offset, shard->v + elem_offset, out, count, s, stream);
     if (e != 0)
         return hip_fail((hipError_t)e, "update kernel launch");
+    return PS_OK;
+}
+
+ps_status_t ps_step_accumulate(const ps_spec_t *spec, const ps_grads_t *grads, float *accum,
+                               int32_t overwrite, uint64_t elem_offset, uint64_t elem_count,
+                               uint64_t valid_len, void *stream)
+{
+    clear_error();
+    ps_status_t st;
+    if ((st = check_path(spec)) != PS_OK)
+        return st;
+    if (is_zero1(spec)) {
+        set_error("accumulation reduces pi_G = S contributions; under pi_G = R the "
+                  "all-reduce has already done it");
+        return PS_EUNSUPPORTED;
+    }
+    if (!grads || !accum) {
+        set_error("grads or accum is NULL");
+        return PS_EINVAL;
+    }
+    if (!aligned16(accum)) {
+        set_error("accum is not 16-byte aligned");
+        return PS_EALIGN;
+    }
+    if ((st = check_contribs(grads->contrib, grads->n_contrib, grads->dtype, spec->n_devices,
+                             "contribution")) != PS_OK)
+        return st;
+    uint64_t padded, off, len, valid;
+    if ((st = shard_geometry(spec, &padded, &off, &len, &valid)) != PS_OK ||
+        (st = check_range(elem_offset, elem_count, len)) != PS_OK)
+        return st;
+    if (valid_len > len) {
+        set_error("valid_len exceeds the shard length");
+        return PS_ERANGE;
+    }
+    const uint64_t count = clamp_count(elem_offset, elem_count, valid_len);
+    if (count == 0)
+        return PS_OK;
+    if ((st = need_device()) != PS_OK)
+        return st;
+    ContribPtrs g;
+    std::memset(&g, 0, sizeof g);
+    for (uint32_t r = 0; r < grads->n_contrib; ++r)
+        g.p[r] = grads->contrib[r];
+    int e = launch_accumulate(grads->dtype, grads->n_contrib, g, accum + elem_offset, overwrite,
+                              count, stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "accumulate kernel launch");
     return PS_OK;
 }
 
@@ -284,6 +351,10 @@ ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
     ps_status_t st;
     if ((st = check_path(spec)) != PS_OK)
         return st;
+    if (is_zero1(spec) && grads && grads->n_contrib != 1) {
+        set_error("under pi_G = R the gradient is one all-reduced buffer");
+        return PS_EINVAL;
+    }
     if (!grads || !sumsq_out || !workspace) {
         set_error("grads, sumsq_out or workspace is NULL");
         return PS_EINVAL;
@@ -303,8 +374,9 @@ ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
         set_error("workspace, sumsq_out or reduced_out is misaligned");
         return PS_EALIGN;
     }
+    const bool z1 = is_zero1(spec);
     if ((st = check_contribs(grads->contrib, grads->n_contrib, grads->dtype, spec->n_devices,
-                             "contribution")) != PS_OK)
+                             "contribution", z1)) != PS_OK)
         return st;
     uint64_t padded, off, len, valid;
     if ((st = shard_geometry(spec, &padded, &off, &len, &valid)) != PS_OK ||
@@ -313,6 +385,11 @@ ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
     if (valid_len > len) {
         set_error("valid_len exceeds the shard length");
         return PS_ERANGE;
+    }
+    if (z1 && off % 8 != 0) {
+        set_error("shard offset %llu into the replicated gradient is not a multiple of 8",
+                  (unsigned long long)off);
+        return PS_EALIGN;
     }
     if ((st = need_device()) != PS_OK)
         return st;
@@ -323,6 +400,9 @@ ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
     std::memset(&g, 0, sizeof g);
     for (uint32_t r = 0; r < grads->n_contrib; ++r)
         g.p[r] = grads->contrib[r];
+    if (z1)
+        g.p[0] = reinterpret_cast<const char *>(g.p[0]) +
+                 (off + elem_offset) * elem_bytes(grads->dtype);
     int e = launch_reduce_sumsq(grads->dtype, grads->n_contrib, g, gs,
                                 reduced_out ? reduced_out + elem_offset : nullptr, count,
                                 reinterpret_cast<double *>(workspace), sumsq_out, accumulate,
@@ -345,6 +425,10 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
     if (!plan) {
         set_error("plan is NULL");
         return PS_EINVAL;
+    }
+    if (is_zero1(spec)) {
+        set_error("the bucket pipeline stages pi_G = S contributions");
+        return PS_EUNSUPPORTED;
     }
     if ((st = check_contribs(plan->source, plan->n_contrib, plan->dtype, spec->n_devices,
                              "bucket source")) != PS_OK)

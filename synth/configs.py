@@ -31,6 +31,7 @@ class Workload:
     student_t_dof: int = 0          # >0: gradients are grad_std * Student-t(dof)
     bucket_elems: int = 0           # >0: gradients arrive in buckets of this many elements
     max_grad_norm: float = 0.0      # >0: global-norm clipping
+    micro_batches: int = 1          # >1: gradient accumulation over this many micro-batches
     seed: int = 20260102
     extra: dict = field(default_factory=dict)
 
@@ -68,6 +69,15 @@ WORKLOADS = {
     "70b_zero3": Workload("70b_zero3", psi=70_000_000_000, n_devices=8, shard_index=7,
                           strategy="zero3", grad_dtype="bf16", first_step=1000,
                           warm_moments=True, grad_std=1e-4, bucket_elems=1 << 28),
+    # The other data-parallel rows of the paper's Table 2 on the 7B shard: ZeRO-1 (the
+    # gradient arrives all-reduced, one replicated full-length buffer) and gradient
+    # accumulation over four micro-batches before one ZeRO-2 update.
+    "7b_zero1": Workload("7b_zero1", psi=6_738_415_616, n_devices=8, shard_index=0,
+                         strategy="zero1", grad_dtype="bf16", first_step=1000,
+                         warm_moments=True, grad_std=8e-4),
+    "7b_accum4": Workload("7b_accum4", psi=6_738_415_616, n_devices=8, shard_index=0,
+                          strategy="zero2", grad_dtype="bf16", first_step=1000,
+                          warm_moments=True, grad_std=1e-4, micro_batches=4),
     # Ragged 13B FSDP-style shard, fp32 heavy-tailed gradients, global-norm clip.
     # psi is already a multiple of 6*256; "psi_ragged" drops 1001 elements so that
     # the last shard owns a pad of 1001 elements that must stay untouched.

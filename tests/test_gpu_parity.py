@@ -368,6 +368,71 @@ def test_bucketed_step_with_a_repeating_source_pool(dtype, engine, pool):
     assert assert_state_parity(got, want, "pool") == 0
 
 
+# ---- the other data-parallel rows: ZeRO-1 and gradient accumulation ----
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_zero1_replicated_gradient_slice(dtype):
+    """ZeRO-1: the gradient is one all-reduced, full-length replicated buffer; device i
+    updates its Omega shard from slice i and writes slice i of the replicated parameters."""
+    n, N, i = 4 * TILE + 264, 4, 2
+    _say("zero1 n=%d shard %d of %d, %s" % (n, i, N, dtype))
+    spec = ps.ps_spec_preset("zero1", N, i, n * N)
+    c = ps.ps_cost_eval(spec)
+    g_full = gen.gradient(n * N, 81, 0, 0, dtype, std=4e-3)          # stands for the all-reduced sum
+    state = [gen.master(n, 81), *gen.moments(n, 81, True), np.zeros(n, np.uint16)]
+    hpd, hp = hp_of(None, 9)
+    want = [a.copy() for a in state]
+    sl = slice(c.shard_offset, c.shard_offset + n)
+    orc.step_f32([np.ascontiguousarray(g_full[sl])], orc.derive_scalars(t=9, n_devices=N, **hpd), *want)
+    th, m, v = [dev(a) for a in state[:3]]
+    full_p = dev(np.full(n * N, 0x7777, np.uint16))
+    gd = dev(g_full)
+    before = host(gd).copy()
+    ps.ps_step_update(spec, hp, shard_of(th, m, v, full_p, n), grads_of([gd], dtype), 0, n,
+                      stream_handle())
+    torch.cuda.synchronize()
+    p = host(full_p)
+    got = [host(th), host(m), host(v), p[sl]]
+    assert assert_state_parity(got, want, "zero1") == 0
+    assert (p[:c.shard_offset] == 0x7777).all() and (p[c.shard_offset + n:] == 0x7777).all()
+    assert np.array_equal(host(gd).view(np.uint8), before.view(np.uint8))
+
+
+@pytest.mark.parametrize("dtype,N", [("bf16", 8), ("f32", 6), ("bf16", 3)])
+def test_gradient_accumulation_then_update(dtype, N):
+    """k micro-batches accumulate into the FP32 shard (fixed order inside a micro-batch,
+    micro-batches in arrival order), then one update with grad_scale = 1/(N k)."""
+    n, k = 6 * TILE + 250 + 5, 4
+    valid = n - 3
+    _say("accumulate k=%d n=%d valid=%d N=%d %s" % (k, n, valid, N, dtype))
+    spec = ps.ps_spec_preset("zero3", N, 1, n * N)
+    acc_want = np.full(n, np.float32(7.0))
+    acc_dev = dev(acc_want.copy())
+    for j in range(k):
+        grads = [gen.gradient(n, 83, j, r, dtype, std=1e-3) for r in range(N)]
+        orc.accumulate(grads, acc_want, overwrite=(j == 0), lo=0, hi=valid)
+        gd = [dev(g) for g in grads]
+        # two calls per micro-batch: the range may arrive in pieces
+        cut = 3 * TILE + 8
+        ps.ps_step_accumulate(spec, grads_of(gd, dtype), acc_dev.data_ptr(), j == 0, 0, cut, valid,
+                              stream_handle())
+        ps.ps_step_accumulate(spec, grads_of(gd, dtype, cut), acc_dev.data_ptr(), j == 0, cut,
+                              n - cut, valid, stream_handle())
+        torch.cuda.synchronize()
+    assert np.array_equal(host(acc_dev).view(np.uint32), acc_want.view(np.uint32))   # pad (7.0) included
+    state = [gen.master(n, 83), *gen.moments(n, 83, True), np.zeros(n, np.uint16)]
+    scale = 1.0 / (N * k)
+    hpd, hp = hp_of(None, 21, grad_scale=scale)
+    want = [a.copy() for a in state]
+    orc.step_f32([acc_want], orc.derive_scalars(t=21, n_devices=N, grad_scale=scale, **hpd), *want,
+                 lo=0, hi=valid)
+    th, m, v, p = [dev(a) for a in state]
+    ps.ps_step_update(spec, hp, shard_of(th, m, v, p, n, valid), grads_of([acc_dev], "f32"), 0, n,
+                      stream_handle())
+    torch.cuda.synchronize()
+    assert assert_state_parity([host(x) for x in (th, m, v, p)], want, "accumulated") == 0
+
+
 # ---- memory safety and statelessness ----
 
 GUARD = 4096  # bytes of guard band on each side of every device buffer

@@ -34,7 +34,7 @@ def test_update_rejects_bad_arguments():
     assert _status(lambda: upd(spec, hp, None, grads, 0, 8)) == ps.PS_EINVAL
     assert _status(lambda: upd(spec, hp, shard, None, 0, 8)) == ps.PS_EINVAL
     # placements this path does not execute
-    for name in ("dp", "zero1", "zero_offload", "tp"):
+    for name in ("dp", "zero_offload", "tp"):
         other = ps.ps_spec_preset(name, 4, 1, 4096)
         assert _status(lambda: upd(other, hp, shard, grads, 0, 8)) == ps.PS_EUNSUPPORTED
     # step count, betas
@@ -82,6 +82,36 @@ def test_update_rejects_integrity_violations():
     spec17 = ps.ps_spec_preset("zero3", 17, 0, 17 * 1024)
     many = ps.make_grads([FAKE] * 17, ps.PS_BF16)
     assert _status(lambda: upd(spec17, hp, shard, many, 0, 8)) == ps.PS_ERANGE
+
+
+def test_zero1_takes_one_replicated_gradient():
+    spec = ps.ps_spec_preset("zero1", 4, 1, 4096)
+    _, hp, shard, grads4 = _valid()
+    upd = ps.ps_step_update
+    assert _status(lambda: upd(spec, hp, shard, grads4, 0, 8)) == ps.PS_EINVAL      # N buffers: no
+    two = ps.make_grads([FAKE, FAKE], ps.PS_BF16)
+    assert _status(lambda: upd(spec, hp, shard, two, 0, 8)) == ps.PS_EINVAL
+    one = ps.make_grads([FAKE], ps.PS_BF16)
+    upd(spec, hp, shard, one, 0, 0)                                                  # valid, empty
+    assert _status(lambda: ps.ps_step_accumulate(spec, one, FAKE, 1, 0, 8, 1024)) == ps.PS_EUNSUPPORTED
+    plan = ps.ps_bucket_plan_t()
+    assert _status(lambda: ps.ps_step_update_bucketed(spec, hp, shard, plan)) == ps.PS_EUNSUPPORTED
+
+
+def test_accumulate_rejects_bad_arguments():
+    spec, _, _, grads = _valid()
+    acc = ps.ps_step_accumulate
+    assert _status(lambda: acc(None, grads, FAKE, 1, 0, 8, 1024)) == ps.PS_EINVAL
+    assert _status(lambda: acc(spec, None, FAKE, 1, 0, 8, 1024)) == ps.PS_EINVAL
+    assert _status(lambda: acc(spec, grads, 0, 1, 0, 8, 1024)) == ps.PS_EINVAL
+    assert _status(lambda: acc(spec, grads, FAKE + 4, 1, 0, 8, 1024)) == ps.PS_EALIGN
+    assert _status(lambda: acc(spec, grads, FAKE, 1, 4, 8, 1024)) == ps.PS_EALIGN
+    assert _status(lambda: acc(spec, grads, FAKE, 1, 1024, 8, 1024)) == ps.PS_ERANGE
+    assert _status(lambda: acc(spec, grads, FAKE, 1, 0, 8, 1025)) == ps.PS_ERANGE
+    missing = ps.make_grads([FAKE] * 3, ps.PS_BF16)
+    assert _status(lambda: acc(spec, missing, FAKE, 1, 0, 8, 1024)) == ps.PS_EINVAL
+    acc(spec, grads, FAKE, 1, 0, 0, 1024)                                            # empty range
+    acc(spec, grads, FAKE, 1, 512, 512, 512)                                         # all padding
 
 
 def test_zero2_output_offset_must_keep_alignment():
