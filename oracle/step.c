@@ -238,3 +238,43 @@ void oracle_step_f64(const void *const *g, uint32_t n_contrib, int is_f32,
         theta_out[e] = th;
     }
 }
+
+/* ---- verification protocol (Section 7.1: gradient integrity check, identical
+ * checksums after a collective) ---- */
+
+/* Sums for the relative gradient difference ||a - b|| / ||a||: out[0] = sum of
+ * (a-b)^2, out[1] = sum of a^2, both sequential in binary64 (the difference of
+ * two widened 16- or 32-bit values is exact in binary64). */
+void oracle_diff_sumsq(const void *a, const void *b, int is_f32, uint64_t lo,
+                       uint64_t hi, double *out)
+{
+    const void *pa[1] = {a}, *pb[1] = {b};
+    double sd = 0.0, sa = 0.0;
+    for (uint64_t e = lo; e < hi; ++e) {
+        double x = (double)contribution(pa, is_f32, 0, e);
+        double y = (double)contribution(pb, is_f32, 0, e);
+        double d = x - y;
+        sd += d * d;
+        sa += x * x;
+    }
+    out[0] = sd;
+    out[1] = sa;
+}
+
+/* Position-sensitive 64-bit checksum of a buffer of 8-byte words: word i (index
+ * counted from first_index) contributes the splitmix64 output function
+ * (Steele, Lea, Flood 2014) of w_i + (i+1) * 0x9E3779B97F4A7C15; the contributions
+ * are added modulo 2^64, so any summation order gives the same value and
+ * checksums of consecutive pieces add up. */
+uint64_t oracle_checksum(const uint64_t *w, uint64_t n_words, uint64_t first_index)
+{
+    uint64_t c = 0;
+    for (uint64_t i = 0; i < n_words; ++i) {
+        uint64_t z = w[i] + (first_index + i + 1) * 0x9E3779B97F4A7C15ull;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        z = z ^ (z >> 31);
+        c += z;
+    }
+    return c;
+}

@@ -46,6 +46,11 @@ def lib():
         L.oracle_accumulate.restype = None
         L.oracle_accumulate.argtypes = [pp, C.c_uint32, C.c_int, C.c_void_p, C.c_int,
                                         C.c_uint64, C.c_uint64]
+        L.oracle_diff_sumsq.restype = None
+        L.oracle_diff_sumsq.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_uint64, C.c_uint64,
+                                        C.POINTER(C.c_double)]
+        L.oracle_checksum.restype = C.c_uint64
+        L.oracle_checksum.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64]
         L.oracle_mean_sumsq.restype = C.c_double
         L.oracle_mean_sumsq.argtypes = [pp, C.c_uint32, C.c_int, C.c_float, C.c_void_p,
                                         C.c_uint64, C.c_uint64]
@@ -162,3 +167,20 @@ def step_f64(grads, lr, beta1, beta2, eps, weight_decay, t, theta, m, v,
                           m.ctypes.data, v.ctypes.data, to.ctypes.data, mo.ctypes.data,
                           vo.ctypes.data, lo, hi)
     return to, mo, vo
+
+
+def diff_sumsq(a, b, lo=0, hi=None):
+    """(sum (a-b)^2, sum a^2) over [lo, hi), sequential binary64."""
+    ptrs, _, is_f32, n = _contrib_ptrs([a, b])
+    hi = n if hi is None else hi
+    out = (C.c_double * 2)()
+    lib().oracle_diff_sumsq(a.ctypes.data, b.ctypes.data, is_f32, lo, hi, out)
+    return out[0], out[1]
+
+
+def checksum(buf, first_index=0):
+    """Checksum of a contiguous array whose byte length is a multiple of 8."""
+    raw = np.ascontiguousarray(buf).view(np.uint8)
+    if raw.shape[0] % 8:
+        raise ValueError("byte length must be a multiple of 8")
+    return lib().oracle_checksum(raw.ctypes.data, raw.shape[0] // 8, int(first_index))

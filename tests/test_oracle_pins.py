@@ -406,3 +406,64 @@ def test_state_consistency_all_shards_equal_unsharded():
         cat = np.concatenate([sh[k] for sh in shards])
         assert np.array_equal(cat.view(np.uint8), full[k].view(np.uint8))
     assert np.abs(full[0] - gen.master(psi, w.seed)).max() > 1e-5   # it did move
+
+
+# --------------------------------------------------------------------------
+# verification protocol
+# --------------------------------------------------------------------------
+
+def test_checksum_against_published_vectors_and_brute_force(golden):
+    M = (1 << 64) - 1
+    outs = [int(golden["splitmix64_seed0_out%d" % k], 16) for k in (1, 2, 3)]
+    # an all-zero buffer: word i contributes output i+1 of the generator seeded with 0
+    assert orc.checksum(np.zeros(1, np.uint64)) == outs[0]
+    assert orc.checksum(np.zeros(3, np.uint64)) == sum(outs) & M
+    assert orc.checksum(np.zeros(1, np.uint64), first_index=2) == outs[2]
+
+    def brute(words, first=0):
+        c = 0
+        for i, w in enumerate(words):
+            z = (int(w) + (first + i + 1) * 0x9E3779B97F4A7C15) & M
+            z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & M
+            z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & M
+            c = (c + (z ^ (z >> 31))) & M
+        return c
+    w = np.random.default_rng(3).integers(0, 2 ** 63, 257, dtype=np.uint64) * np.uint64(2) + np.uint64(1)
+    assert orc.checksum(w) == brute(w)
+    # pieces add up; position matters; one flipped bit shows
+    assert (orc.checksum(w[:100]) + orc.checksum(w[100:], first_index=100)) & M == orc.checksum(w)
+    sw = w.copy(); sw[[5, 9]] = sw[[9, 5]]
+    assert orc.checksum(sw) != orc.checksum(w)
+    fl = w.copy(); fl[77] ^= np.uint64(1 << 40)
+    assert orc.checksum(fl) != orc.checksum(w)
+    # any dtype by bytes
+    f = gen.master(1024, 5)
+    assert orc.checksum(f) == orc.checksum(f.view(np.uint64))
+    with pytest.raises(ValueError):
+        orc.checksum(np.zeros(3, np.uint16))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_relative_difference_sums(dtype):
+    import math
+    n = 5003
+    a = gen.gradient(n, 7, 0, 0, dtype, std=1e-2)
+    b = gen.gradient(n, 7, 0, 1, dtype, std=1e-2)
+    wid = lambda g: (g.astype(np.uint32) << 16).view(np.float32).astype(np.float64) if g.dtype == np.uint16 \
+        else g.astype(np.float64)
+    sd, sa = orc.diff_sumsq(a, b)
+    assert sd == pytest.approx(math.fsum((wid(a) - wid(b)) ** 2), rel=1e-13)
+    assert sa == pytest.approx(math.fsum(wid(a) ** 2), rel=1e-13)
+    assert orc.diff_sumsq(a, a) == (0.0, sa)
+    s1, s2 = orc.diff_sumsq(a, b, 0, 2000), orc.diff_sumsq(a, b, 2000, n)
+    assert s1[0] + s2[0] == pytest.approx(sd, rel=1e-14) and s1[1] + s2[1] == pytest.approx(sa, rel=1e-14)
+    # the paper's threshold: a reduction in another order stays far below 1e-5, a lost contribution does not
+    g = [gen.gradient(n, 8, 0, r, "f32") for r in range(8)]
+    fwd, rev, lost = orc.reduce_sum(g), orc.reduce_sum(g[::-1]), orc.reduce_sum(g[:-1])
+    rel = lambda x, y: math.sqrt(orc.diff_sumsq(x, y)[0] / orc.diff_sumsq(x, y)[1])
+    assert rel(fwd, rev) < float(load_tol()) and rel(fwd, lost) > float(load_tol())
+
+
+def load_tol():
+    from conftest import load_golden
+    return load_golden()["grad_check_rel_tol"]
