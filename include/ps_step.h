@@ -280,6 +280,33 @@ ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
                                  uint64_t workspace_bytes, uint64_t elem_offset,
                                  uint64_t elem_count, uint64_t valid_len, void *stream);
 
+/* ---- verification protocol (Section 7.1) ---- */
+
+/* Bytes of DEVICE workspace the two verification scans need for a buffer of
+ * buffer_bytes bytes (about buffer_bytes / 128; host-only query). */
+uint64_t ps_verify_workspace_bytes(uint64_t buffer_bytes);
+
+/* Gradient integrity check: writes out2[0] = sum (a-b)^2 and out2[1] = sum a^2
+ * over elem_count elements of the DEVICE buffers a and b (PS_BF16 or PS_F32,
+ * one type for both), accumulated in binary64 in a fixed tree (reproducible bit
+ * for bit).  The caller forms ||a-b|| / ||a|| = sqrt(out2[0] / out2[1]) and
+ * compares it with the protocol's 1e-5.  accumulate != 0 adds to the values
+ * already in out2 (DEVICE, two doubles). */
+ps_status_t ps_verify_diff_sumsq(const void *a, const void *b, int32_t dtype, uint64_t elem_count,
+                                 double *out2, int32_t accumulate, void *workspace,
+                                 uint64_t workspace_bytes, void *stream);
+
+/* State consistency check: a position-sensitive 64-bit checksum of `bytes` bytes
+ * (a multiple of 8) of a DEVICE buffer, for comparing copies across devices
+ * after a collective.  Word i (8 bytes, little endian, index first_word_index +
+ * i) contributes the splitmix64 output function of
+ * w_i + (index + 1) * 0x9E3779B97F4A7C15; contributions add modulo 2^64, so the
+ * value does not depend on summation order and checksums of consecutive pieces
+ * add up (accumulate != 0 adds to *out, DEVICE). */
+ps_status_t ps_verify_checksum(const void *buf, uint64_t bytes, uint64_t first_word_index,
+                               uint64_t *out, int32_t accumulate, void *workspace,
+                               uint64_t workspace_bytes, void *stream);
+
 /* Plain streaming copy of `bytes` bytes (multiple of 16) between DEVICE buffers
  * with the same launch shape as the update kernel.  A yardstick for achievable
  * HBM bandwidth and for calibrating hardware byte counters; not part of the

@@ -22,7 +22,7 @@ __all__ = [
     "ps_abi_version", "ps_status_string", "ps_last_error", "ps_spec_preset", "ps_cost_eval",
     "ps_device_info", "ps_step_update", "ps_step_update_bucketed", "ps_workspace_bytes",
     "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
-    "EXPORTED_SYMBOLS",
+    "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum", "EXPORTED_SYMBOLS",
 ]
 
 PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
@@ -36,6 +36,7 @@ EXPORTED_SYMBOLS = (
     "ps_abi_version", "ps_status_string", "ps_last_error", "ps_spec_preset", "ps_cost_eval",
     "ps_device_info", "ps_step_update", "ps_step_update_bucketed", "ps_workspace_bytes",
     "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
+    "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum",
 )
 
 
@@ -143,6 +144,15 @@ def library():
         L.ps_step_accumulate.argtypes = [C.POINTER(ps_spec_t), C.POINTER(ps_grads_t), C.c_void_p,
                                          C.c_int32, C.c_uint64, C.c_uint64, C.c_uint64,
                                          C.c_void_p]
+        L.ps_verify_workspace_bytes.restype = C.c_uint64
+        L.ps_verify_workspace_bytes.argtypes = [C.c_uint64]
+        L.ps_verify_diff_sumsq.restype = C.c_int
+        L.ps_verify_diff_sumsq.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_uint64,
+                                           C.c_void_p, C.c_int32, C.c_void_p, C.c_uint64,
+                                           C.c_void_p]
+        L.ps_verify_checksum.restype = C.c_int
+        L.ps_verify_checksum.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_int32,
+                                         C.c_void_p, C.c_uint64, C.c_void_p]
         L.ps_probe_copy.restype = C.c_int
         L.ps_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
         if L.ps_abi_version() != 1:
@@ -237,6 +247,24 @@ def ps_step_accumulate(spec, grads, accum, overwrite, elem_offset, elem_count, v
                        stream=0):
     _check(library().ps_step_accumulate(_ref(spec), _ref(grads), accum or None, int(overwrite),
                                         elem_offset, elem_count, valid_len, stream or None))
+
+
+def ps_verify_workspace_bytes(buffer_bytes):
+    return library().ps_verify_workspace_bytes(buffer_bytes)
+
+
+def ps_verify_diff_sumsq(a, b, dtype, elem_count, out2, accumulate, workspace, workspace_bytes,
+                         stream=0):
+    _check(library().ps_verify_diff_sumsq(a or None, b or None, dtype, elem_count, out2 or None,
+                                          int(accumulate), workspace or None, workspace_bytes,
+                                          stream or None))
+
+
+def ps_verify_checksum(buf, nbytes, first_word_index, out, accumulate, workspace, workspace_bytes,
+                       stream=0):
+    _check(library().ps_verify_checksum(buf or None, nbytes, first_word_index, out or None,
+                                        int(accumulate), workspace or None, workspace_bytes,
+                                        stream or None))
 
 
 def ps_probe_copy(dst, src, nbytes, stream=0):

@@ -46,6 +46,12 @@ int launch_reduce_sumsq(int dtype, uint32_t n_contrib, const ContribPtrs &g, flo
                         double *sumsq_out, int accumulate, void *stream);
 int launch_accumulate(int dtype, uint32_t n_contrib, const ContribPtrs &g, float *accum,
                       int overwrite, uint64_t count, void *stream);
+// Verification scans.  `slots` 8-byte slots of workspace as verify_workspace_slots() says.
+uint64_t verify_workspace_slots(uint64_t bytes);
+int launch_diff_sumsq(int dtype, const void *a, const void *b, uint64_t count, double *out2,
+                      int accumulate, void *workspace, uint64_t slots, void *stream);
+int launch_checksum(const void *buf, uint64_t n_words, uint64_t first_index, uint64_t *out,
+                    int accumulate, void *workspace, void *stream);
 int launch_copy(void *dst, const void *src, uint64_t bytes, void *stream);
 // Stage one bucket: for each contribution r copy n_vec 16-byte vectors to
 // dst + r * slot_stride_bytes from src.p[r], starting at vector first_vec of the

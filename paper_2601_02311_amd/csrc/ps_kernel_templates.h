@@ -265,7 +265,8 @@ __global__ __launch_bounds__(kWave) void accumulate_tail(const AccumArgs a)
 // ---- sum of squares: the only place that needs cross-lane traffic ----
 
 // Butterfly over the 64 lanes; every lane ends with the same bits.
-__device__ __forceinline__ double wave_sum(double x)
+template <typename T>
+__device__ __forceinline__ T wave_sum(T x)
 {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1)
@@ -275,14 +276,15 @@ __device__ __forceinline__ double wave_sum(double x)
 
 // Fixed-shape tree for a kThreads-wide workgroup: butterfly inside each wave,
 // then the wave sums through LDS, added in wave order.  Every lane must call it.
-__device__ __forceinline__ double block_sum(double x)
+template <typename T>
+__device__ __forceinline__ T block_sum(T x)
 {
-    __shared__ double partial[kThreads / 64];
+    __shared__ T partial[kThreads / 64];
     x = wave_sum(x);
     if ((threadIdx.x & 63) == 0)
         partial[threadIdx.x >> 6] = x;
     __syncthreads();
-    double t = partial[0];
+    T t = partial[0];
 #pragma unroll
     for (int w = 1; w < kThreads / 64; ++w)
         t += partial[w];
@@ -364,30 +366,128 @@ __global__ __launch_bounds__(kWave) void reduce_sumsq_tail(const ReduceArgs a)
 
 // First stage of the final sum: workgroup b adds the contiguous slice
 // [b*per, min((b+1)*per, n)) of `in` in a fixed order into out[b].
-__global__ __launch_bounds__(kThreads) void fold_partials(const double *in, uint64_t n,
-                                                          uint64_t per, double *out)
+template <typename T>
+__global__ __launch_bounds__(kThreads) void fold_partials(const T *in, uint64_t n, uint64_t per,
+                                                          T *out)
 {
     const uint64_t lo = (uint64_t)blockIdx.x * per;
     const uint64_t hi = lo + per < n ? lo + per : n;
-    double ss = 0.0;
+    T ss = 0;
     for (uint64_t i = lo + threadIdx.x; i < hi; i += kThreads)
         ss += in[i];
-    const double t = block_sum(ss);
+    const T t = block_sum(ss);
     if (threadIdx.x == 0)
         out[blockIdx.x] = t;
 }
 
 // Last stage: sum partials[0 .. n) in a fixed order (lane-strided, then the
 // block tree) and store the total, or add it to what *out already holds.
-__global__ __launch_bounds__(kThreads) void finalize_sumsq(const double *partials, uint32_t n,
-                                                          double *out, int accumulate)
+template <typename T>
+__global__ __launch_bounds__(kThreads) void finalize_sum(const T *partials, uint32_t n, T *out,
+                                                        int accumulate)
 {
-    double ss = 0.0;
+    T ss = 0;
     for (uint32_t i = threadIdx.x; i < n; i += kThreads)
         ss += partials[i];
-    const double t = block_sum(ss);
+    const T t = block_sum(ss);
     if (threadIdx.x == 0)
         *out = accumulate ? *out + t : t;
+}
+
+// ---- verification protocol: read-only scans ----
+
+struct ScanArgs {
+    const void *a;
+    const void *b;
+    void *partials0; // per-workgroup partial sums (first quantity)
+    void *partials1; // second quantity, where there is one
+    uint64_t n_tiles; // whole tiles (tile kernels) or leftover units (tail kernels)
+    uint64_t first_index;
+    uint32_t partial_slot;
+};
+
+// Sums of (a-b)^2 and a^2 in binary64 over whole 256-element tiles; workgroup b
+// owns tiles [4b, 4b+4).
+template <typename G>
+__global__ __launch_bounds__(kWave) void diff_sumsq_tiles(const ScanArgs s)
+{
+    double sd = 0.0, sa = 0.0;
+    const uint64_t t0 = (uint64_t)blockIdx.x * kReduceTilesPerGroup;
+    const uint64_t t1 = t0 + kReduceTilesPerGroup < s.n_tiles ? t0 + kReduceTilesPerGroup : s.n_tiles;
+    for (uint64_t tile = t0; tile < t1; ++tile) {
+        const uint64_t e = tile * kTileElems + (uint64_t)threadIdx.x * 4;
+        const f32x4 x = load_contrib4<G, true>(s.a, e);
+        const f32x4 y = load_contrib4<G, true>(s.b, e);
+        const float xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const double d = (double)xs[i] - (double)ys[i];
+            sd += d * d;
+            sa += (double)xs[i] * (double)xs[i];
+        }
+    }
+    sd = wave_sum(sd);
+    sa = wave_sum(sa);
+    if (threadIdx.x == 0) {
+        reinterpret_cast<double *>(s.partials0)[blockIdx.x] = sd;
+        reinterpret_cast<double *>(s.partials1)[blockIdx.x] = sa;
+    }
+}
+
+template <typename G>
+__global__ __launch_bounds__(kWave) void diff_sumsq_tail(const ScanArgs s)
+{
+    double sd = 0.0, sa = 0.0;
+    for (uint64_t e = threadIdx.x; e < s.n_tiles; e += kWave) {
+        const double x = (double)load_contrib1<G>(s.a, e), y = (double)load_contrib1<G>(s.b, e);
+        const double d = x - y;
+        sd += d * d;
+        sa += x * x;
+    }
+    sd = wave_sum(sd);
+    sa = wave_sum(sa);
+    if (threadIdx.x == 0) {
+        reinterpret_cast<double *>(s.partials0)[s.partial_slot] = sd;
+        reinterpret_cast<double *>(s.partials1)[s.partial_slot] = sa;
+    }
+}
+
+// One word's contribution to the checksum: the splitmix64 output function of
+// w + (index + 1) * golden-ratio increment.
+__device__ __forceinline__ uint64_t checksum_term(uint64_t w, uint64_t index)
+{
+    uint64_t z = w + (index + 1) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// Checksum over whole 128-word (1 KiB) tiles; lane t owns words 2t, 2t+1.
+__global__ __launch_bounds__(kWave) void checksum_tiles(const ScanArgs s)
+{
+    uint64_t c = 0;
+    const uint64_t t0 = (uint64_t)blockIdx.x * kReduceTilesPerGroup;
+    const uint64_t t1 = t0 + kReduceTilesPerGroup < s.n_tiles ? t0 + kReduceTilesPerGroup : s.n_tiles;
+    for (uint64_t tile = t0; tile < t1; ++tile) {
+        const uint64_t w0 = tile * (kWave * 2) + (uint64_t)threadIdx.x * 2;
+        const u32x4 v = load_vec<true>(reinterpret_cast<const u32x4 *>(s.a) + w0 / 2);
+        c += checksum_term((uint64_t)v.x | ((uint64_t)v.y << 32), s.first_index + w0);
+        c += checksum_term((uint64_t)v.z | ((uint64_t)v.w << 32), s.first_index + w0 + 1);
+    }
+    c = wave_sum(c);
+    if (threadIdx.x == 0)
+        reinterpret_cast<uint64_t *>(s.partials0)[blockIdx.x] = c;
+}
+
+__global__ __launch_bounds__(kWave) void checksum_tail(const ScanArgs s)
+{
+    uint64_t c = 0;
+    const uint64_t *w = reinterpret_cast<const uint64_t *>(s.a);
+    for (uint64_t i = threadIdx.x; i < s.n_tiles; i += kWave)
+        c += checksum_term(w[i], s.first_index + i);
+    c = wave_sum(c);
+    if (threadIdx.x == 0)
+        reinterpret_cast<uint64_t *>(s.partials0)[s.partial_slot] = c;
 }
 
 // Plain copy with the update kernel's access shape: one wave per 1 KiB, 16 B

@@ -165,6 +165,30 @@ uint64_t reduce_workspace_doubles(uint64_t count)
     return kFoldBlocks + reduce_groups(count) + 1; // second level, groups, tail
 }
 
+// Fold n first-level partials into at most kFoldBlocks sums (scratch `level2`),
+// then into *out.  The slicing depends only on n.
+template <typename T>
+static int fold_to_one(const T *level1, T *level2, uint64_t n, T *out, int accumulate,
+                       hipStream_t st)
+{
+    const T *last = level1;
+    uint32_t n_last = (uint32_t)n;
+    if (n > kFoldBlocks) {
+        const uint64_t per = (n + kFoldBlocks - 1) / kFoldBlocks;
+        const uint32_t blocks = (uint32_t)((n + per - 1) / per);
+        hipLaunchKernelGGL((fold_partials<T>), dim3(blocks), dim3(kThreads), 0, st, level1, n, per,
+                           level2);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return (int)e;
+        last = level2;
+        n_last = blocks;
+    }
+    hipLaunchKernelGGL((finalize_sum<T>), dim3(1), dim3(kThreads), 0, st, last, n_last, out,
+                       accumulate);
+    return (int)hipGetLastError();
+}
+
 template <int N, typename G>
 static void launch_reduce_n(const ReduceArgs &a, uint32_t grid, hipStream_t st)
 {
@@ -219,23 +243,7 @@ static int launch_reduce_t(uint32_t n_contrib, const ContribPtrs &g, float gs, f
             return (int)e;
         n_partials += 1;
     }
-    // Fold the first level into at most kFoldBlocks sums, then into one.
-    const double *last = level1;
-    uint32_t n_last = (uint32_t)n_partials;
-    if (n_partials > kFoldBlocks) {
-        const uint64_t per = (n_partials + kFoldBlocks - 1) / kFoldBlocks;
-        const uint32_t blocks = (uint32_t)((n_partials + per - 1) / per);
-        hipLaunchKernelGGL(fold_partials, dim3(blocks), dim3(kThreads), 0, st, level1, n_partials,
-                           per, level2);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess)
-            return (int)e;
-        last = level2;
-        n_last = blocks;
-    }
-    hipLaunchKernelGGL(finalize_sumsq, dim3(1), dim3(kThreads), 0, st, last, n_last, sumsq_out,
-                       accumulate);
-    return (int)hipGetLastError();
+    return fold_to_one(level1, level2, n_partials, sumsq_out, accumulate, st);
 }
 
 int launch_reduce_sumsq(int dtype, uint32_t n_contrib, const ContribPtrs &g, float gs,
@@ -248,6 +256,117 @@ int launch_reduce_sumsq(int dtype, uint32_t n_contrib, const ContribPtrs &g, flo
                                          sumsq_out, accumulate, st);
     return launch_reduce_t<float>(n_contrib, g, gs, reduced_out, count, partials, sumsq_out,
                                   accumulate, st);
+}
+
+// Workspace of the verification scans, in 8-byte slots, for `units` tiles' worth
+// of input: two partial arrays, each with its own second level.
+static uint64_t scan_groups(uint64_t n_tiles)
+{
+    return (n_tiles + kReduceTilesPerGroup - 1) / kReduceTilesPerGroup;
+}
+
+uint64_t verify_workspace_slots(uint64_t bytes)
+{
+    // the narrowest element is 2 bytes: at most bytes/2/256 tiles
+    return 2 * (kFoldBlocks + scan_groups(bytes / 2 / kTileElems) + 1);
+}
+
+template <typename G>
+static int launch_diff_t(const void *a, const void *b, uint64_t count, double *out2,
+                         int accumulate, uint64_t *workspace, uint64_t slots, hipStream_t st)
+{
+    const uint64_t n_tiles = count / kTileElems;
+    const uint64_t body = n_tiles * kTileElems;
+    const uint64_t groups = scan_groups(n_tiles);
+    if (groups > kMaxGrid)
+        return (int)hipErrorInvalidConfiguration;
+    const uint64_t half = slots / 2;
+    double *l2a = reinterpret_cast<double *>(workspace), *l1a = l2a + kFoldBlocks;
+    double *l2b = l2a + half, *l1b = l2b + kFoldBlocks;
+    ScanArgs s;
+    s.a = a;
+    s.b = b;
+    s.partials0 = l1a;
+    s.partials1 = l1b;
+    s.first_index = 0;
+    s.partial_slot = 0;
+    uint64_t n_partials = 0;
+    if (n_tiles) {
+        s.n_tiles = n_tiles;
+        hipLaunchKernelGGL((diff_sumsq_tiles<G>), dim3((uint32_t)groups), dim3(kWave),
+                           kReduceLdsBytes, st, s);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return (int)e;
+        n_partials = groups;
+    }
+    if (count > body) {
+        s.a = advance<G>(a, body);
+        s.b = advance<G>(b, body);
+        s.n_tiles = count - body;
+        s.partial_slot = (uint32_t)n_partials;
+        hipLaunchKernelGGL((diff_sumsq_tail<G>), dim3(1), dim3(kWave), 0, st, s);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return (int)e;
+        n_partials += 1;
+    }
+    int e = fold_to_one(l1a, l2a, n_partials, out2, accumulate, st);
+    if (e != 0)
+        return e;
+    return fold_to_one(l1b, l2b, n_partials, out2 + 1, accumulate, st);
+}
+
+int launch_diff_sumsq(int dtype, const void *a, const void *b, uint64_t count, double *out2,
+                      int accumulate, void *workspace, uint64_t slots, void *stream)
+{
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    uint64_t *ws = reinterpret_cast<uint64_t *>(workspace);
+    if (dtype == PS_BF16)
+        return launch_diff_t<uint16_t>(a, b, count, out2, accumulate, ws, slots, st);
+    return launch_diff_t<float>(a, b, count, out2, accumulate, ws, slots, st);
+}
+
+int launch_checksum(const void *buf, uint64_t n_words, uint64_t first_index, uint64_t *out,
+                    int accumulate, void *workspace, void *stream)
+{
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    constexpr uint64_t kTileWords = kWave * 2;
+    const uint64_t n_tiles = n_words / kTileWords;
+    const uint64_t body = n_tiles * kTileWords;
+    const uint64_t groups = scan_groups(n_tiles);
+    if (groups > kMaxGrid)
+        return (int)hipErrorInvalidConfiguration;
+    uint64_t *l2 = reinterpret_cast<uint64_t *>(workspace), *l1 = l2 + kFoldBlocks;
+    ScanArgs s;
+    s.a = buf;
+    s.b = nullptr;
+    s.partials0 = l1;
+    s.partials1 = nullptr;
+    s.first_index = first_index;
+    s.partial_slot = 0;
+    uint64_t n_partials = 0;
+    if (n_tiles) {
+        s.n_tiles = n_tiles;
+        hipLaunchKernelGGL(checksum_tiles, dim3((uint32_t)groups), dim3(kWave), kReduceLdsBytes, st,
+                           s);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return (int)e;
+        n_partials = groups;
+    }
+    if (n_words > body) {
+        s.a = reinterpret_cast<const uint64_t *>(buf) + body;
+        s.first_index = first_index + body;
+        s.n_tiles = n_words - body;
+        s.partial_slot = (uint32_t)n_partials;
+        hipLaunchKernelGGL(checksum_tail, dim3(1), dim3(kWave), 0, st, s);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return (int)e;
+        n_partials += 1;
+    }
+    return fold_to_one(l1, l2, n_partials, out, accumulate, st);
 }
 
 int launch_copy(void *dst, const void *src, uint64_t bytes, void *stream)

@@ -607,6 +607,71 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
     return PS_OK;
 }
 
+uint64_t ps_verify_workspace_bytes(uint64_t buffer_bytes)
+{
+    return verify_workspace_slots(buffer_bytes) * 8;
+}
+
+ps_status_t ps_verify_diff_sumsq(const void *a, const void *b, int32_t dtype, uint64_t elem_count,
+                                 double *out2, int32_t accumulate, void *workspace,
+                                 uint64_t workspace_bytes, void *stream)
+{
+    clear_error();
+    if (!a || !b || !out2 || !workspace) {
+        set_error("a, b, out2 or workspace is NULL");
+        return PS_EINVAL;
+    }
+    if (dtype != PS_BF16 && dtype != PS_F32) {
+        set_error("dtype must be PS_BF16 or PS_F32");
+        return PS_EINVAL;
+    }
+    if (!aligned16(a) || !aligned16(b) || !aligned16(workspace) ||
+        (reinterpret_cast<uintptr_t>(out2) & 7u)) {
+        set_error("a, b, workspace need 16-byte and out2 8-byte alignment");
+        return PS_EALIGN;
+    }
+    if (elem_count > UINT64_MAX / 4 ||
+        workspace_bytes < ps_verify_workspace_bytes(elem_count * elem_bytes(dtype))) {
+        set_error("workspace smaller than ps_verify_workspace_bytes()");
+        return PS_ERANGE;
+    }
+    ps_status_t st = need_device();
+    if (st != PS_OK)
+        return st;
+    int e = launch_diff_sumsq(dtype, a, b, elem_count, out2, accumulate, workspace,
+                              verify_workspace_slots(elem_count * elem_bytes(dtype)), stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "difference kernel launch");
+    return PS_OK;
+}
+
+ps_status_t ps_verify_checksum(const void *buf, uint64_t bytes, uint64_t first_word_index,
+                               uint64_t *out, int32_t accumulate, void *workspace,
+                               uint64_t workspace_bytes, void *stream)
+{
+    clear_error();
+    if (!buf || !out || !workspace) {
+        set_error("buf, out or workspace is NULL");
+        return PS_EINVAL;
+    }
+    if (!aligned16(buf) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(out) & 7u) ||
+        bytes % 8 != 0) {
+        set_error("buf, workspace need 16-byte alignment, out 8-byte, bytes a multiple of 8");
+        return PS_EALIGN;
+    }
+    if (workspace_bytes < ps_verify_workspace_bytes(bytes)) {
+        set_error("workspace smaller than ps_verify_workspace_bytes()");
+        return PS_ERANGE;
+    }
+    ps_status_t st = need_device();
+    if (st != PS_OK)
+        return st;
+    int e = launch_checksum(buf, bytes / 8, first_word_index, out, accumulate, workspace, stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "checksum kernel launch");
+    return PS_OK;
+}
+
 ps_status_t ps_probe_copy(void *dst, const void *src, uint64_t bytes, void *stream)
 {
     clear_error();

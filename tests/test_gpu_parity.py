@@ -433,6 +433,85 @@ def test_gradient_accumulation_then_update(dtype, N):
     assert assert_state_parity([host(x) for x in (th, m, v, p)], want, "accumulated") == 0
 
 
+# ---- verification protocol kernels ----
+
+@pytest.mark.parametrize("dtype,n", [("f32", 9 * TILE + 777), ("bf16", 9 * TILE + 777),
+                                     ("f32", 1200 * TILE + 131), ("bf16", 100)])
+def test_verify_relative_difference(dtype, n):
+    _say("verify diff n=%d %s" % (n, dtype))
+    a = gen.gradient(n, 101, 0, 0, dtype, std=1e-2)
+    b = gen.gradient(n, 101, 0, 1, dtype, std=1e-2)
+    sd, sa = orc.diff_sumsq(a, b)
+    ad, bd = dev(a), dev(b)
+    esz = 2 if dtype == "bf16" else 4
+    ws = torch.empty(ps.ps_verify_workspace_bytes(n * esz), dtype=torch.uint8, device="cuda")
+    out = torch.zeros(2, dtype=torch.float64, device="cuda")
+    dt = ps.PS_BF16 if dtype == "bf16" else ps.PS_F32
+
+    def call(acc=0, lo=0, cnt=n):
+        ps.ps_verify_diff_sumsq(ad.data_ptr() + lo * esz, bd.data_ptr() + lo * esz, dt, cnt,
+                                out.data_ptr(), acc, ws.data_ptr(), ws.numel(), stream_handle())
+        torch.cuda.synchronize()
+        return out.cpu().numpy().copy()
+    got = call()
+    assert abs(got[0] - sd) <= 1e-12 * sd and abs(got[1] - sa) <= 1e-12 * sa
+    assert np.array_equal(call(), got)                               # reproducible bit for bit
+    if n > 64:                                                       # pieces accumulate
+        cut = (n // 3) // 8 * 8
+        call(0, 0, cut)
+        two = call(1, cut, n - cut)
+        assert abs(two[0] - sd) <= 1e-12 * sd and abs(two[1] - sa) <= 1e-12 * sa
+    ps.ps_verify_diff_sumsq(ad.data_ptr(), ad.data_ptr(), dt, n, out.data_ptr(), 0, ws.data_ptr(),
+                            ws.numel(), stream_handle())
+    assert out.cpu().numpy()[0] == 0.0                               # identical buffers: exactly zero
+
+
+@pytest.mark.parametrize("n_words", [1, 2, 127, 128, 129, 5 * 1024 + 77, 700 * 1024 + 3])
+def test_verify_checksum_is_bit_exact(n_words):
+    _say("verify checksum words=%d" % n_words)
+    w = np.random.default_rng(n_words).integers(0, 2 ** 63, n_words, dtype=np.uint64)
+    want = orc.checksum(w)
+    wd = torch.from_numpy(w.view(np.int64)).cuda()
+    ws = torch.empty(ps.ps_verify_workspace_bytes(n_words * 8), dtype=torch.uint8, device="cuda")
+    out = torch.zeros(1, dtype=torch.int64, device="cuda")
+
+    def call(ptr, nbytes, first=0, acc=0):
+        ps.ps_verify_checksum(ptr, nbytes, first, out.data_ptr(), acc, ws.data_ptr(), ws.numel(),
+                              stream_handle())
+        torch.cuda.synchronize()
+        return int(out.cpu().numpy().view(np.uint64)[0])
+    assert call(wd.data_ptr(), n_words * 8) == want
+    if n_words > 4:                                                  # pieces add up modulo 2^64
+        cut = (n_words // 2) // 2 * 2                                # keeps 16-byte alignment
+        call(wd.data_ptr(), cut * 8)
+        assert call(wd.data_ptr() + cut * 8, (n_words - cut) * 8, first=cut, acc=1) == want
+        sw = w.copy(); sw[[0, n_words - 1]] = sw[[n_words - 1, 0]]   # a swap shows
+        assert call(torch.from_numpy(sw.view(np.int64)).cuda().data_ptr(), n_words * 8) == orc.checksum(sw) != want
+
+
+def test_verify_checksum_of_updated_state_matches_oracle():
+    """The protocol's use: after a step, the checksum of the device's shard equals the
+    checksum of the oracle's shard (identical bits => identical checksums)."""
+    n, N = 4 * TILE + 8, 4
+    _say("checksum after a step n=%d" % n)
+    spec = ps.ps_spec_preset("zero3", N, 0, n * N)
+    grads = [gen.gradient(n, 103, 0, r, "bf16") for r in range(N)]
+    state = [gen.master(n, 103), *gen.moments(n, 103, True), np.zeros(n, np.uint16)]
+    hpd, hp = hp_of(None, 4)
+    want = [a.copy() for a in state]
+    orc.step_f32(grads, orc.derive_scalars(t=4, n_devices=N, **hpd), *want)
+    th, m, v, p = [dev(a) for a in state]
+    ps.ps_step_update(spec, hp, shard_of(th, m, v, p, n), grads_of([dev(g) for g in grads], "bf16"),
+                      0, n, stream_handle())
+    ws = torch.empty(ps.ps_verify_workspace_bytes(n * 4), dtype=torch.uint8, device="cuda")
+    out = torch.zeros(1, dtype=torch.int64, device="cuda")
+    for t_dev, w_host in zip((th, m, v, p), want):
+        ps.ps_verify_checksum(t_dev.data_ptr(), w_host.nbytes, 0, out.data_ptr(), 0, ws.data_ptr(),
+                              ws.numel(), stream_handle())
+        torch.cuda.synchronize()
+        assert int(out.cpu().numpy().view(np.uint64)[0]) == orc.checksum(w_host)
+
+
 # ---- memory safety and statelessness ----
 
 GUARD = 4096  # bytes of guard band on each side of every device buffer

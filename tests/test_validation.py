@@ -185,6 +185,22 @@ def test_bucketed_rejects_bad_arguments():
     assert _status(lambda: run(spec, hp, shard, plan(kernel_ms=ms, kernel_ms_len=2))) == ps.PS_ERANGE
 
 
+def test_verification_calls_validation():
+    ws = ps.ps_verify_workspace_bytes(4096)
+    assert ws >= 2 * 1024 * 8
+    d = ps.ps_verify_diff_sumsq
+    assert _status(lambda: d(0, FAKE, ps.PS_F32, 8, FAKE, 0, FAKE, ws)) == ps.PS_EINVAL
+    assert _status(lambda: d(FAKE, FAKE, 5, 8, FAKE, 0, FAKE, ws)) == ps.PS_EINVAL
+    assert _status(lambda: d(FAKE, FAKE + 4, ps.PS_F32, 8, FAKE, 0, FAKE, ws)) == ps.PS_EALIGN
+    assert _status(lambda: d(FAKE, FAKE, ps.PS_F32, 8, FAKE + 4, 0, FAKE, ws)) == ps.PS_EALIGN
+    assert _status(lambda: d(FAKE, FAKE, ps.PS_F32, 1 << 30, FAKE, 0, FAKE, ws)) == ps.PS_ERANGE
+    c = ps.ps_verify_checksum
+    assert _status(lambda: c(0, 64, 0, FAKE, 0, FAKE, ws)) == ps.PS_EINVAL
+    assert _status(lambda: c(FAKE, 60, 0, FAKE, 0, FAKE, ws)) == ps.PS_EALIGN
+    assert _status(lambda: c(FAKE, 64, 0, FAKE + 2, 0, FAKE, ws)) == ps.PS_EALIGN
+    assert _status(lambda: c(FAKE, 1 << 32, 0, FAKE, 0, FAKE, ws)) == ps.PS_ERANGE
+
+
 def test_copy_probe_validation():
     assert _status(lambda: ps.ps_probe_copy(0, FAKE, 16)) == ps.PS_EINVAL
     assert _status(lambda: ps.ps_probe_copy(FAKE, FAKE + 8, 16)) == ps.PS_EALIGN
