@@ -48,7 +48,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="70b_zero3",
                     choices=["tiny", "gpt2s", "7b_zero2", "70b_zero3", "13b_clip", "7b_zero1",
-                             "7b_accum4"])
+                             "7b_accum4", "7b_verify"])
     ap.add_argument("--pool-elems", type=int, default=1 << 21,
                     help="elements per contribution of the resident, repeating bucket source")
     ap.add_argument("--copy-engine", choices=["kernel", "memcpy"], default="kernel")
@@ -70,6 +70,8 @@ def main():
     from synth import WORKLOADS
     from synth import device as dgen
 
+    if args.workload == "7b_verify":
+        return verify_bench(args)
     w = WORKLOADS[args.workload]
     torch.cuda.set_device(0)
     info = ps.ps_device_info()
@@ -267,6 +269,70 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, bpe)
     print(json.dumps(result), flush=True)
+
+
+def verify_bench(args):
+    """The verification protocol's two scans on buffers of the 7B shard: relative difference
+    of two bf16 gradient copies and the checksum of the FP32 master shard."""
+    import torch
+
+    import paper_2601_02311_amd as ps
+    from synth import WORKLOADS
+    from synth import device as dgen
+
+    w = WORKLOADS["7b_zero2"]
+    torch.cuda.set_device(0)
+    info = ps.ps_device_info()
+    n = w.shard_len
+    a = dgen.fill_gradient_(torch.empty(n, dtype=torch.bfloat16, device="cuda"), w.seed, 1, 0, w.grad_std)
+    b = a.clone()
+    b[12345] += 1.0
+    master, _, _ = dgen.workload_state(w)
+    ws = torch.empty(ps.ps_verify_workspace_bytes(n * 4), dtype=torch.uint8, device="cuda")
+    out2 = torch.zeros(2, dtype=torch.float64, device="cuda")
+    outc = torch.zeros(1, dtype=torch.int64, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        ps.ps_verify_diff_sumsq(a.data_ptr(), b.data_ptr(), ps.PS_BF16, n, out2.data_ptr(), 0,
+                                ws.data_ptr(), ws.numel(), st)
+        ps.ps_verify_checksum(master.data_ptr(), n * 4, 0, outc.data_ptr(), 0, ws.data_ptr(),
+                              ws.numel(), st)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    t_diff = t_sum = 0.0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev[0].record()
+        ps.ps_verify_diff_sumsq(a.data_ptr(), b.data_ptr(), ps.PS_BF16, n, out2.data_ptr(), 0,
+                                ws.data_ptr(), ws.numel(), st)
+        ev[1].record()
+        ps.ps_verify_checksum(master.data_ptr(), n * 4, 0, outc.data_ptr(), 0, ws.data_ptr(),
+                              ws.numel(), st)
+        ev[2].record()
+        torch.cuda.synchronize()
+        t_diff += ev[0].elapsed_time(ev[1])
+        t_sum += ev[1].elapsed_time(ev[2])
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    t_diff /= args.steps
+    t_sum /= args.steps
+    sd, sa = out2.cpu().tolist()
+    achieved = (4 * n + 4 * n) / ((t_diff + t_sum) * 1e-3) / 1e9
+    log("diff scan %.3f ms (%.0f GB/s), checksum %.3f ms (%.0f GB/s); relative difference %.3e" %
+        (t_diff, 4 * n / t_diff / 1e6, t_sum, 4 * n / t_sum / 1e6, (sd / sa) ** 0.5))
+    print(json.dumps({
+        "metric": "verification scans (relative gradient difference + state checksum): HBM GB/s, elements/s",
+        "value": 2 * n / ((t_diff + t_sum) * 1e-3), "unit": "elements/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": "7b_verify", "shard_elems": n, "device": info.name.decode(),
+                   "diff_ms": t_diff, "checksum_ms": t_sum},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                     "kernel": "diff_sumsq_tiles + checksum_tiles"}}), flush=True)
 
 
 def measured_traffic(w, elems_per_launch):

@@ -407,18 +407,28 @@ struct ScanArgs {
 };
 
 // Sums of (a-b)^2 and a^2 in binary64 over whole 256-element tiles; workgroup b
-// owns tiles [4b, 4b+4).
+// owns tiles [4b, 4b+4) and issues all of their loads before the arithmetic.
 template <typename G>
 __global__ __launch_bounds__(kWave) void diff_sumsq_tiles(const ScanArgs s)
 {
+    constexpr int K = kReduceTilesPerGroup;
     double sd = 0.0, sa = 0.0;
-    const uint64_t t0 = (uint64_t)blockIdx.x * kReduceTilesPerGroup;
-    const uint64_t t1 = t0 + kReduceTilesPerGroup < s.n_tiles ? t0 + kReduceTilesPerGroup : s.n_tiles;
-    for (uint64_t tile = t0; tile < t1; ++tile) {
-        const uint64_t e = tile * kTileElems + (uint64_t)threadIdx.x * 4;
-        const f32x4 x = load_contrib4<G, true>(s.a, e);
-        const f32x4 y = load_contrib4<G, true>(s.b, e);
-        const float xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+    const uint64_t t0 = (uint64_t)blockIdx.x * K;
+    f32x4 x[K], y[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint64_t e = (t0 + k) * kTileElems + (uint64_t)threadIdx.x * 4;
+        if (t0 + k < s.n_tiles) {
+            x[k] = load_contrib4<G, true>(s.a, e);
+            y[k] = load_contrib4<G, true>(s.b, e);
+        } else {
+            x[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+            y[k] = x[k];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const float xs[4] = {x[k].x, x[k].y, x[k].z, x[k].w}, ys[4] = {y[k].x, y[k].y, y[k].z, y[k].w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const double d = (double)xs[i] - (double)ys[i];
@@ -462,17 +472,27 @@ __device__ __forceinline__ uint64_t checksum_term(uint64_t w, uint64_t index)
     return z ^ (z >> 31);
 }
 
-// Checksum over whole 128-word (1 KiB) tiles; lane t owns words 2t, 2t+1.
+// Checksum over whole 128-word (1 KiB) tiles; lane t owns words 2t, 2t+1 of each
+// of the workgroup's four tiles, all loaded before the arithmetic.
 __global__ __launch_bounds__(kWave) void checksum_tiles(const ScanArgs s)
 {
+    constexpr int K = kReduceTilesPerGroup;
     uint64_t c = 0;
-    const uint64_t t0 = (uint64_t)blockIdx.x * kReduceTilesPerGroup;
-    const uint64_t t1 = t0 + kReduceTilesPerGroup < s.n_tiles ? t0 + kReduceTilesPerGroup : s.n_tiles;
-    for (uint64_t tile = t0; tile < t1; ++tile) {
-        const uint64_t w0 = tile * (kWave * 2) + (uint64_t)threadIdx.x * 2;
-        const u32x4 v = load_vec<true>(reinterpret_cast<const u32x4 *>(s.a) + w0 / 2);
-        c += checksum_term((uint64_t)v.x | ((uint64_t)v.y << 32), s.first_index + w0);
-        c += checksum_term((uint64_t)v.z | ((uint64_t)v.w << 32), s.first_index + w0 + 1);
+    const uint64_t t0 = (uint64_t)blockIdx.x * K;
+    u32x4 v[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint64_t vec = (t0 + k) * kWave + threadIdx.x;
+        if (t0 + k < s.n_tiles)
+            v[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.a) + vec);
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        if (t0 + k < s.n_tiles) {
+            const uint64_t w0 = ((t0 + k) * kWave + threadIdx.x) * 2;
+            c += checksum_term((uint64_t)v[k].x | ((uint64_t)v[k].y << 32), s.first_index + w0);
+            c += checksum_term((uint64_t)v[k].z | ((uint64_t)v[k].w << 32), s.first_index + w0 + 1);
+        }
     }
     c = wave_sum(c);
     if (threadIdx.x == 0)

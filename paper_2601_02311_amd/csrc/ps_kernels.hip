@@ -16,6 +16,9 @@ constexpr uint32_t kReduceLdsBytes = 40960;
 // source).  When it shares the device with the update kernel it asks for no LDS,
 // so that it never waits behind the update's own LDS reservations.
 constexpr uint32_t kStageAloneLdsBytes = 20480;
+// The read-only verification scans have one or two streams, 4-8 KiB in flight per
+// wave; they run with residency uncapped.
+constexpr uint32_t kScanLdsBytes = 0;
 // Largest grid used; beyond it the kernels loop (never reached below 5e11 elements).
 constexpr uint64_t kMaxGrid = 0x7fffffffull;
 // Second level of the sum-of-squares tree.
@@ -294,7 +297,7 @@ static int launch_diff_t(const void *a, const void *b, uint64_t count, double *o
     if (n_tiles) {
         s.n_tiles = n_tiles;
         hipLaunchKernelGGL((diff_sumsq_tiles<G>), dim3((uint32_t)groups), dim3(kWave),
-                           kReduceLdsBytes, st, s);
+                           kScanLdsBytes, st, s);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return (int)e;
@@ -348,7 +351,7 @@ int launch_checksum(const void *buf, uint64_t n_words, uint64_t first_index, uin
     uint64_t n_partials = 0;
     if (n_tiles) {
         s.n_tiles = n_tiles;
-        hipLaunchKernelGGL(checksum_tiles, dim3((uint32_t)groups), dim3(kWave), kReduceLdsBytes, st,
+        hipLaunchKernelGGL(checksum_tiles, dim3((uint32_t)groups), dim3(kWave), kScanLdsBytes, st,
                            s);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
