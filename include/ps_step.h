@@ -209,6 +209,34 @@ ps_status_t ps_cost_eval(const ps_spec_t *spec, ps_cost_t *cost);
  * step).  Pass the result as ps_adamw_t.clip_coef. */
 double ps_clip_coef(double sumsq_local, double sumsq_others, double max_norm);
 
+/* Illustrative strategy selection (Algorithm 1) with its printed thresholds:
+ * 16 psi < 0.7 device_mem_bytes -> data parallel (R,R,R,R); else ZeRO-3
+ * (S*,S,S,R).  *fits is set to whether the chosen placement's model state stays
+ * below 0.7 device_mem_bytes per device.  *add_tp is set when ZeRO-3 alone does
+ * not fit, a single layer (layer_bytes) exceeds 0.3 device_mem_bytes and the
+ * interconnect is fast: tensor parallelism is then to be added within a node
+ * (the composed specification itself is left to the caller).  Comparisons are
+ * exact (integers, strict inequalities as printed).  spec receives n_devices,
+ * psi and shard_index 0. */
+ps_status_t ps_select_strategy(uint64_t psi, uint64_t device_mem_bytes, uint32_t n_devices,
+                               uint64_t layer_bytes, int32_t fast_interconnect, ps_spec_t *spec,
+                               int32_t *fits, int32_t *add_tp);
+
+/* Composition calculus (Definition 5): where device `device` of n = inner * outer
+ * devices sits when one strategy is applied within groups of `inner` consecutive
+ * devices and another across the groups.
+ *   Tensor x data parallel (Theorem 6): inner = T; TP group i = {iT..(i+1)T-1};
+ *     data-parallel sync runs across groups between equal positions.
+ *   Pipeline x data parallel (Theorem 7): inner = D; stage k is replicated on
+ *     {kD..(k+1)D-1} (gradient sync inside); activations move across groups
+ *     between equal positions (device +- D).
+ * Outputs: inner_group = device / inner, inner_rank = device % inner; the outer
+ * group is the set {inner_rank + j * inner}, indexed by outer_group = inner_rank,
+ * with outer_rank = inner_group. */
+ps_status_t ps_compose_index(uint32_t inner, uint32_t outer, uint32_t device,
+                             uint32_t *inner_group, uint32_t *inner_rank,
+                             uint32_t *outer_group, uint32_t *outer_rank);
+
 /* ---- device calls ---- */
 
 ps_status_t ps_device_info(ps_device_info_t *info);

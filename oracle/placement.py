@@ -92,3 +92,37 @@ def shard_geometry(psi, N, i, align=1):
     off = i * n
     valid = min(max(psi - off, 0), n)
     return psi_pad, off, n, valid
+
+
+def select_strategy(P, device_mem_bytes, N, layer_bytes=0, fast_interconnect=False):
+    """Algorithm 1 (illustrative strategy selection), thresholds 0.7 and 0.3 as printed.
+    Returns (spec, add_tp): data parallelism if 16P fits in 70 % of a device, else
+    ZeRO-3 (whether or not 16P/N fits; that it does is the second test of the
+    algorithm), with tensor parallelism added inside a node when a single layer
+    exceeds 30 % of a device and the interconnect is fast.  add_tp is only
+    considered on the path the algorithm reaches it: when ZeRO-3 alone does not fit."""
+    m_model = 16 * P
+    if Fraction(m_model) < Fraction(7, 10) * device_mem_bytes:
+        return STRATEGIES["dp"], False
+    if Fraction(m_model, N) < Fraction(7, 10) * device_mem_bytes:
+        return STRATEGIES["zero3"], False
+    add_tp = bool(Fraction(layer_bytes) > Fraction(3, 10) * device_mem_bytes and fast_interconnect)
+    return STRATEGIES["zero3"], add_tp
+
+
+def tp_dp_groups(T, D):
+    """Theorem 6: on N = T*D devices TP group i is {iT, ..., (i+1)T-1}; data-parallel
+    synchronisation runs across groups, between devices at the same position.
+    Returns (tp_groups, dp_groups) as lists of device lists."""
+    tp = [list(range(i * T, (i + 1) * T)) for i in range(D)]
+    dp = [[i * T + j for i in range(D)] for j in range(T)]
+    return tp, dp
+
+
+def pp_dp_groups(K, D):
+    """Theorem 7: on N = K*D devices stage k is replicated on {kD, ..., (k+1)D-1};
+    gradient sync is among the replicas of one stage, activations move between
+    corresponding replicas of adjacent stages.  Returns (stage_groups, pipelines)."""
+    stages = [list(range(k * D, (k + 1) * D)) for k in range(K)]
+    pipes = [[k * D + r for k in range(K)] for r in range(D)]
+    return stages, pipes

@@ -22,7 +22,8 @@ __all__ = [
     "ps_abi_version", "ps_status_string", "ps_last_error", "ps_spec_preset", "ps_cost_eval",
     "ps_device_info", "ps_step_update", "ps_step_update_bucketed", "ps_workspace_bytes",
     "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
-    "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum", "EXPORTED_SYMBOLS",
+    "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum",
+    "ps_select_strategy", "ps_compose_index", "EXPORTED_SYMBOLS",
 ]
 
 PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
@@ -37,6 +38,7 @@ EXPORTED_SYMBOLS = (
     "ps_device_info", "ps_step_update", "ps_step_update_bucketed", "ps_workspace_bytes",
     "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
     "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum",
+    "ps_select_strategy", "ps_compose_index",
 )
 
 
@@ -123,6 +125,12 @@ def library():
         L.ps_cost_eval.argtypes = [C.POINTER(ps_spec_t), C.POINTER(ps_cost_t)]
         L.ps_clip_coef.restype = C.c_double
         L.ps_clip_coef.argtypes = [C.c_double] * 3
+        L.ps_select_strategy.restype = C.c_int
+        L.ps_select_strategy.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint64, C.c_int32,
+                                         C.POINTER(ps_spec_t), C.POINTER(C.c_int32),
+                                         C.POINTER(C.c_int32)]
+        L.ps_compose_index.restype = C.c_int
+        L.ps_compose_index.argtypes = [C.c_uint32] * 3 + [C.POINTER(C.c_uint32)] * 4
         L.ps_device_info.restype = C.c_int
         L.ps_device_info.argtypes = [C.POINTER(ps_device_info_t)]
         L.ps_step_update.restype = C.c_int
@@ -202,6 +210,22 @@ def ps_cost_eval(spec):
 
 def ps_clip_coef(sumsq_local, sumsq_others, max_norm):
     return library().ps_clip_coef(sumsq_local, sumsq_others, max_norm)
+
+
+def ps_select_strategy(psi, device_mem_bytes, n_devices, layer_bytes=0, fast_interconnect=False):
+    """Returns (spec, fits, add_tp)."""
+    spec, fits, tp = ps_spec_t(), C.c_int32(), C.c_int32()
+    _check(library().ps_select_strategy(psi, device_mem_bytes, n_devices, layer_bytes,
+                                        int(bool(fast_interconnect)), C.byref(spec),
+                                        C.byref(fits), C.byref(tp)))
+    return spec, bool(fits.value), bool(tp.value)
+
+
+def ps_compose_index(inner, outer, device):
+    """Returns (inner_group, inner_rank, outer_group, outer_rank)."""
+    out = [C.c_uint32() for _ in range(4)]
+    _check(library().ps_compose_index(inner, outer, device, *[C.byref(x) for x in out]))
+    return tuple(x.value for x in out)
 
 
 def ps_device_info():

@@ -197,6 +197,60 @@ double ps_clip_coef(double sumsq_local, double sumsq_others, double max_norm)
     return coef < 1.0 ? coef : 1.0;
 }
 
+ps_status_t ps_select_strategy(uint64_t psi, uint64_t device_mem_bytes, uint32_t n_devices,
+                               uint64_t layer_bytes, int32_t fast_interconnect, ps_spec_t *spec,
+                               int32_t *fits, int32_t *add_tp)
+{
+    clear_error();
+    if (!spec || !fits || !add_tp) {
+        set_error("spec, fits or add_tp is NULL");
+        return PS_EINVAL;
+    }
+    if (n_devices == 0) {
+        set_error("n_devices must be >= 1");
+        return PS_EINVAL;
+    }
+    // 16 psi < 0.7 M  <=>  160 psi < 7 M, in 128-bit integers
+    const unsigned __int128 model10 = (unsigned __int128)psi * 160u;
+    const unsigned __int128 cap7 = (unsigned __int128)device_mem_bytes * 7u;
+    *add_tp = 0;
+    if (model10 < cap7) {
+        *fits = 1;
+        return ps_spec_preset("dp", n_devices, 0, psi, spec);
+    }
+    // 16 psi / N < 0.7 M  <=>  160 psi < 7 M N
+    *fits = model10 < cap7 * n_devices ? 1 : 0;
+    if (!*fits && fast_interconnect &&
+        (unsigned __int128)layer_bytes * 10u > (unsigned __int128)device_mem_bytes * 3u)
+        *add_tp = 1;
+    return ps_spec_preset("zero3", n_devices, 0, psi, spec);
+}
+
+ps_status_t ps_compose_index(uint32_t inner, uint32_t outer, uint32_t device,
+                             uint32_t *inner_group, uint32_t *inner_rank,
+                             uint32_t *outer_group, uint32_t *outer_rank)
+{
+    clear_error();
+    if (!inner_group || !inner_rank || !outer_group || !outer_rank) {
+        set_error("an output pointer is NULL");
+        return PS_EINVAL;
+    }
+    if (inner == 0 || outer == 0) {
+        set_error("group sizes must be >= 1");
+        return PS_EINVAL;
+    }
+    if ((uint64_t)inner * outer > UINT32_MAX || device >= (uint64_t)inner * outer) {
+        set_error("device %u not below inner * outer = %llu", device,
+                  (unsigned long long)inner * outer);
+        return PS_ERANGE;
+    }
+    *inner_group = device / inner;
+    *inner_rank = device % inner;
+    *outer_group = *inner_rank;
+    *outer_rank = *inner_group;
+    return PS_OK;
+}
+
 ps_status_t ps_cost_eval(const ps_spec_t *spec, ps_cost_t *cost)
 {
     clear_error();

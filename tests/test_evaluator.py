@@ -136,3 +136,45 @@ def test_clip_coef_against_the_oracle():
     assert ps.ps_clip_coef(1e-12, 0.0, 1.0) == 1.0
     for bad in [(math.inf, 0.0, 1.0), (math.nan, 0.0, 1.0), (-1.0, 0.0, 1.0), (1.0, 1.0, 0.0)]:
         assert math.isnan(ps.ps_clip_coef(*bad))
+
+
+def test_strategy_selection_against_the_oracle():
+    rnd = random.Random(11)
+    GBy = 10 ** 9
+    cases = [(70 * GBy, 80 * GBy, 8, 30 * GBy, True), (70 * GBy, 80 * GBy, 8, 30 * GBy, False),
+             (70 * GBy, 80 * GBy, 8, 20 * GBy, True), (1 * GBy, 80 * GBy, 8, 0, False),
+             (7 * GBy, 80 * GBy, 8, 0, True), (7, 160, 8, 0, False), (7, 161, 8, 0, False),
+             (7 * GBy, 288 * GBy, 8, 0, False), (70 * GBy, 288 * GBy, 8, 0, False),
+             (2 ** 60, 2 ** 62, 3, 2 ** 61, True)]
+    for _ in range(300):
+        cases.append((rnd.randrange(1, 10 ** 12), rnd.randrange(1, 10 ** 12), rnd.choice([1, 2, 8, 64]),
+                      rnd.randrange(0, 10 ** 12), rnd.random() < 0.5))
+    for P, M, N, L, fast in cases:
+        want_modes, want_tp = pl.select_strategy(P, M, N, L, fast)
+        spec, fits, tp = ps.ps_select_strategy(P, M, N, L, fast)
+        assert (spec.theta, spec.omega, spec.grad, spec.act) == tuple(MODE[m] for m in want_modes)
+        assert tp == want_tp and (spec.n_devices, spec.psi) == (N, P)
+        per_device = 16 * P if want_modes == pl.STRATEGIES["dp"] else 16 * P / N
+        assert fits == (per_device * 10 < 7 * M if isinstance(per_device, int) else 160 * P < 7 * M * N)
+    spec, fits, tp = ps.ps_select_strategy(70 * GBy, 80 * GBy, 8, 30 * GBy, True)
+    assert (not fits) and tp                       # the paper's 70B on 80 GB devices: ZeRO-3 + TP
+    with pytest.raises(ps.PsError):
+        ps.ps_select_strategy(1, 1, 0)
+
+
+def test_composition_index_against_the_oracle(golden):
+    for A, B in [(4, 2), (1, 8), (8, 1), (3, 5), (2, 2)]:
+        tp, dp = pl.tp_dp_groups(A, B)
+        stages, pipes = pl.pp_dp_groups(B, A)      # pipeline x data: inner = replicas per stage
+        for d in range(A * B):
+            ig, ir, og, orank = ps.ps_compose_index(A, B, d)
+            assert tp[ig][ir] == d and dp[og][orank] == d
+            assert stages[ig][ir] == d and pipes[og][orank] == d
+    T, D = int(golden["fig2_tp_degree"]), int(golden["fig2_dp_degree"])
+    assert ps.ps_compose_index(T, D, 6) == (1, 2, 2, 1)     # Figure 2: device 6 = TP group 1, syncs with 2
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_compose_index(4, 2, 8)
+    assert e.value.status == ps.PS_ERANGE
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_compose_index(0, 2, 0)
+    assert e.value.status == ps.PS_EINVAL

@@ -106,3 +106,46 @@ def test_shard_geometry_matches_eq2_when_divisible():
     for i in range(N):
         _, off, n, valid = pl.shard_geometry(psi, N, i)
         assert off == i * psi // N and off + n == (i + 1) * psi // N and valid == n
+
+
+def test_figure2_groups(golden):
+    T, D = int(golden["fig2_tp_degree"]), int(golden["fig2_dp_degree"])
+    tp, dp = pl.tp_dp_groups(T, D)
+    assert tp[0] == [int(x) for x in golden["fig2_tp_group0"].split()]
+    assert tp[1] == [int(x) for x in golden["fig2_tp_group1"].split()]
+    pairs = [tuple(int(x) for x in p.split("-")) for p in golden["fig2_dp_pairs"].split()]
+    assert [tuple(g) for g in dp] == pairs
+
+
+@pytest.mark.parametrize("A,B", [(4, 2), (1, 8), (8, 1), (3, 5)])
+def test_group_calculus_partitions_the_devices(A, B):
+    for groups in (*pl.tp_dp_groups(A, B), *pl.pp_dp_groups(A, B)):
+        flat = sorted(d for g in groups for d in g)
+        assert flat == list(range(A * B))                      # every device in exactly one group
+    tp, dp = pl.tp_dp_groups(A, B)
+    for g in tp:
+        for h in dp:
+            assert len(set(g) & set(h)) == 1                   # inner and outer groups cross once
+    stages, pipes = pl.pp_dp_groups(A, B)
+    assert all(len(s_) == B for s_ in stages) and all(len(p_) == A for p_ in pipes)
+    assert all(p_[k + 1] - p_[k] == B for p_ in pipes for k in range(A - 1))
+
+
+def test_algorithm1_thresholds(golden):
+    GBy = 10 ** 9
+    th = float(golden["alg1_dp_threshold"])
+    assert th == 0.7 and float(golden["alg1_layer_threshold"]) == 0.3
+    # 70B on 80 GB devices: 1120 GB model state, 140 GB per device at N=8 -> neither fits
+    spec, tp = pl.select_strategy(70 * GBy, 80 * GBy, 8, layer_bytes=30 * GBy, fast_interconnect=True)
+    assert spec == pl.STRATEGIES["zero3"] and tp
+    assert pl.select_strategy(70 * GBy, 80 * GBy, 8, 30 * GBy, False) == (pl.STRATEGIES["zero3"], False)
+    assert pl.select_strategy(70 * GBy, 80 * GBy, 8, 20 * GBy, True) == (pl.STRATEGIES["zero3"], False)
+    # 1B: 16 GB < 56 GB -> data parallel; 7B: 112 GB, /8 = 14 GB -> ZeRO-3
+    assert pl.select_strategy(1 * GBy, 80 * GBy, 8)[0] == pl.STRATEGIES["dp"]
+    assert pl.select_strategy(7 * GBy, 80 * GBy, 8) == (pl.STRATEGIES["zero3"], False)
+    # strict inequalities at the boundary: 16P == 0.7 M_d is not "<"
+    assert pl.select_strategy(7, 160, 8)[0] == pl.STRATEGIES["zero3"]     # 112 == 0.7 * 160
+    assert pl.select_strategy(7, 161, 8)[0] == pl.STRATEGIES["dp"]
+    # on a 288 GB device the 7B model fits plain data parallelism (112 GB < 201.6 GB)
+    assert pl.select_strategy(7 * GBy, 288 * GBy, 8)[0] == pl.STRATEGIES["dp"]
+    assert pl.select_strategy(70 * GBy, 288 * GBy, 8)[0] == pl.STRATEGIES["zero3"]
