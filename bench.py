@@ -48,7 +48,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="70b_zero3",
                     choices=["tiny", "gpt2s", "7b_zero2", "70b_zero3", "13b_clip", "7b_zero1",
-                             "7b_accum4", "7b_verify"])
+                             "7b_accum4", "7b_verify", "7b_offload"])
     ap.add_argument("--pool-elems", type=int, default=1 << 21,
                     help="elements per contribution of the resident, repeating bucket source")
     ap.add_argument("--copy-engine", choices=["kernel", "memcpy"], default="kernel")
@@ -72,6 +72,8 @@ def main():
 
     if args.workload == "7b_verify":
         return verify_bench(args)
+    if args.workload == "7b_offload":
+        return offload_bench(args)
     w = WORKLOADS[args.workload]
     torch.cuda.set_device(0)
     info = ps.ps_device_info()
@@ -269,6 +271,61 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, bpe)
     print(json.dumps(result), flush=True)
+
+
+def offload_bench(args):
+    """ZeRO-Offload row: state in pinned host memory, streamed through three device slots."""
+    import torch
+
+    import paper_2601_02311_amd as ps
+    from synth import WORKLOADS
+    from synth import device as dgen
+
+    w = WORKLOADS["7b_offload"]
+    torch.cuda.set_device(0)
+    info = ps.ps_device_info()
+    n, N, B = w.shard_len, w.n_devices, (args.bucket_elems or w.bucket_elems)
+    spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi)
+    master, m, v = [t.cpu().pin_memory() for t in dgen.workload_state(w)]
+    out = torch.zeros(n, dtype=torch.bfloat16).pin_memory()
+    grads = dgen.workload_gradients(w, w.first_step)
+    slots = [torch.empty(14 * B, dtype=torch.uint8, device="cuda") for _ in range(3)]
+    s1, s2, s3 = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    plan = ps.ps_offload_plan_t()
+    plan.host_master, plan.host_m, plan.host_v, plan.host_param_out = (master.data_ptr(), m.data_ptr(),
+                                                                       v.data_ptr(), out.data_ptr())
+    plan.len, plan.valid_len, plan.bucket_elems, plan.n_slots = n, n, B, 3
+    for k, t in enumerate(slots):
+        plan.slot[k] = t.data_ptr()
+    plan.h2d_stream, plan.compute_stream, plan.d2h_stream = s1.cuda_stream, s2.cuda_stream, s3.cuda_stream
+    g = ps.make_grads([t.data_ptr() for t in grads], ps.PS_BF16)
+    t_no = [w.first_step]
+
+    def step():
+        hp = ps.ps_adamw_t(w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, t_no[0], 0.0, 0.0)
+        ps.ps_step_update_offloaded(spec, hp, plan, g)
+        torch.cuda.synchronize()       # the next step reads what this one wrote back
+        t_no[0] += 1
+    for _ in range(args.warmup):
+        step()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    up, down = 12 * n, 14 * n
+    log("%.3f ms/step: %.1f GB/s up, %.1f GB/s down over the host link" %
+        (ms_per_step, up / ms_per_step / 1e6, down / ms_per_step / 1e6))
+    print(json.dumps({
+        "metric": "offloaded shard reduce+AdamW+cast: host-link GB/s, elements/s",
+        "value": n / (ms_per_step * 1e-3), "unit": "elements/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "shard_elems": n, "n_devices": N, "bucket_elems": B,
+                   "slots": 3, "device": info.name.decode()},
+        "roofline": {"bound": "host link (PCIe, full duplex)", "achieved": down / ms_per_step / 1e6,
+                     "peak": 64.0, "unit": "GB/s", "frac": down / ms_per_step / 1e6 / 64.0,
+                     "traffic": None, "note": "the busier direction: 14 bytes per element device to host; "
+                     "peak is PCIe 5.0 x16 per direction"}}), flush=True)
 
 
 def verify_bench(args):

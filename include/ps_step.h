@@ -171,6 +171,27 @@ typedef struct ps_bucket_plan_t {
     uint64_t kernel_ms_len;     /* capacity of kernel_ms                                */
 } ps_bucket_plan_t;
 
+/* Offloaded optimizer state (Table 2, ZeRO-Offload: Theta and Omega in mode O,
+ * G sharded): master, m, v and the bf16 parameters of this shard live in pinned
+ * HOST memory and stream through the device in buckets. */
+typedef struct ps_offload_plan_t {
+    float *host_master;     /* pinned HOST, len floats, updated in place                 */
+    float *host_m;          /* pinned HOST, len floats                                   */
+    float *host_v;          /* pinned HOST, len floats                                   */
+    void *host_param_out;   /* pinned HOST, len bf16: the updated 16-bit parameters      */
+    uint64_t len;           /* shard length n = psi_padded / N                           */
+    uint64_t valid_len;     /* elements [valid_len, len) are never read or written       */
+    uint64_t bucket_elems;  /* multiple of 8                                             */
+    uint32_t n_slots;       /* 2 or 3 DEVICE slots; 3 lets upload, update and download
+                               of neighbouring buckets run at the same time             */
+    uint32_t reserved;      /* must be 0                                                 */
+    void *slot[3];          /* DEVICE, each 14 * bucket_elems bytes, 16-byte aligned:
+                               master | m | v (FP32) | parameters (bf16) of one bucket  */
+    void *h2d_stream;       /* hipStream_t; the three streams must differ                */
+    void *compute_stream;
+    void *d2h_stream;
+} ps_offload_plan_t;
+
 typedef struct ps_device_info_t {
     char name[128];
     char arch[64];
@@ -287,6 +308,18 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
 ps_status_t ps_step_accumulate(const ps_spec_t *spec, const ps_grads_t *grads, float *accum,
                                int32_t overwrite, uint64_t elem_offset, uint64_t elem_count,
                                uint64_t valid_len, void *stream);
+
+/* The same step with the optimizer state offloaded to pinned host memory
+ * (Definition 1, Eq. 5: mode O holds nothing on the GPU).  Requires theta ==
+ * PS_O, omega == PS_O, grad == PS_S.  grads->contrib[r] points at element 0 of
+ * this shard's slice of contribution r in DEVICE memory (n_contrib ==
+ * n_devices, or 1 with PS_F32).  Per bucket: three host-to-device copies on
+ * h2d_stream, the update kernel on compute_stream, four device-to-host copies on
+ * d2h_stream, ordered by events; nothing waits on the host.  The caller
+ * synchronises d2h_stream before reading the host buffers.  The path is bound by
+ * the host link (12 bytes in, 14 bytes out per element), not by HBM. */
+ps_status_t ps_step_update_offloaded(const ps_spec_t *spec, const ps_adamw_t *hp,
+                                     const ps_offload_plan_t *plan, const ps_grads_t *grads);
 
 /* Bytes of DEVICE workspace ps_step_reduce_sumsq needs for a call over
  * elem_count elements (about elem_count / 128 bytes; host-only query). */

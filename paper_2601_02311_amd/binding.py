@@ -18,12 +18,12 @@ __all__ = [
     "PS_R", "PS_S", "PS_SG", "PS_M", "PS_O", "PS_BF16", "PS_F32", "PS_MAX_CONTRIB", "PS_COPY_KERNEL", "PS_COPY_MEMCPY", "PS_SCHED_AUTO", "PS_SCHED_OVERLAP", "PS_SCHED_ALTERNATE",
     "PS_OK", "PS_EINVAL", "PS_EUNSUPPORTED", "PS_EALIGN", "PS_ERANGE", "PS_ENODEVICE", "PS_EHIP",
     "PsError", "ps_spec_t", "ps_cost_t", "ps_adamw_t", "ps_shard_t", "ps_grads_t",
-    "ps_bucket_plan_t", "ps_device_info_t", "library", "library_path",
+    "ps_bucket_plan_t", "ps_offload_plan_t", "ps_device_info_t", "library", "library_path",
     "ps_abi_version", "ps_status_string", "ps_last_error", "ps_spec_preset", "ps_cost_eval",
     "ps_device_info", "ps_step_update", "ps_step_update_bucketed", "ps_workspace_bytes",
     "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
     "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum",
-    "ps_select_strategy", "ps_compose_index", "EXPORTED_SYMBOLS",
+    "ps_select_strategy", "ps_compose_index", "ps_step_update_offloaded", "EXPORTED_SYMBOLS",
 ]
 
 PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
@@ -38,7 +38,7 @@ EXPORTED_SYMBOLS = (
     "ps_device_info", "ps_step_update", "ps_step_update_bucketed", "ps_workspace_bytes",
     "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
     "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum",
-    "ps_select_strategy", "ps_compose_index",
+    "ps_select_strategy", "ps_compose_index", "ps_step_update_offloaded",
 )
 
 
@@ -92,6 +92,14 @@ class ps_bucket_plan_t(C.Structure):
                 ("kernel_ms", C.POINTER(C.c_float)), ("kernel_ms_len", C.c_uint64)]
 
 
+class ps_offload_plan_t(C.Structure):
+    _fields_ = [("host_master", C.c_void_p), ("host_m", C.c_void_p), ("host_v", C.c_void_p),
+                ("host_param_out", C.c_void_p), ("len", C.c_uint64), ("valid_len", C.c_uint64),
+                ("bucket_elems", C.c_uint64), ("n_slots", C.c_uint32), ("reserved", C.c_uint32),
+                ("slot", C.c_void_p * 3), ("h2d_stream", C.c_void_p),
+                ("compute_stream", C.c_void_p), ("d2h_stream", C.c_void_p)]
+
+
 class ps_device_info_t(C.Structure):
     _fields_ = [("name", C.c_char * 128), ("arch", C.c_char * 64),
                 ("compute_units", C.c_int32), ("wavefront_size", C.c_int32),
@@ -141,6 +149,10 @@ def library():
         L.ps_step_update_bucketed.argtypes = [C.POINTER(ps_spec_t), C.POINTER(ps_adamw_t),
                                               C.POINTER(ps_shard_t),
                                               C.POINTER(ps_bucket_plan_t)]
+        L.ps_step_update_offloaded.restype = C.c_int
+        L.ps_step_update_offloaded.argtypes = [C.POINTER(ps_spec_t), C.POINTER(ps_adamw_t),
+                                               C.POINTER(ps_offload_plan_t),
+                                               C.POINTER(ps_grads_t)]
         L.ps_workspace_bytes.restype = C.c_uint64
         L.ps_workspace_bytes.argtypes = [C.c_uint64]
         L.ps_step_reduce_sumsq.restype = C.c_int
@@ -252,6 +264,10 @@ def ps_step_update(spec, hp, shard, grads, elem_offset, elem_count, stream=0):
 
 def ps_step_update_bucketed(spec, hp, shard, plan):
     _check(library().ps_step_update_bucketed(_ref(spec), _ref(hp), _ref(shard), _ref(plan)))
+
+
+def ps_step_update_offloaded(spec, hp, plan, grads):
+    _check(library().ps_step_update_offloaded(_ref(spec), _ref(hp), _ref(plan), _ref(grads)))
 
 
 def ps_workspace_bytes(elem_count):

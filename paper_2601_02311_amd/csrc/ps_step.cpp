@@ -672,6 +672,151 @@ ps_status_t ps_verify_checksum(const void *buf, uint64_t bytes, uint64_t first_w
     return PS_OK;
 }
 
+ps_status_t ps_step_update_offloaded(const ps_spec_t *spec, const ps_adamw_t *hp,
+                                     const ps_offload_plan_t *plan, const ps_grads_t *grads)
+{
+    clear_error();
+    ps_status_t st;
+    if ((st = check_spec(spec)) != PS_OK || (st = check_hp(hp)) != PS_OK)
+        return st;
+    if (spec->theta != PS_O || spec->omega != PS_O || spec->grad != PS_S) {
+        set_error("offloaded step needs pi_Theta = O, pi_Omega = O, pi_G = S");
+        return PS_EUNSUPPORTED;
+    }
+    if (!plan || !grads) {
+        set_error("plan or grads is NULL");
+        return PS_EINVAL;
+    }
+    if (!plan->host_master || !plan->host_m || !plan->host_v || !plan->host_param_out) {
+        set_error("plan has a NULL host buffer");
+        return PS_EINVAL;
+    }
+    if (plan->reserved != 0 || (plan->n_slots != 2 && plan->n_slots != 3)) {
+        set_error("n_slots must be 2 or 3, reserved 0");
+        return PS_EINVAL;
+    }
+    for (uint32_t k = 0; k < plan->n_slots; ++k) {
+        if (!plan->slot[k]) {
+            set_error("slot %u is NULL", k);
+            return PS_EINVAL;
+        }
+        if (!aligned16(plan->slot[k])) {
+            set_error("slot %u is not 16-byte aligned", k);
+            return PS_EALIGN;
+        }
+        for (uint32_t j = 0; j < k; ++j)
+            if (plan->slot[j] == plan->slot[k]) {
+                set_error("slots must be distinct");
+                return PS_EINVAL;
+            }
+    }
+    if (plan->bucket_elems == 0 || plan->bucket_elems % 8 != 0) {
+        set_error("bucket_elems must be a positive multiple of 8");
+        return PS_EALIGN;
+    }
+    if (!aligned16(plan->host_master) || !aligned16(plan->host_m) || !aligned16(plan->host_v) ||
+        !aligned16(plan->host_param_out)) {
+        set_error("host buffer not 16-byte aligned");
+        return PS_EALIGN;
+    }
+    if (plan->h2d_stream == plan->compute_stream || plan->h2d_stream == plan->d2h_stream ||
+        plan->compute_stream == plan->d2h_stream) {
+        set_error("the three streams must differ");
+        return PS_EINVAL;
+    }
+    uint64_t padded, off, len, valid;
+    if ((st = shard_geometry(spec, &padded, &off, &len, &valid)) != PS_OK)
+        return st;
+    if (plan->len != len || plan->valid_len > plan->len) {
+        set_error("plan.len %llu differs from psi_padded/N = %llu, or valid_len exceeds it",
+                  (unsigned long long)plan->len, (unsigned long long)len);
+        return PS_ERANGE;
+    }
+    if ((st = check_contribs(grads->contrib, grads->n_contrib, grads->dtype, spec->n_devices,
+                             "contribution")) != PS_OK)
+        return st;
+    const uint64_t B = plan->bucket_elems;
+    const uint64_t n_buckets = (plan->valid_len + B - 1) / B;
+    if (n_buckets == 0)
+        return PS_OK;
+    if ((st = need_device()) != PS_OK)
+        return st;
+
+    hipStream_t up = reinterpret_cast<hipStream_t>(plan->h2d_stream);
+    hipStream_t comp = reinterpret_cast<hipStream_t>(plan->compute_stream);
+    hipStream_t down = reinterpret_cast<hipStream_t>(plan->d2h_stream);
+    const StepScalars s = derive_scalars(*hp, spec->n_devices);
+    const uint64_t eb = elem_bytes(grads->dtype);
+    const uint32_t S = plan->n_slots;
+    hipEvent_t loaded[3] = {}, computed[3] = {}, drained[3] = {};
+    hipError_t e = hipSuccess;
+    const char *what = "";
+#define PS_TRY(call)                                                                              \
+    do {                                                                                          \
+        if (e == hipSuccess) {                                                                    \
+            e = (call);                                                                           \
+            what = #call;                                                                         \
+        }                                                                                         \
+    } while (0)
+    for (uint32_t k = 0; k < S; ++k) {
+        PS_TRY(hipEventCreateWithFlags(&loaded[k], hipEventDisableTiming));
+        PS_TRY(hipEventCreateWithFlags(&computed[k], hipEventDisableTiming));
+        PS_TRY(hipEventCreateWithFlags(&drained[k], hipEventDisableTiming));
+    }
+    for (uint64_t b = 0; b < n_buckets && e == hipSuccess; ++b) {
+        const uint32_t k = (uint32_t)(b % S);
+        const uint64_t lo = b * B;
+        const uint64_t cnt = clamp_count(lo, B, plan->valid_len);
+        char *slot = reinterpret_cast<char *>(plan->slot[k]);
+        float *d_master = reinterpret_cast<float *>(slot);
+        float *d_m = reinterpret_cast<float *>(slot + 4 * B);
+        float *d_v = reinterpret_cast<float *>(slot + 8 * B);
+        uint16_t *d_out = reinterpret_cast<uint16_t *>(slot + 12 * B);
+        // upload: the slot is free once bucket b - S has been written back
+        if (b >= S)
+            PS_TRY(hipStreamWaitEvent(up, drained[k], 0));
+        PS_TRY(hipMemcpyAsync(d_master, plan->host_master + lo, cnt * 4, hipMemcpyHostToDevice, up));
+        PS_TRY(hipMemcpyAsync(d_m, plan->host_m + lo, cnt * 4, hipMemcpyHostToDevice, up));
+        PS_TRY(hipMemcpyAsync(d_v, plan->host_v + lo, cnt * 4, hipMemcpyHostToDevice, up));
+        PS_TRY(hipEventRecord(loaded[k], up));
+        // update in the slot
+        PS_TRY(hipStreamWaitEvent(comp, loaded[k], 0));
+        if (e == hipSuccess) {
+            ContribPtrs g;
+            std::memset(&g, 0, sizeof g);
+            for (uint32_t r = 0; r < grads->n_contrib; ++r)
+                g.p[r] = reinterpret_cast<const char *>(grads->contrib[r]) + lo * eb;
+            int le = launch_update(grads->dtype, grads->n_contrib, g, d_master, d_m, d_v, d_out, cnt,
+                                   s, comp);
+            if (le != 0) {
+                e = (hipError_t)le;
+                what = "update kernel launch";
+            }
+        }
+        PS_TRY(hipEventRecord(computed[k], comp));
+        // download
+        PS_TRY(hipStreamWaitEvent(down, computed[k], 0));
+        PS_TRY(hipMemcpyAsync(plan->host_master + lo, d_master, cnt * 4, hipMemcpyDeviceToHost, down));
+        PS_TRY(hipMemcpyAsync(plan->host_m + lo, d_m, cnt * 4, hipMemcpyDeviceToHost, down));
+        PS_TRY(hipMemcpyAsync(plan->host_v + lo, d_v, cnt * 4, hipMemcpyDeviceToHost, down));
+        PS_TRY(hipMemcpyAsync(reinterpret_cast<uint16_t *>(plan->host_param_out) + lo, d_out, cnt * 2,
+                              hipMemcpyDeviceToHost, down));
+        PS_TRY(hipEventRecord(drained[k], down));
+    }
+#undef PS_TRY
+    for (uint32_t k = 0; k < S; ++k) {
+        if (loaded[k])
+            (void)hipEventDestroy(loaded[k]);
+        if (computed[k])
+            (void)hipEventDestroy(computed[k]);
+        if (drained[k])
+            (void)hipEventDestroy(drained[k]);
+    }
+    if (e != hipSuccess)
+        return hip_fail(e, what);
+    return PS_OK;
+}
+
 ps_status_t ps_probe_copy(void *dst, const void *src, uint64_t bytes, void *stream)
 {
     clear_error();

@@ -433,6 +433,41 @@ def test_gradient_accumulation_then_update(dtype, N):
     assert assert_state_parity([host(x) for x in (th, m, v, p)], want, "accumulated") == 0
 
 
+# ---- offloaded optimizer state (ZeRO-Offload row) ----
+
+@pytest.mark.parametrize("n_slots,dtype,N", [(3, "bf16", 4), (2, "bf16", 4), (3, "f32", 6)])
+def test_offloaded_state_streams_through_the_device(n_slots, dtype, N):
+    n = 5 * TILE + 100
+    valid = n - 3
+    bucket = TILE + 8
+    _say("offload n=%d bucket=%d slots=%d N=%d %s" % (n, bucket, n_slots, N, dtype))
+    spec = ps.ps_spec_preset("zero_offload", N, 2, n * N)
+    grads = [gen.gradient(n, 111, 0, r, dtype) for r in range(N)]
+    state = [gen.master(n, 111), *gen.moments(n, 111, True), np.full(n, 0x5555, np.uint16)]
+    hpd, hp = hp_of(None, 12)
+    want = [a.copy() for a in state]
+    orc.step_f32(grads, orc.derive_scalars(t=12, n_devices=N, **hpd), *want, lo=0, hi=valid)
+    pinned = [torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).pin_memory()
+              for a in state]
+    gd = [dev(g) for g in grads]
+    slots = [torch.zeros(14 * bucket, dtype=torch.uint8, device="cuda") for _ in range(n_slots)]
+    s1, s2, s3 = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    plan = ps.ps_offload_plan_t()
+    plan.host_master, plan.host_m, plan.host_v, plan.host_param_out = [t.data_ptr() for t in pinned]
+    plan.len, plan.valid_len, plan.bucket_elems, plan.n_slots = n, valid, bucket, n_slots
+    for k, t in enumerate(slots):
+        plan.slot[k] = t.data_ptr()
+    plan.h2d_stream, plan.compute_stream, plan.d2h_stream = s1.cuda_stream, s2.cuda_stream, s3.cuda_stream
+    ps.ps_step_update_offloaded(spec, hp, plan, grads_of(gd, dtype))
+    torch.cuda.synchronize()
+    got = [t.numpy().copy() for t in pinned]
+    got[3] = got[3].view(np.uint16)
+    assert assert_state_parity(got, want, "offload") == 0
+    for g, a in zip(got, state):                                   # pad untouched on the host
+        assert np.array_equal(g[valid:].view(np.uint8), a[valid:].view(np.uint8))
+
+
 # ---- verification protocol kernels ----
 
 @pytest.mark.parametrize("dtype,n", [("f32", 9 * TILE + 777), ("bf16", 9 * TILE + 777),

@@ -185,6 +185,45 @@ def test_bucketed_rejects_bad_arguments():
     assert _status(lambda: run(spec, hp, shard, plan(kernel_ms=ms, kernel_ms_len=2))) == ps.PS_ERANGE
 
 
+def test_offloaded_rejects_bad_arguments():
+    spec = ps.ps_spec_preset("zero_offload", 4, 1, 4096)
+    _, hp, _, grads = _valid()
+
+    def plan(**kw):
+        p = ps.ps_offload_plan_t()
+        p.host_master, p.host_m, p.host_v, p.host_param_out = FAKE, FAKE * 2, FAKE * 3, FAKE * 4
+        p.len, p.valid_len, p.bucket_elems, p.n_slots = 1024, 1024, 256, 3
+        p.slot[0], p.slot[1], p.slot[2] = FAKE * 5, FAKE * 6, FAKE * 7
+        p.h2d_stream, p.compute_stream, p.d2h_stream = 0x100, 0x200, 0x300
+        for k, v in kw.items():
+            if k.startswith("slot"):
+                p.slot[int(k[4])] = v
+            else:
+                setattr(p, k, v)
+        return p
+    run = ps.ps_step_update_offloaded
+    assert _status(lambda: run(spec, hp, None, grads)) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, plan(), None)) == ps.PS_EINVAL
+    z3 = ps.ps_spec_preset("zero3", 4, 1, 4096)
+    assert _status(lambda: run(z3, hp, plan(), grads)) == ps.PS_EUNSUPPORTED
+    assert _status(lambda: run(spec, hp, plan(host_m=0), grads)) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, plan(n_slots=1), grads)) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, plan(n_slots=4), grads)) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, plan(slot1=0), grads)) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, plan(slot1=FAKE * 5), grads)) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, plan(slot2=FAKE * 7 + 8), grads)) == ps.PS_EALIGN
+    assert _status(lambda: run(spec, hp, plan(bucket_elems=100), grads)) == ps.PS_EALIGN
+    assert _status(lambda: run(spec, hp, plan(d2h_stream=0x100), grads)) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, plan(len=1000), grads)) == ps.PS_ERANGE
+    assert _status(lambda: run(spec, hp, plan(valid_len=1025), grads)) == ps.PS_ERANGE
+    missing = ps.make_grads([FAKE] * 3, ps.PS_BF16)
+    assert _status(lambda: run(spec, hp, plan(), missing)) == ps.PS_EINVAL
+    run(spec, hp, plan(valid_len=0), grads)                       # nothing valid: no work, no device needed
+    # the resident-state entry point refuses the offloaded placement
+    shard = ps.ps_shard_t(FAKE, FAKE, FAKE, FAKE, 1024, 1024)
+    assert _status(lambda: ps.ps_step_update(spec, hp, shard, grads, 0, 8)) == ps.PS_EUNSUPPORTED
+
+
 def test_verification_calls_validation():
     ws = ps.ps_verify_workspace_bytes(4096)
     assert ws >= 2 * 1024 * 8
