@@ -406,34 +406,46 @@ struct ScanArgs {
     uint32_t partial_slot;
 };
 
-// Sums of (a-b)^2 and a^2 in binary64 over whole 256-element tiles; workgroup b
-// owns tiles [4b, 4b+4) and issues all of their loads before the arithmetic.
+// Sums of (a-b)^2 and a^2 in binary64.  Read-only, so every lane takes 16 bytes
+// per buffer whatever the element type: a scan tile is 1 KiB per buffer (256
+// fp32 or 512 bf16 elements).  Workgroup b owns tiles [4b, 4b+4) and issues all
+// of their loads before the arithmetic.
 template <typename G>
 __global__ __launch_bounds__(kWave) void diff_sumsq_tiles(const ScanArgs s)
 {
     constexpr int K = kReduceTilesPerGroup;
     double sd = 0.0, sa = 0.0;
     const uint64_t t0 = (uint64_t)blockIdx.x * K;
-    f32x4 x[K], y[K];
+    u32x4 x[K], y[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-        const uint64_t e = (t0 + k) * kTileElems + (uint64_t)threadIdx.x * 4;
+        const uint64_t vec = (t0 + k) * kWave + threadIdx.x;
         if (t0 + k < s.n_tiles) {
-            x[k] = load_contrib4<G, true>(s.a, e);
-            y[k] = load_contrib4<G, true>(s.b, e);
+            x[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.a) + vec);
+            y[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.b) + vec);
         } else {
-            x[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+            x[k] = u32x4{0u, 0u, 0u, 0u};
             y[k] = x[k];
         }
     }
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-        const float xs[4] = {x[k].x, x[k].y, x[k].z, x[k].w}, ys[4] = {y[k].x, y[k].y, y[k].z, y[k].w};
+        const uint32_t xw[4] = {x[k].x, x[k].y, x[k].z, x[k].w}, yw[4] = {y[k].x, y[k].y, y[k].z, y[k].w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const double d = (double)xs[i] - (double)ys[i];
-            sd += d * d;
-            sa += (double)xs[i] * (double)xs[i];
+            if constexpr (sizeof(G) == 2) {
+                const double xl = (double)widen_lo(xw[i]), xh = (double)widen_hi(xw[i]);
+                const double dl = xl - (double)widen_lo(yw[i]), dh = xh - (double)widen_hi(yw[i]);
+                sd += dl * dl;
+                sa += xl * xl;
+                sd += dh * dh;
+                sa += xh * xh;
+            } else {
+                const double xv = (double)__uint_as_float(xw[i]);
+                const double d = xv - (double)__uint_as_float(yw[i]);
+                sd += d * d;
+                sa += xv * xv;
+            }
         }
     }
     sd = wave_sum(sd);

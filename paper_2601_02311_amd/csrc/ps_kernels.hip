@@ -62,10 +62,13 @@ static int launch_update_t(uint32_t n_contrib, const ContribPtrs &g, float *mast
         switch (n_contrib) {
         case 1: launch_update_n<1, G>(a, grid, st); break;
         case 2: launch_update_n<2, G>(a, grid, st); break;
+        case 3: launch_update_n<3, G>(a, grid, st); break;
         case 4: launch_update_n<4, G>(a, grid, st); break;
+        case 5: launch_update_n<5, G>(a, grid, st); break;
         case 6: launch_update_n<6, G>(a, grid, st); break;
+        case 7: launch_update_n<7, G>(a, grid, st); break;
         case 8: launch_update_n<8, G>(a, grid, st); break;
-        default: launch_update_n<0, G>(a, grid, st); break;
+        default: launch_update_n<0, G>(a, grid, st); break; // 9..16: contribution loop not unrolled
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
@@ -124,10 +127,13 @@ static int launch_accum_t(uint32_t n_contrib, const ContribPtrs &g, float *accum
         switch (n_contrib) {
         case 1: launch_accum_n<1, G>(a, grid, st); break;
         case 2: launch_accum_n<2, G>(a, grid, st); break;
+        case 3: launch_accum_n<3, G>(a, grid, st); break;
         case 4: launch_accum_n<4, G>(a, grid, st); break;
+        case 5: launch_accum_n<5, G>(a, grid, st); break;
         case 6: launch_accum_n<6, G>(a, grid, st); break;
+        case 7: launch_accum_n<7, G>(a, grid, st); break;
         case 8: launch_accum_n<8, G>(a, grid, st); break;
-        default: launch_accum_n<0, G>(a, grid, st); break;
+        default: launch_accum_n<0, G>(a, grid, st); break; // 9..16: contribution loop not unrolled
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
@@ -224,10 +230,13 @@ static int launch_reduce_t(uint32_t n_contrib, const ContribPtrs &g, float gs, f
         switch (n_contrib) {
         case 1: launch_reduce_n<1, G>(a, grid, st); break;
         case 2: launch_reduce_n<2, G>(a, grid, st); break;
+        case 3: launch_reduce_n<3, G>(a, grid, st); break;
         case 4: launch_reduce_n<4, G>(a, grid, st); break;
+        case 5: launch_reduce_n<5, G>(a, grid, st); break;
         case 6: launch_reduce_n<6, G>(a, grid, st); break;
+        case 7: launch_reduce_n<7, G>(a, grid, st); break;
         case 8: launch_reduce_n<8, G>(a, grid, st); break;
-        default: launch_reduce_n<0, G>(a, grid, st); break;
+        default: launch_reduce_n<0, G>(a, grid, st); break; // 9..16: contribution loop not unrolled
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
@@ -278,8 +287,9 @@ template <typename G>
 static int launch_diff_t(const void *a, const void *b, uint64_t count, double *out2,
                          int accumulate, uint64_t *workspace, uint64_t slots, hipStream_t st)
 {
-    const uint64_t n_tiles = count / kTileElems;
-    const uint64_t body = n_tiles * kTileElems;
+    constexpr uint64_t kScanTile = kWave * (16 / sizeof(G)); // elements in 1 KiB
+    const uint64_t n_tiles = count / kScanTile;
+    const uint64_t body = n_tiles * kScanTile;
     const uint64_t groups = scan_groups(n_tiles);
     if (groups > kMaxGrid)
         return (int)hipErrorInvalidConfiguration;
