@@ -196,3 +196,33 @@ def test_13b_clip_ragged_full_shard_sampled():
     _whole_shard_properties(master, m, v, out, valid)
     del master, m, v, out, red, grads, ws
     torch.cuda.empty_cache()
+
+
+def test_single_launch_beyond_2_32_elements():
+    """Maximum size in one launch: the whole 70B shard (8.75e9 elements, 34 million
+    workgroups) updated from one pre-reduced fp32 gradient; element indices pass 2^32
+    and byte offsets pass 2^35.  Sampled slices straddle 2^31, 2^32 and 2^33."""
+    w = WORKLOADS["70b_zero3"]
+    _need(165)
+    n, N, t = w.shard_len, w.n_devices, w.first_step
+    _say("single launch over n=%d elements (fp32 pre-reduced gradient)" % n)
+    spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi)
+    master, m, v = dgen.workload_state(w)
+    g = dgen.fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), 1e-4, w.seed, 9)
+    out = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    sl = _slices(n, extra=[((1 << 31) - 4096, (1 << 31) + 4096), ((1 << 32) - 4096, (1 << 32) + 4096),
+                           ((1 << 33) - 4096, (1 << 33) + 4096)])
+    before = [([_take(x, lo, hi) for x in (master, m, v)], [_take(g, lo, hi)]) for lo, hi in sl]
+    hpd, hp = _hp(w, t, grad_scale=1.0)
+    ps.ps_step_update(spec, hp, shard_of(master, m, v, out, n),
+                      ps.make_grads([g.data_ptr()], ps.PS_F32), 0, n, stream_handle())
+    torch.cuda.synchronize()
+    s = orc.derive_scalars(t=t, n_devices=N, grad_scale=1.0, **hpd)
+    for (lo, hi), (st, gr) in zip(sl, before):
+        want = [a.copy() for a in st] + [np.zeros(hi - lo, np.uint16)]
+        orc.step_f32(gr, s, *want)
+        got = [_take(x, lo, hi) for x in (master, m, v, out)]
+        assert assert_state_parity(got, want, "big [%d,%d)" % (lo, hi)) == 0
+    _whole_shard_properties(master, m, v, out, n)
+    del master, m, v, g, out
+    torch.cuda.empty_cache()
