@@ -257,7 +257,8 @@ def main():
                                      (args.pool_elems, args.copy_engine, args.schedule)) if bucketed else None,
                    "bytes_per_elem": bpe, "step_GBps": bpe * elems_per_step / (ms_per_step * 1e-3) / 1e9,
                    "device": info.name.decode(), "arch": info.arch.decode(),
-                   "compute_units": info.compute_units},
+                   "compute_units": info.compute_units, "memory_clock_khz": info.memory_clock_khz,
+                   "memory_bus_bits": info.memory_bus_bits, "hbm_total_GB": info.total_bytes / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBS,
                      "traffic": measured_traffic(w, elems_per_launch),
@@ -265,7 +266,8 @@ def main():
                                 "accumulate_tiles x%d + update_tiles" % w.micro_batches
                                 if w.micro_batches > 1 else "update_tiles"),
                      "elems_per_launch": elems_per_launch, "avg_launch_ms": avg_ms,
-                     "launches_timed": len(kernel_ms)},
+                     "median_launch_ms": sorted(kernel_ms)[len(kernel_ms) // 2],
+                     "best_launch_ms": min(kernel_ms), "launches_timed": len(kernel_ms)},
         "extras": extras,
     }
     if not args.no_cpu_baseline:
@@ -446,10 +448,21 @@ def cpu_baseline(w, bpe):
     reps = max(1, min(2000, int(12.0 / max(first, 1e-3))))
     total = sum(one_pass() for _ in range(reps))
     rate = sample * reps / total
-    log("cpu oracle: %d threads, %d x %d elements in %.1f s -> %.3e elements/s" %
-        (cores, reps, sample, total, rate))
+    # and one thread alone on an eighth of the sample
+    t0 = time.perf_counter()
+    orc.step_f32(grads, s, th, m, v, p, 0, sample // 8)
+    single = (sample // 8) / (time.perf_counter() - t0)
+    cpu = "?"
+    try:
+        cpu = [l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name")][0]
+    except (OSError, IndexError):
+        pass
+    log("cpu oracle on %s (%d logical cpus): %d threads, %d x %d elements in %.1f s -> %.3e "
+        "elements/s; one thread %.3e elements/s" %
+        (cpu, os.cpu_count() or 0, cores, reps, sample, total, rate, single))
     return {"value": rate, "unit": "elements/s", "cores": cores, "kind": "oracle",
-            "GBps": rate * bpe / 1e9,
+            "GBps": rate * bpe / 1e9, "single_thread_value": single, "cpu_model": cpu,
+            "logical_cpus": os.cpu_count(),
             "sample": "%d passes over the first %d elements of the shard (%s gradients, N=%d), "
                       "split into %d contiguous ranges" % (reps, sample, w.grad_dtype, w.n_devices, cores)}
 
