@@ -445,7 +445,7 @@ def cpu_baseline(w, bpe):
             t.join()
         return time.perf_counter() - t0
     first = one_pass()
-    reps = max(1, min(2000, int(12.0 / max(first, 1e-3))))
+    reps = max(1, min(2000, int(15.0 / max(first, 1e-3))))
     total = sum(one_pass() for _ in range(reps))
     rate = sample * reps / total
     # and one thread alone on an eighth of the sample

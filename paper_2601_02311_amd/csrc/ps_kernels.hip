@@ -6,16 +6,37 @@
 namespace ps {
 
 // Dynamic LDS requested by the streaming launches.  The kernels never touch it:
-// with 160 KiB of LDS per CU it holds residency at 8 single-wave workgroups per
-// CU (4 for the reduce pass, whose groups walk four tiles each), which is where
-// the HBM request stream stays narrow enough to run at ~6.6 TB/s on MI355X.
-constexpr uint32_t kUpdateLdsBytes = 20480;
-constexpr uint32_t kReduceLdsBytes = 40960;
+// with 160 KiB of LDS per CU it caps how many single-wave workgroups are
+// resident per CU, which is what keeps the HBM request stream narrow.  The best
+// cap depends on how many bytes one wave keeps in flight; measured on MI355X:
+//   update, 8 bf16 contributions (7 KiB per wave)        8 waves per CU  6.6 TB/s
+//   update, 2..4 bf16 contributions (4-5 KiB)            8-10 waves      6.6 TB/s
+//   update, one contribution (3.5-4 KiB)                 10-12 waves     6.6 TB/s
+//   accumulate (4.5-5 KiB, one store)                    12 waves        6.5-6.7 TB/s
+//   reduce + sum of squares, four tiles per workgroup    6 waves (fp32), 8 (bf16)
+// Two waves fewer or four more than the best cost 5-10 %.
+constexpr uint32_t lds_for_waves(uint32_t waves_per_cu)
+{
+    return (163840u / waves_per_cu) & ~255u;
+}
+
+static uint32_t update_lds(uint32_t n_contrib, int dtype)
+{
+    if (n_contrib == 1)
+        return lds_for_waves(dtype == PS_BF16 ? 12 : 10);
+    const uint32_t in_flight = n_contrib * (dtype == PS_BF16 ? 512u : 1024u) + 3072u;
+    return lds_for_waves(in_flight <= 4608u ? 10 : 8);
+}
+
+constexpr uint32_t kAccumLdsBytes = lds_for_waves(12);
+
+static uint32_t reduce_lds(int dtype) { return lds_for_waves(dtype == PS_BF16 ? 8 : 6); }
+
 // The staging copy, when it has the device to itself, runs best with the same cap
 // (8 waves of 4 KiB in flight per CU: 6.8 TB/s of writes from an L2-resident
 // source).  When it shares the device with the update kernel it asks for no LDS,
 // so that it never waits behind the update's own LDS reservations.
-constexpr uint32_t kStageAloneLdsBytes = 20480;
+constexpr uint32_t kStageAloneLdsBytes = lds_for_waves(8);
 // The read-only verification scans have one or two streams, 4-8 KiB in flight per
 // wave; they run with residency uncapped.
 constexpr uint32_t kScanLdsBytes = 0;
@@ -38,7 +59,8 @@ static const void *advance(const void *p, uint64_t elems)
 template <int N, typename G>
 static void launch_update_n(const UpdateArgs &a, uint32_t grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((update_tiles<N, G>), dim3(grid), dim3(kWave), kUpdateLdsBytes, st, a);
+    const uint32_t lds = update_lds(a.n_contrib, sizeof(G) == 2 ? PS_BF16 : PS_F32);
+    hipLaunchKernelGGL((update_tiles<N, G>), dim3(grid), dim3(kWave), lds, st, a);
 }
 
 template <typename G>
@@ -105,9 +127,9 @@ template <int N, typename G>
 static void launch_accum_n(const AccumArgs &a, uint32_t grid, hipStream_t st)
 {
     if (a.overwrite)
-        hipLaunchKernelGGL((accumulate_tiles<N, G, true>), dim3(grid), dim3(kWave), kUpdateLdsBytes, st, a);
+        hipLaunchKernelGGL((accumulate_tiles<N, G, true>), dim3(grid), dim3(kWave), kAccumLdsBytes, st, a);
     else
-        hipLaunchKernelGGL((accumulate_tiles<N, G, false>), dim3(grid), dim3(kWave), kUpdateLdsBytes, st, a);
+        hipLaunchKernelGGL((accumulate_tiles<N, G, false>), dim3(grid), dim3(kWave), kAccumLdsBytes, st, a);
 }
 
 template <typename G>
@@ -201,7 +223,8 @@ static int fold_to_one(const T *level1, T *level2, uint64_t n, T *out, int accum
 template <int N, typename G>
 static void launch_reduce_n(const ReduceArgs &a, uint32_t grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((reduce_sumsq_tiles<N, G>), dim3(grid), dim3(kWave), kReduceLdsBytes, st, a);
+    hipLaunchKernelGGL((reduce_sumsq_tiles<N, G>), dim3(grid), dim3(kWave),
+                       reduce_lds(sizeof(G) == 2 ? PS_BF16 : PS_F32), st, a);
 }
 
 template <typename G>
