@@ -79,7 +79,13 @@ __device__ __forceinline__ uint32_t narrow_bf16(float x)
     return (u & 0x7fffffffu) > 0x7f800000u ? nan : r;
 }
 
-// The per-element update.  acc is the fixed-order sum of the contributions.
+// The per-element update.  acc is the fixed-order sum of the N per-device
+// contributions (the Reduce-Scatter result of Section 2.3 for this element; one
+// data type and one order for all of them, Theorem 4).  acc * gs is the
+// global-batch mean that gradient integrity requires (Theorem 3, Eq. 15; the
+// division by N of the proof of Theorem 5).  m, v and th are the FP32 Adam moments
+// and master weight of Table 1; the paper prints no Adam formula, the textbook
+// bias-corrected form with decoupled decay is used in this exact operation order.
 __device__ __forceinline__ void step_element(float acc, float &th, float &m, float &v,
                                              const StepScalars &s)
 {
@@ -148,7 +154,10 @@ struct UpdateArgs {
     StepScalars s;
 };
 
-// Fused reduce + AdamW + bf16 cast over whole tiles, one wave per tile.
+// Fused reduce + AdamW + bf16 cast over whole tiles, one wave per tile.  Each
+// device runs this on its own shard only (proof of Corollary 1, part 1); the bf16
+// image it writes is the persistent S* shard that the next All-Gather reads
+// (Definition 1, Eq. 3), or this shard's slice of the replicated parameters.
 //   N : contribution count known at compile time, 0 = read it from args
 //   G : uint16_t (bf16 bits) or float
 // The loop only repeats when there are more tiles than the grid can hold.
@@ -263,6 +272,9 @@ __global__ __launch_bounds__(kWave) void accumulate_tail(const AccumArgs a)
 }
 
 // ---- sum of squares: the only place that needs cross-lane traffic ----
+// No atomics anywhere: the paper's determinism assumption (Theorem 5, assumption 1)
+// names atomics in reductions as what breaks it (Remark 3).  Every tree below has a
+// shape that depends only on the element count.
 
 // Butterfly over the 64 lanes; every lane ends with the same bits.
 template <typename T>
