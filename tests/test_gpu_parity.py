@@ -634,3 +634,80 @@ def test_checkpoint_and_resume_is_bit_identical():
     run(c, range(6, 11))
     for x, y in zip(a, c):
         assert np.array_equal(host(x).view(np.uint8), host(y).view(np.uint8))
+
+
+# ---- the paper's verification protocol, end to end on the device ----
+
+def test_protocol_gradient_integrity_check_on_device():
+    """Item 1 of the protocol: the reduced gradient from N contributions against a
+    reference, ||G_1 - G_N|| / ||G_1|| < 1e-5.  Another summation order passes; a lost
+    or duplicated contribution and a wrong normaliser fail."""
+    n, N = 20 * TILE + 96, 8
+    _say("protocol: gradient integrity on device n=%d" % n)
+    spec = ps.ps_spec_preset("zero3", N, 0, n * N)
+    grads = [gen.gradient(n, 121, 0, r, "f32", std=1e-3) for r in range(N)]
+    gd = [dev(g) for g in grads]
+    ws = torch.empty(max(ps.ps_workspace_bytes(n), ps.ps_verify_workspace_bytes(n * 4)),
+                     dtype=torch.uint8, device="cuda")
+    ss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    out2 = torch.zeros(2, dtype=torch.float64, device="cuda")
+
+    def mean_of(tensors, scale=0.0, n_dev=N):
+        sp = ps.ps_spec_preset("zero3", n_dev, 0, n * n_dev)
+        red = torch.zeros(n, dtype=torch.float32, device="cuda")
+        ps.ps_step_reduce_sumsq(sp, grads_of(tensors, "f32"), scale, red.data_ptr(), ss.data_ptr(), 0,
+                                ws.data_ptr(), ws.numel(), 0, n, n, stream_handle())
+        return red
+
+    def rel(a, b):
+        ps.ps_verify_diff_sumsq(a.data_ptr(), b.data_ptr(), ps.PS_F32, n, out2.data_ptr(), 0,
+                                ws.data_ptr(), ws.numel(), stream_handle())
+        torch.cuda.synchronize()
+        sd, sa = out2.cpu().tolist()
+        return (sd / sa) ** 0.5
+    ref = mean_of(gd)
+    tol = 1e-5
+    assert rel(ref, mean_of(gd)) == 0.0
+    assert 0.0 < rel(ref, mean_of(gd[::-1])) < tol                      # reduction order: allowed
+    assert rel(ref, mean_of(gd[:-1], 1.0 / N, N - 1)) > tol             # a device failed to contribute
+    assert rel(ref, mean_of(gd[:-1] + [gd[0]])) > tol                   # a contribution counted twice
+    assert rel(ref, mean_of(gd, 1.0)) > tol                             # divided by the wrong count
+    # and against the oracle's own numbers
+    want, _ = orc.mean_sumsq(grads, 1.0 / N)
+    assert np.array_equal(host(ref).view(np.uint32), want.view(np.uint32))
+
+
+def test_protocol_trajectory_100_steps_sharded_equals_single_device():
+    """Item 3 of the protocol: 100 steps on N devices (each its own shard) against the
+    single-device run with the same seed.  There is no loss here; the parameters
+    themselves are compared, and they agree bit for bit."""
+    psi, N, steps = 4 * (2 * TILE + 72), 4, 100
+    _say("protocol: 100-step trajectory psi=%d N=%d" % (psi, N))
+    full = [gen.master(psi, 131), *gen.moments(psi, 131, False), np.zeros(psi, np.uint16)]
+    shards = []
+    for i in range(N):
+        spec = ps.ps_spec_preset("zero3", N, i, psi)
+        c = ps.ps_cost_eval(spec)
+        sl = slice(c.shard_offset, c.shard_offset + c.shard_len)
+        shards.append((spec, c, sl, [dev(np.ascontiguousarray(a[sl])) for a in full]))
+    for t in range(1, steps + 1):
+        grads = [gen.gradient(psi, 131, t, r, "bf16", 1e-3) for r in range(N)]
+        hpd, hp = hp_of(None, t, lr=1e-3)
+        orc.step_f32(grads, orc.derive_scalars(t=t, n_devices=N, **hpd), *full)
+        for spec, c, sl, bufs in shards:
+            gd = [dev(np.ascontiguousarray(g[sl])) for g in grads]
+            ps.ps_step_update(spec, hp, shard_of(*bufs, c.shard_len), grads_of(gd, "bf16"), 0,
+                              c.shard_len, stream_handle())
+        torch.cuda.synchronize()
+    ws = torch.empty(ps.ps_verify_workspace_bytes(psi), dtype=torch.uint8, device="cuda")
+    out = torch.zeros(1, dtype=torch.int64, device="cuda")
+    for k in range(4):
+        cat = np.concatenate([host(bufs[k]) for _, _, _, bufs in shards])
+        assert np.array_equal(cat.view(np.uint8), full[k].view(np.uint8))
+    # item 2 of the protocol: checksums of each shard agree with the single-device state
+    for spec, c, sl, bufs in shards:
+        ps.ps_verify_checksum(bufs[0].data_ptr(), c.shard_len * 4, 0, out.data_ptr(), 0,
+                              ws.data_ptr(), ws.numel(), stream_handle())
+        torch.cuda.synchronize()
+        assert int(out.cpu().numpy().view(np.uint64)[0]) == orc.checksum(np.ascontiguousarray(full[0][sl]))
+    assert np.abs(full[0] - gen.master(psi, 131)).max() > 1e-3          # a hundred steps did move it
