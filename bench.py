@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--schedule", choices=["auto", "overlap", "alternate"], default="auto")
     ap.add_argument("--bucket-elems", type=int, default=0, help="override the workload's bucket size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-seconds", type=float, default=15.0,
+                    help="about how much CPU work the oracle baseline may take")
     ap.add_argument("--extras", action="store_true",
                     help="also time the update kernel alone, the other pipeline schedule and a plain copy")
     args = ap.parse_args()
@@ -271,7 +273,7 @@ def main():
         "extras": extras,
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, bpe)
+        result["cpu_baseline"] = cpu_baseline(w, bpe, args.cpu_baseline_seconds)
     print(json.dumps(result), flush=True)
 
 
@@ -415,7 +417,7 @@ def measured_traffic(w, elems_per_launch):
     return float(kv["hbm_bytes_per_element"]) * elems_per_launch
 
 
-def cpu_baseline(w, bpe):
+def cpu_baseline(w, bpe, seconds=15.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: contiguous
     index ranges of the sample handed to host threads that share nothing."""
     import numpy as np
@@ -445,7 +447,7 @@ def cpu_baseline(w, bpe):
             t.join()
         return time.perf_counter() - t0
     first = one_pass()
-    reps = max(1, min(2000, int(15.0 / max(first, 1e-3))))
+    reps = max(1, min(2000, int(seconds / max(first, 1e-3))))
     total = sum(one_pass() for _ in range(reps))
     rate = sample * reps / total
     # and one thread alone on an eighth of the sample

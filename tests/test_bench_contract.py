@@ -1,0 +1,53 @@
+"""The benchmark's command-line contract: one GPU only, one JSON line with the agreed keys."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+KEYS = {"metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better",
+        "scaling", "vs_baseline", "dtype", "data", "config", "roofline"}
+
+
+def test_more_than_one_gpu_is_refused():
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+    assert p.returncode == 2 and "ONE GPU" in p.stderr and p.stdout.strip() == ""
+
+
+def test_measured_traffic_matches_the_algorithmic_bytes_or_is_absent():
+    sys.path.insert(0, ROOT)
+    import bench
+    from synth import WORKLOADS
+    w = WORKLOADS["70b_zero3"]
+    t = bench.measured_traffic(w, 1 << 28)
+    assert t is None or abs(t / (42.0 * (1 << 28)) - 1.0) < 0.01
+    assert bench.measured_traffic(WORKLOADS["tiny"], 1 << 18) is None     # no counters for this workload
+    assert bench.bytes_per_elem(w) == 42 and bench.bytes_per_elem(WORKLOADS["13b_clip"], True) == 58
+    assert bench.bytes_per_elem(WORKLOADS["tiny"]) == 34
+    assert bench.bytes_per_elem(WORKLOADS["7b_zero1"]) == 28
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("workload", ["tiny", "gpt2s"])
+def test_json_line(workload):
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", workload,
+                        "--steps", "3", "--warmup", "1", "--cpu-baseline-seconds", "2"],
+                       stdout=subprocess.PIPE,
+                       stderr=subprocess.PIPE, text=True, timeout=280)
+    assert p.returncode == 0, p.stderr[-2000:]
+    lines = [l for l in p.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert KEYS <= set(d) and "cpu_baseline" in d
+    assert d["n_gpus"] == 1 and d["steps"] == 3 and d["warmup"] == 1 and d["vs_baseline"] is None
+    assert d["unit"] == "elements/s" and d["dtype"] == "f32" and d["data"] == "synthetic"
+    assert d["config"]["workload"] == workload and "model" not in d["config"]
+    r = d["roofline"]
+    assert r["bound"] == "hbm" and r["peak"] == 8000.0 and r["unit"] == "GB/s"
+    assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-12 and r["achieved"] > 0
+    c = d["cpu_baseline"]
+    assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and c["sample"]
+    assert d["value"] > c["value"]
