@@ -487,17 +487,27 @@ __global__ __launch_bounds__(kWave) void diff_sumsq_tail(const ScanArgs s)
 }
 
 // One word's contribution to the checksum: the splitmix64 output function of
-// w + (index + 1) * golden-ratio increment.
-__device__ __forceinline__ uint64_t checksum_term(uint64_t w, uint64_t index)
+// w + (index + 1) * golden-ratio increment.  The product is passed in (`ramp`)
+// so that callers walking consecutive indices can form it by addition.
+constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;
+
+__device__ __forceinline__ uint64_t checksum_mix(uint64_t w, uint64_t ramp)
 {
-    uint64_t z = w + (index + 1) * 0x9E3779B97F4A7C15ull;
+    uint64_t z = w + ramp;
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
     return z ^ (z >> 31);
 }
 
+__device__ __forceinline__ uint64_t checksum_term(uint64_t w, uint64_t index)
+{
+    return checksum_mix(w, (index + 1) * kGolden);
+}
+
 // Checksum over whole 128-word (1 KiB) tiles; lane t owns words 2t, 2t+1 of each
-// of the workgroup's four tiles, all loaded before the arithmetic.
+// of the workgroup's four tiles, all loaded before the arithmetic.  One 64-bit
+// multiply per lane forms (index + 1) * increment for its first word; the
+// others follow by adding multiples of the increment (arithmetic modulo 2^64).
 __global__ __launch_bounds__(kWave) void checksum_tiles(const ScanArgs s)
 {
     constexpr int K = kReduceTilesPerGroup;
@@ -510,13 +520,15 @@ __global__ __launch_bounds__(kWave) void checksum_tiles(const ScanArgs s)
         if (t0 + k < s.n_tiles)
             v[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.a) + vec);
     }
+    const uint64_t w_first = (t0 * kWave + threadIdx.x) * 2; // this lane's first word in the buffer
+    uint64_t ramp = (s.first_index + w_first + 1) * kGolden;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         if (t0 + k < s.n_tiles) {
-            const uint64_t w0 = ((t0 + k) * kWave + threadIdx.x) * 2;
-            c += checksum_term((uint64_t)v[k].x | ((uint64_t)v[k].y << 32), s.first_index + w0);
-            c += checksum_term((uint64_t)v[k].z | ((uint64_t)v[k].w << 32), s.first_index + w0 + 1);
+            c += checksum_mix((uint64_t)v[k].x | ((uint64_t)v[k].y << 32), ramp);
+            c += checksum_mix((uint64_t)v[k].z | ((uint64_t)v[k].w << 32), ramp + kGolden);
         }
+        ramp += (uint64_t)(kWave * 2) * kGolden; // next tile: 128 words further on
     }
     c = wave_sum(c);
     if (threadIdx.x == 0)
