@@ -61,7 +61,7 @@ def main():
                     help="also time the update kernel alone, the other pipeline schedule and a plain copy")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (the other N-1 devices of the placement are "
+        print("bench.py: the step runs on ONE GPU (the other N-1 devices of the placement are "
               "modelled as input buffers); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
