@@ -398,10 +398,10 @@ def verify_bench(args):
 
 def measured_traffic(w, elems_per_launch):
     """HBM bytes per launch of the dominant kernel from the committed hardware-counter summary
-    (profiles/update_tiles_hbm_traffic.txt).  None when there is no summary for this workload
+    (profiles/update_tiles__70b_zero3__hbm_traffic.txt).  None when there is no summary for this workload
     or when the kernel sources have changed since the counters were taken."""
     import hashlib
-    path = os.path.join(ROOT, "profiles", "update_tiles_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", "update_tiles__70b_zero3__hbm_traffic.txt")
     if not os.path.exists(path):
         return None
     kv = {}
