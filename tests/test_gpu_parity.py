@@ -711,3 +711,16 @@ def test_protocol_trajectory_100_steps_sharded_equals_single_device():
         torch.cuda.synchronize()
         assert int(out.cpu().numpy().view(np.uint64)[0]) == orc.checksum(np.ascontiguousarray(full[0][sl]))
     assert np.abs(full[0] - gen.master(psi, 131)).max() > 1e-3          # a hundred steps did move it
+
+
+def test_c_abi_without_python():
+    """The prebuilt native driver (built by build()): library and oracle meet in one C++
+    program, no Python or torch in between."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "native", "abi_parity")
+    if not os.path.exists(exe):
+        pytest.skip("tests/native/abi_parity has not been built (run build())")
+    _say("native C ABI driver")
+    p = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=100)
+    assert p.returncode == 0 and "abi parity ok" in p.stdout, p.stdout
