@@ -724,3 +724,49 @@ def test_c_abi_without_python():
     _say("native C ABI driver")
     p = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=100)
     assert p.returncode == 0 and "abi parity ok" in p.stdout, p.stdout
+
+
+def test_two_host_threads_on_two_streams():
+    """No shared state in the library: two host threads step two different shards on two
+    streams at once; each result equals its own oracle run, and an error raised in one
+    thread does not show up as the other's last error."""
+    import threading
+    n, N = 6 * TILE + 40, 4
+    _say("two threads, two streams, n=%d" % n)
+    results, errors = {}, {}
+
+    def work(tag, seed, t):
+        try:
+            torch.cuda.set_device(0)
+            spec = ps.ps_spec_preset("zero3", N, tag, n * N)
+            grads = [gen.gradient(n, seed, 0, r, "bf16") for r in range(N)]
+            state = [gen.master(n, seed), *gen.moments(n, seed, True), np.zeros(n, np.uint16)]
+            hpd, hp = hp_of(None, t)
+            want = [a.copy() for a in state]
+            orc.step_f32(grads, orc.derive_scalars(t=t, n_devices=N, **hpd), *want)
+            s = torch.cuda.Stream()
+            with torch.cuda.stream(s):
+                bufs = [dev(a) for a in state]
+                gd = [dev(g) for g in grads]
+                s.synchronize()
+                for _ in range(3):      # idempotent inputs: restore and repeat to overlap in time
+                    for b, a in zip(bufs, state):
+                        b.copy_(dev(a))
+                    ps.ps_step_update(spec, hp, shard_of(*bufs, n), grads_of(gd, "bf16"), 0, n, s.cuda_stream)
+                if tag == 1:
+                    try:
+                        ps.ps_step_update(spec, hp, shard_of(*bufs, n), grads_of(gd[:2], "bf16"), 0, n, s.cuda_stream)
+                    except ps.PsError as e:
+                        errors[tag] = e.status
+                s.synchronize()
+            results[tag] = assert_state_parity([host(b) for b in bufs], want, "thread %d" % tag)
+            errors.setdefault(tag, ps.ps_last_error())
+        except Exception as e:      # surface assertion failures from the thread
+            results[tag] = e
+    th = [threading.Thread(target=work, args=(0, 141, 3)), threading.Thread(target=work, args=(1, 142, 9))]
+    for t in th:
+        t.start()
+    for t in th:
+        t.join()
+    assert results == {0: 0, 1: 0}, results
+    assert errors[1] == ps.PS_EINVAL and errors[0] == ""
