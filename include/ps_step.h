@@ -262,6 +262,10 @@ ps_status_t ps_compose_index(uint32_t inner, uint32_t outer, uint32_t device,
 
 /* ---- device calls ---- */
 
+/* Properties of the current HIP device as hipGetDeviceProperties and
+ * hipMemGetInfo report them (name, architecture, compute units, clocks, memory
+ * bus, L2 size, total and free memory); recorded next to every measurement.
+ * info is HOST memory owned by the caller.  PS_ENODEVICE without a GPU. */
 ps_status_t ps_device_info(ps_device_info_t *info);
 
 /* One optimizer step on elements [elem_offset, elem_offset + elem_count) of the
