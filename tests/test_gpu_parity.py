@@ -770,3 +770,35 @@ def test_two_host_threads_on_two_streams():
         t.join()
     assert results == {0: 0, 1: 0}, results
     assert errors[1] == ps.PS_EINVAL and errors[0] == ""
+
+
+@pytest.mark.parametrize("engine", [ps.PS_COPY_MEMCPY, ps.PS_COPY_KERNEL])
+def test_bucketed_step_from_pinned_host_source(engine):
+    """The bucket source may be pinned host memory (contributions arriving over the host
+    link): DMA copies overlap the update; the copy kernel reads the mapped host pages."""
+    bucket, N = 2 * TILE, 4
+    n = 3 * bucket + 520
+    n_b = -(-n // bucket)
+    _say("bucketed from pinned host memory n=%d engine=%d" % (n, engine))
+    spec = ps.ps_spec_preset("zero3", N, 3, n * N)
+    src_np = [gen.gradient(n_b * bucket, 151, 0, r, "bf16", 1e-3) for r in range(N)]
+    src = [torch.from_numpy(g.view(np.int16)).pin_memory() for g in src_np]
+    state = [gen.master(n, 151), *gen.moments(n, 151, True), np.zeros(n, np.uint16)]
+    hpd, hp = hp_of(None, 33)
+    want = [a.copy() for a in state]
+    orc.step_f32([np.ascontiguousarray(g[:n]) for g in src_np],
+                 orc.derive_scalars(t=33, n_devices=N, **hpd), *want)
+    th, m, v, p = [dev(a) for a in state]
+    staging = [torch.zeros(N * bucket * 2, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    copy, comp = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    plan = ps.ps_bucket_plan_t()
+    arr = (C.c_void_p * N)(*[s.data_ptr() for s in src])
+    plan.source = C.cast(arr, C.POINTER(C.c_void_p))
+    plan.n_contrib, plan.dtype, plan.bucket_elems, plan.source_elems = N, ps.PS_BF16, bucket, n_b * bucket
+    plan.staging[0], plan.staging[1] = staging[0].data_ptr(), staging[1].data_ptr()
+    plan.copy_stream, plan.compute_stream = copy.cuda_stream, comp.cuda_stream
+    plan.copy_engine, plan.schedule = engine, ps.PS_SCHED_AUTO
+    ps.ps_step_update_bucketed(spec, hp, shard_of(th, m, v, p, n), plan)
+    torch.cuda.synchronize()
+    assert assert_state_parity([host(x) for x in (th, m, v, p)], want, "pinned source") == 0
