@@ -53,6 +53,9 @@ def main():
                     help="elements per contribution of the resident, repeating bucket source")
     ap.add_argument("--copy-engine", choices=["kernel", "memcpy"], default="kernel")
     ap.add_argument("--schedule", choices=["auto", "overlap", "alternate"], default="auto")
+    ap.add_argument("--source-host", action="store_true",
+                    help="keep the bucket source in pinned host memory (the step is then bound by "
+                         "the host link; reported for reference, never the headline value)")
     ap.add_argument("--bucket-elems", type=int, default=0, help="override the workload's bucket size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-baseline-seconds", type=float, default=15.0,
@@ -113,6 +116,8 @@ def main():
         pool = [dgen.fill_gradient_(torch.empty(args.pool_elems, dtype=tdt, device="cuda"),
                                     w.seed, w.first_step, r, w.grad_std, w.outlier_frac,
                                     w.outlier_mult, w.student_t_dof) for r in range(N)]
+        if args.source_host:
+            pool = [p.cpu().pin_memory() for p in pool]
         staging = [torch.empty(N * B, dtype=tdt, device="cuda") for _ in range(2)]
         src = (C.c_void_p * N)(*[p.data_ptr() for p in pool])
         ms = (C.c_float * n_b)()
@@ -256,7 +261,9 @@ def main():
                    "bucket_elems": (B if bucketed else 0), "launches_per_step": launches_per_step,
                    "bucket_source": ("resident pool of %d elements per contribution, repeating; "
                                      "copy engine %s, schedule %s" %
-                                     (args.pool_elems, args.copy_engine, args.schedule)) if bucketed else None,
+                                     (args.pool_elems, args.copy_engine, args.schedule)) +
+                                    (" (source in pinned HOST memory)" if args.source_host else "")
+                                    if bucketed else None,
                    "bytes_per_elem": bpe, "step_GBps": bpe * elems_per_step / (ms_per_step * 1e-3) / 1e9,
                    "device": info.name.decode(), "arch": info.arch.decode(),
                    "compute_units": info.compute_units, "memory_clock_khz": info.memory_clock_khz,
