@@ -467,3 +467,20 @@ def test_relative_difference_sums(dtype):
 def load_tol():
     from conftest import load_golden
     return load_golden()["grad_check_rel_tol"]
+
+
+def test_bf16_rne_exhaustive_against_library_conversion():
+    """All 2^32 binary32 patterns: the oracle's cast against the library's float32 ->
+    bfloat16 conversion (round to nearest even).  NaNs are compared as a class (the
+    oracle canonicalises them to 0x7FC0 with the sign, the library keeps payload bits)."""
+    chunk = 1 << 26
+    torch.set_num_threads(max(1, min(8, torch.get_num_threads())))
+    for lo in range(0, 1 << 32, chunk):
+        u = np.arange(lo, lo + chunk, dtype=np.uint32)
+        got = orc.bf16_rne_bits(u)
+        lib = torch.from_numpy(u.view(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        nan = (u & 0x7fffffff) > 0x7f800000
+        assert np.array_equal(got[~nan], lib[~nan]), hex(lo)
+        if nan.any():
+            assert ((got[nan] & 0x7fff) == 0x7fc0).all() and ((lib[nan] & 0x7f80) == 0x7f80).all()
+            assert np.array_equal(got[nan] >> 15, (u[nan] >> 31).astype(np.uint16))
