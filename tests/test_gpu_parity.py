@@ -177,6 +177,43 @@ def test_special_values_propagate():
     assert np.array_equal(got[3][~nan], want[3][~nan])
 
 
+def test_cast_exhaustive_over_all_binary32_patterns():
+    """Every binary32 pattern goes through the kernel as a master value.  With lr = 0, zero
+    moments and a zero gradient the update leaves every finite value as it is (only -0
+    becomes +0, and an infinity turns into NaN by 0 x inf), so the bf16 image the kernel
+    writes is the cast of all 2^32 patterns: compared bit for bit with the library's
+    round-to-nearest-even conversion of the master the kernel left behind."""
+    chunk = 1 << 28
+    _say("exhaustive cast: 2^32 master patterns in %d launches" % ((1 << 32) // chunk))
+    spec = ps.ps_spec_preset("zero3", 4, 0, chunk * 4)
+    _, hp = hp_of(None, 1, lr=0.0, weight_decay=0.0, grad_scale=1.0)
+    bits = torch.empty(chunk, dtype=torch.int32, device="cuda")
+    th = bits.view(torch.float32)
+    m = torch.zeros(chunk, dtype=torch.float32, device="cuda")
+    v = torch.zeros_like(m)
+    g = torch.zeros_like(m)
+    out = torch.empty(chunk, dtype=torch.int16, device="cuda")
+    ramp = torch.arange(chunk, dtype=torch.int64, device="cuda")
+    for lo in range(0, 1 << 32, chunk):
+        before = ((ramp + lo) & 0xffffffff)
+        bits.copy_(torch.where(before >= (1 << 31), before - (1 << 32), before).to(torch.int32))
+        before = bits.clone()
+        out.fill_(0x1111)
+        ps.ps_step_update(spec, hp, shard_of(th, m, v, out, chunk), grads_of([g], "f32"), 0, chunk,
+                          stream_handle())
+        torch.cuda.synchronize()
+        mag = before & 0x7fffffff
+        finite = mag < 0x7f800000
+        keep = finite & (before != -(1 << 31))                   # all finite values but -0
+        assert torch.equal(bits[keep], before[keep]), hex(lo)    # identity: the cast sees them all
+        nan = torch.isnan(th)
+        lib = th.to(torch.bfloat16).view(torch.int16)
+        assert torch.equal(out[~nan], lib[~nan]), hex(lo)
+        assert bool(((out[nan] & 0x7fff) == 0x7fc0).all()), hex(lo)
+        assert bool(nan[~finite].all()) and not bool(nan[finite].any())
+    assert not bool(m.view(torch.int32).any()) and not bool(v.view(torch.int32).any())
+
+
 def test_run_twice_is_bitwise_identical():
     n, N = 7 * TILE + 99, 8
     _say("determinism n=%d" % n)
