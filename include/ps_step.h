@@ -292,7 +292,9 @@ ps_status_t ps_device_info(ps_device_info_t *info);
  *     parameters' slice.  grad_scale <= 0 still means 1/N: the all-reduce sums.
  * Anything else: PS_EUNSUPPORTED.  elem_offset must be a multiple of 8.
  * Deterministic: no atomics, results do not depend on launch shape (Theorem 5,
- * assumption 1). */
+ * assumption 1).  The call only enqueues kernels on hip_stream: it allocates
+ * nothing and waits for nothing, so it may be recorded into a HIP graph by a
+ * stream capture (the scalars derived from *hp are then fixed in the graph). */
 ps_status_t ps_step_update(const ps_spec_t *spec, const ps_adamw_t *hp,
                            const ps_shard_t *shard, const ps_grads_t *grads,
                            uint64_t elem_offset, uint64_t elem_count, void *stream);
@@ -340,7 +342,10 @@ uint64_t ps_workspace_bytes(uint64_t elem_count);
  * already there, so several buckets called in order give a reproducible total.
  * The caller combines it with the other devices' sums, forms the clip
  * coefficient and calls ps_step_update with the reduced gradient as a single
- * PS_F32 contribution, grad_scale = 1 and that coefficient. */
+ * PS_F32 contribution, grad_scale = 1 and that coefficient.  Like
+ * ps_step_update the call only enqueues kernels (the partial sums live in the
+ * caller's workspace, which a later call on another stream must not share while
+ * this one is in flight) and may be recorded by a stream capture. */
 ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
                                  double grad_scale, float *reduced_out, double *sumsq_out,
                                  int32_t accumulate, void *workspace,

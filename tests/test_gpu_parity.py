@@ -326,6 +326,50 @@ def test_clipped_two_phase_step_matches_oracle():
     assert np.float32(ps.ps_clip_coef(ss_gpu, 5 * ss_gpu, w.max_grad_norm)) == np.float32(coef)
 
 
+def test_both_phases_captured_in_a_hip_graph_and_replayed():
+    """The two launch-only entry points allocate nothing and synchronise nothing, so a
+    caller may capture them.  One graph holds phase 1 (reduce + sum of squares) and
+    phase 2 (update from the reduced gradient, fixed coefficient); it is replayed three
+    times with eager work and synchronisation between the replays, and every replay is
+    compared with the oracle advanced by one more step."""
+    N, n = 6, 5 * TILE + 777
+    valid = n - 3
+    _say("graph capture: phases 1+2, n=%d N=%d, 3 replays" % (n, N))
+    spec = ps.ps_spec_preset("zero3", N, 0, n * N)
+    grads = [gen.gradient(n, 41, 0, r, "f32", 1e-2) for r in range(N)]
+    state = [gen.master(n, 41), *gen.moments(n, 41, True), np.full(n, 0x7777, np.uint16)]
+    t, coef = 9, 0.37
+    hpd, hp = hp_of(None, t, grad_scale=1.0, clip_coef=coef)
+    _, ss = orc.mean_sumsq(grads, 1.0 / N, 0, valid)
+    want = [a.copy() for a in state]
+    s = orc.derive_scalars(t=t, n_devices=N, clip_coef=coef, **hpd)
+    gd = [dev(g) for g in grads]
+    th, m, v, p = [dev(a) for a in state]
+    red = torch.zeros(n, dtype=torch.float32, device="cuda")
+    ssd = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ws = torch.empty(ps.ps_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    shard, gl, gr = shard_of(th, m, v, p, n, valid), grads_of(gd, "f32"), grads_of([red], "f32")
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ps.ps_step_reduce_sumsq(spec, gl, 0.0, red.data_ptr(), ssd.data_ptr(), 0, ws.data_ptr(),
+                                ws.numel(), 0, n, valid, stream_handle())
+        ps.ps_step_update(spec, hp, shard, gr, 0, n, stream_handle())
+    torch.cuda.synchronize()
+    assert np.array_equal(host(th).view(np.uint32), state[0].view(np.uint32))   # capture ran nothing
+    for k in range(3):
+        red.fill_(float("nan")); ssd.fill_(-1.0)           # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        orc.step_f32(grads, s, *want, lo=0, hi=valid)
+        got = [host(x) for x in (th, m, v, p)]
+        assert assert_state_parity(got, want, "replay %d" % k) == 0
+        assert abs(float(ssd.item()) - ss) <= 1e-12 * ss
+        for g_, a in zip(got, state):
+            assert np.array_equal(g_[valid:].view(np.uint8), a[valid:].view(np.uint8))
+
+
 # ---- bucket pipeline ----
 
 def _bucketed(spec, hp, state, src_np, dtype, n, valid, bucket, engine, timed=False,
