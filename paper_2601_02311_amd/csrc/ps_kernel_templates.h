@@ -413,15 +413,16 @@ struct ScanArgs {
     const void *b;
     void *partials0; // per-workgroup partial sums (first quantity)
     void *partials1; // second quantity, where there is one
-    uint64_t n_tiles; // whole tiles (tile kernels) or leftover units (tail kernels)
+    uint64_t n_tiles; // tail kernels: leftover units; tile kernels take their extent from the grid
     uint64_t first_index;
     uint32_t partial_slot;
 };
 
 // Sums of (a-b)^2 and a^2 in binary64.  Read-only, so every lane takes 16 bytes
 // per buffer whatever the element type: a scan tile is 1 KiB per buffer (256
-// fp32 or 512 bf16 elements).  Workgroup b owns tiles [4b, 4b+4) and issues all
-// of their loads before the arithmetic.
+// fp32 or 512 bf16 elements).  Workgroup b owns tiles [4b, 4b+4), all four whole
+// (the grid covers whole groups only; what is left goes to the tail kernel), so
+// the eight loads are unconditional and all in flight before the arithmetic.
 template <typename G>
 __global__ __launch_bounds__(kWave) void diff_sumsq_tiles(const ScanArgs s)
 {
@@ -432,13 +433,8 @@ __global__ __launch_bounds__(kWave) void diff_sumsq_tiles(const ScanArgs s)
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const uint64_t vec = (t0 + k) * kWave + threadIdx.x;
-        if (t0 + k < s.n_tiles) {
-            x[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.a) + vec);
-            y[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.b) + vec);
-        } else {
-            x[k] = u32x4{0u, 0u, 0u, 0u};
-            y[k] = x[k];
-        }
+        x[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.a) + vec);
+        y[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.b) + vec);
     }
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -505,9 +501,10 @@ __device__ __forceinline__ uint64_t checksum_term(uint64_t w, uint64_t index)
 }
 
 // Checksum over whole 128-word (1 KiB) tiles; lane t owns words 2t, 2t+1 of each
-// of the workgroup's four tiles, all loaded before the arithmetic.  One 64-bit
-// multiply per lane forms (index + 1) * increment for its first word; the
-// others follow by adding multiples of the increment (arithmetic modulo 2^64).
+// of the workgroup's four tiles (whole groups only, as in the scan above), all
+// loaded before the arithmetic.  One 64-bit multiply per lane forms (index + 1)
+// * increment for its first word; the others follow by adding multiples of the
+// increment (arithmetic modulo 2^64).
 __global__ __launch_bounds__(kWave) void checksum_tiles(const ScanArgs s)
 {
     constexpr int K = kReduceTilesPerGroup;
@@ -517,17 +514,14 @@ __global__ __launch_bounds__(kWave) void checksum_tiles(const ScanArgs s)
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const uint64_t vec = (t0 + k) * kWave + threadIdx.x;
-        if (t0 + k < s.n_tiles)
-            v[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.a) + vec);
+        v[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.a) + vec);
     }
     const uint64_t w_first = (t0 * kWave + threadIdx.x) * 2; // this lane's first word in the buffer
     uint64_t ramp = (s.first_index + w_first + 1) * kGolden;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-        if (t0 + k < s.n_tiles) {
-            c += checksum_mix((uint64_t)v[k].x | ((uint64_t)v[k].y << 32), ramp);
-            c += checksum_mix((uint64_t)v[k].z | ((uint64_t)v[k].w << 32), ramp + kGolden);
-        }
+        c += checksum_mix((uint64_t)v[k].x | ((uint64_t)v[k].y << 32), ramp);
+        c += checksum_mix((uint64_t)v[k].z | ((uint64_t)v[k].w << 32), ramp + kGolden);
         ramp += (uint64_t)(kWave * 2) * kGolden; // next tile: 128 words further on
     }
     c = wave_sum(c);

@@ -311,9 +311,9 @@ static int launch_diff_t(const void *a, const void *b, uint64_t count, double *o
                          int accumulate, uint64_t *workspace, uint64_t slots, hipStream_t st)
 {
     constexpr uint64_t kScanTile = kWave * (16 / sizeof(G)); // elements in 1 KiB
-    const uint64_t n_tiles = count / kScanTile;
-    const uint64_t body = n_tiles * kScanTile;
-    const uint64_t groups = scan_groups(n_tiles);
+    constexpr uint64_t kGroupElems = kScanTile * kReduceTilesPerGroup;
+    const uint64_t groups = count / kGroupElems; // whole groups; the tail takes the rest
+    const uint64_t body = groups * kGroupElems;
     if (groups > kMaxGrid)
         return (int)hipErrorInvalidConfiguration;
     const uint64_t half = slots / 2;
@@ -327,8 +327,8 @@ static int launch_diff_t(const void *a, const void *b, uint64_t count, double *o
     s.first_index = 0;
     s.partial_slot = 0;
     uint64_t n_partials = 0;
-    if (n_tiles) {
-        s.n_tiles = n_tiles;
+    if (groups) {
+        s.n_tiles = groups * kReduceTilesPerGroup;
         hipLaunchKernelGGL((diff_sumsq_tiles<G>), dim3((uint32_t)groups), dim3(kWave),
                            kScanLdsBytes, st, s);
         hipError_t e = hipGetLastError();
@@ -367,10 +367,9 @@ int launch_checksum(const void *buf, uint64_t n_words, uint64_t first_index, uin
                     int accumulate, void *workspace, void *stream)
 {
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    constexpr uint64_t kTileWords = kWave * 2;
-    const uint64_t n_tiles = n_words / kTileWords;
-    const uint64_t body = n_tiles * kTileWords;
-    const uint64_t groups = scan_groups(n_tiles);
+    constexpr uint64_t kGroupWords = kWave * 2 * kReduceTilesPerGroup;
+    const uint64_t groups = n_words / kGroupWords; // whole groups; the tail takes the rest
+    const uint64_t body = groups * kGroupWords;
     if (groups > kMaxGrid)
         return (int)hipErrorInvalidConfiguration;
     uint64_t *l2 = reinterpret_cast<uint64_t *>(workspace), *l1 = l2 + kFoldBlocks;
@@ -382,8 +381,8 @@ int launch_checksum(const void *buf, uint64_t n_words, uint64_t first_index, uin
     s.first_index = first_index;
     s.partial_slot = 0;
     uint64_t n_partials = 0;
-    if (n_tiles) {
-        s.n_tiles = n_tiles;
+    if (groups) {
+        s.n_tiles = groups * kReduceTilesPerGroup;
         hipLaunchKernelGGL(checksum_tiles, dim3((uint32_t)groups), dim3(kWave), kScanLdsBytes, st,
                            s);
         hipError_t e = hipGetLastError();
