@@ -260,6 +260,21 @@ ps_status_t ps_compose_index(uint32_t inner, uint32_t outer, uint32_t device,
                              uint32_t *inner_group, uint32_t *inner_rank,
                              uint32_t *outer_group, uint32_t *outer_rank);
 
+/* Cost of a composed strategy as one device sees it (Definition 5; Theorems 6
+ * and 7; the remark on three-way composition).  The inner strategy (tensor
+ * parallelism of degree T, a pipeline of K stages, or both: inner = T, K or
+ * T * K) leaves each device 1/inner of the model; *outer is a data-parallel
+ * family specification (a row of Table 2) over the outer->n_devices devices
+ * that hold the same share, its psi being the parameter count of the WHOLE
+ * model.  The result is Theorems 1 and 2 applied inside that group: memory per
+ * device and the bytes one device moves per step for gradient sync and
+ * parameter gathers among its outer->n_devices peers.  What the inner strategy
+ * itself communicates (per-layer collectives on activations, stage-to-stage
+ * activation transfers) is not quantified by the paper and is not included.
+ * Shard geometry in *cost refers to the group's flat buffers of psi / inner
+ * elements.  PS_ERANGE if inner does not divide psi, else as ps_cost_eval. */
+ps_status_t ps_compose_cost(const ps_spec_t *outer, uint32_t inner, ps_cost_t *cost);
+
 /* ---- device calls ---- */
 
 /* Properties of the current HIP device as hipGetDeviceProperties and

@@ -126,3 +126,14 @@ def pp_dp_groups(K, D):
     stages = [list(range(k * D, (k + 1) * D)) for k in range(K)]
     pipes = [[k * D + r for k in range(K)] for r in range(D)]
     return stages, pipes
+
+
+def composed_cost(outer_spec, P, inner, D, s_unit=0):
+    """Definition 5 with Theorems 6 and 7: an inner strategy of degree `inner` (TP degree,
+    pipeline stages, or their product) leaves each device P/inner parameters; the outer
+    data-parallel family specification acts on that share among the D devices holding the
+    same share.  Returns (memory per device, bytes per device per step inside the outer
+    group), Theorems 1 and 2 applied to the share.  The inner strategy's own activation
+    traffic is not quantified by the paper and not included."""
+    share = Fraction(P, inner)
+    return memory(outer_spec, share, D, s_unit), communication(outer_spec, share, D)

@@ -23,7 +23,8 @@ __all__ = [
     "ps_device_info", "ps_step_update", "ps_step_update_bucketed", "ps_workspace_bytes",
     "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
     "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum",
-    "ps_select_strategy", "ps_compose_index", "ps_step_update_offloaded", "EXPORTED_SYMBOLS",
+    "ps_select_strategy", "ps_compose_index", "ps_compose_cost", "ps_step_update_offloaded",
+    "EXPORTED_SYMBOLS",
 ]
 
 PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
@@ -38,7 +39,7 @@ EXPORTED_SYMBOLS = (
     "ps_device_info", "ps_step_update", "ps_step_update_bucketed", "ps_workspace_bytes",
     "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
     "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum",
-    "ps_select_strategy", "ps_compose_index", "ps_step_update_offloaded",
+    "ps_select_strategy", "ps_compose_index", "ps_compose_cost", "ps_step_update_offloaded",
 )
 
 
@@ -139,6 +140,8 @@ def library():
                                          C.POINTER(C.c_int32)]
         L.ps_compose_index.restype = C.c_int
         L.ps_compose_index.argtypes = [C.c_uint32] * 3 + [C.POINTER(C.c_uint32)] * 4
+        L.ps_compose_cost.restype = C.c_int
+        L.ps_compose_cost.argtypes = [C.POINTER(ps_spec_t), C.c_uint32, C.POINTER(ps_cost_t)]
         L.ps_device_info.restype = C.c_int
         L.ps_device_info.argtypes = [C.POINTER(ps_device_info_t)]
         L.ps_step_update.restype = C.c_int
@@ -238,6 +241,12 @@ def ps_compose_index(inner, outer, device):
     out = [C.c_uint32() for _ in range(4)]
     _check(library().ps_compose_index(inner, outer, device, *[C.byref(x) for x in out]))
     return tuple(x.value for x in out)
+
+
+def ps_compose_cost(outer, inner):
+    cost = ps_cost_t()
+    _check(library().ps_compose_cost(_ref(outer), inner, C.byref(cost)))
+    return cost
 
 
 def ps_device_info():

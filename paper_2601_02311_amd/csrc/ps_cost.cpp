@@ -251,6 +251,29 @@ ps_status_t ps_compose_index(uint32_t inner, uint32_t outer, uint32_t device,
     return PS_OK;
 }
 
+ps_status_t ps_compose_cost(const ps_spec_t *outer, uint32_t inner, ps_cost_t *cost)
+{
+    clear_error();
+    if (!outer || !cost) {
+        set_error("outer or cost is NULL");
+        return PS_EINVAL;
+    }
+    if (inner == 0) {
+        set_error("inner degree must be >= 1");
+        return PS_EINVAL;
+    }
+    if (outer->psi % inner != 0) {
+        set_error("inner degree %u does not divide psi = %llu", inner,
+                  (unsigned long long)outer->psi);
+        return PS_ERANGE;
+    }
+    // Each device of the outer group holds the same 1/inner of every state; the
+    // outer rules then act on that share among the group's devices.
+    ps_spec_t local = *outer;
+    local.psi = outer->psi / inner;
+    return ps_cost_eval(&local, cost);
+}
+
 ps_status_t ps_cost_eval(const ps_spec_t *spec, ps_cost_t *cost)
 {
     clear_error();

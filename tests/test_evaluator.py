@@ -178,3 +178,36 @@ def test_composition_index_against_the_oracle(golden):
     with pytest.raises(ps.PsError) as e:
         ps.ps_compose_index(0, 2, 0)
     assert e.value.status == ps.PS_EINVAL
+
+
+def test_composed_cost_per_device_and_per_group(golden):
+    """Definition 5 / Theorems 6-7: the outer data-parallel family rules act on the 1/inner
+    share an inner strategy leaves each device, among the D devices holding that share."""
+    P = int(golden["P_70b"])
+    T, D = int(golden["fig2_tp_degree"]), int(golden["fig2_dp_degree"])       # Figure 2: TP(4) x DP(2)
+    c = ps.ps_compose_cost(ps.ps_spec_preset("dp", D, 0, P), T)
+    assert c.peak_total == 16 * P // T == 280 * GB                             # a quarter of 1120 GB
+    assert c.comm_grad_sync_xN == 2 * (D - 1) * (2 * P // T) and c.comm_total_bytes == 35 * GB
+    z3 = ps.ps_compose_cost(ps.ps_spec_preset("zero3", D, 0, P), T)
+    assert z3.peak_total == 16 * P // (T * D) == 140 * GB                      # same bytes as ZeRO-3 over 8
+    assert 2 * (z3.comm_grad_sync_xN + z3.comm_param_gather_xN) == 3 * c.comm_grad_sync_xN   # 1.5x inside the group
+    # against the exact closed forms, including the three-way case inner = T * K
+    for name, modes in pl.STRATEGIES.items():
+        for inner, Dg in [(1, 8), (4, 2), (2, 4), (8, 4), (16, 1), (7, 5)]:
+            Pm = 70 * 10 ** 9 // (7 * 16 * 5 * 8) * (7 * 16 * 5 * 8)
+            got = ps.ps_compose_cost(ps.ps_spec_preset(name, Dg, 0, Pm), inner)
+            mem, comm = pl.composed_cost(modes, Pm, inner, Dg)
+            assert got.peak_total == mem, (name, inner, Dg)
+            assert got.comm_grad_sync_xN + got.comm_param_gather_xN == comm * Dg
+            assert got.psi_padded == Pm // inner
+    # inner = 1 is the outer strategy itself; one outer device means no data-parallel traffic
+    spec = ps.ps_spec_preset("zero2", 8, 3, P)
+    a, b = ps.ps_cost_eval(spec), ps.ps_compose_cost(spec, 1)
+    assert bytes(a) == bytes(b)
+    assert ps.ps_compose_cost(ps.ps_spec_preset("dp", 1, 0, P), 8).comm_total_bytes == 0.0
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_compose_cost(spec, 0)
+    assert e.value.status == ps.PS_EINVAL
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_compose_cost(spec, 3)            # 70e9 is not a multiple of 3
+    assert e.value.status == ps.PS_ERANGE

@@ -149,3 +149,22 @@ def test_algorithm1_thresholds(golden):
     # on a 288 GB device the 7B model fits plain data parallelism (112 GB < 201.6 GB)
     assert pl.select_strategy(7 * GBy, 288 * GBy, 8)[0] == pl.STRATEGIES["dp"]
     assert pl.select_strategy(70 * GBy, 288 * GBy, 8)[0] == pl.STRATEGIES["zero3"]
+
+
+def test_composed_cost_worked_by_hand(golden):
+    """Figure 2's TP(4) x DP(2) on the 70B model, figures worked by hand from Theorems 1-2:
+    a device holds a quarter of 1120 GB; its data-parallel All-Reduce moves 2(D-1)/D of a
+    quarter of |G| = 140 GB."""
+    GBy = 10 ** 9
+    P = int(golden["P_70b"])
+    T, D = int(golden["fig2_tp_degree"]), int(golden["fig2_dp_degree"])
+    assert pl.composed_cost(pl.STRATEGIES["dp"], P, T, D) == (280 * GBy, 35 * GBy)
+    # ZeRO-3 across the two groups: 1/8 of the state again, 3 x (1/2) x 35 GB inside the group
+    assert pl.composed_cost(pl.STRATEGIES["zero3"], P, T, D) == (140 * GBy, Fraction(105 * GBy, 2))
+    # degenerate compositions: no inner strategy is the outer strategy; a single outer
+    # device has nobody to synchronise with
+    for modes in pl.STRATEGIES.values():
+        assert pl.composed_cost(modes, P, 1, 8) == (pl.memory(modes, P, 8), pl.communication(modes, P, 8))
+        assert pl.composed_cost(modes, P, 8, 1)[1] == 0
+    # sharding fully over the outer group leaves what sharding over all T*D devices leaves
+    assert pl.composed_cost(pl.STRATEGIES["zero3"], P, T, D)[0] == pl.memory(pl.STRATEGIES["zero3"], P, T * D)
