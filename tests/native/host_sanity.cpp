@@ -50,6 +50,10 @@ int main()
     uint32_t a, b, c, d;
     CHECK(ps_compose_index(4, 2, 6, &a, &b, &c, &d) == PS_OK && a == 1 && b == 2 && c == 2 && d == 1);
     CHECK(ps_compose_index(65536, 65536, 0, &a, &b, &c, &d) == PS_ERANGE);
+    CHECK(ps_spec_preset("dp", 2, 0, P, &spec) == PS_OK && ps_compose_cost(&spec, 4, &cost) == PS_OK);
+    CHECK(cost.peak_total == 280000000000ull && cost.comm_total_bytes == 35e9);
+    CHECK(ps_compose_cost(&spec, 0, &cost) == PS_EINVAL && ps_compose_cost(&spec, 3, &cost) == PS_ERANGE);
+    CHECK(ps_compose_cost(nullptr, 4, &cost) == PS_EINVAL && ps_compose_cost(&spec, 4, nullptr) == PS_EINVAL);
     CHECK(ps_clip_coef(4.0, 12.0, 1.0) < 1.0 && ps_clip_coef(-1.0, 0.0, 1.0) != ps_clip_coef(-1.0, 0.0, 1.0));
     for (int st = 0; st < 9; ++st)
         CHECK(ps_status_string((ps_status_t)st) != nullptr);
