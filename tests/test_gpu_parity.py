@@ -278,7 +278,21 @@ def test_reduce_sumsq_degenerate_ranges():
     assert abs(_reduce_gpu(spec, grads, "f32", n, n)[1] - ss) <= 1e-12 * ss
     assert _reduce_gpu(spec, grads, "f32", n, 0)[1] == 0.0           # all padding
     grads[1][5] = np.inf
-    assert np.isinf(_reduce_gpu(spec, grads, "f32", n, n)[1])         # caller sees it and may skip
+    red, ss_inf = _reduce_gpu(spec, grads, "f32", n, n)
+    assert np.isinf(ss_inf)                                           # caller sees it and may skip
+    # ... and a caller who does not look cannot damage the state: the library reports the
+    # coefficient of a non-finite sum as NaN, and the update refuses a NaN before any launch
+    assert np.isnan(ps.ps_clip_coef(ss_inf, 0.0, 1.0))
+    state = [gen.master(n, 1), *gen.moments(n, 1, True), np.full(n, 0x4242, np.uint16)]
+    th, m, v, p = [dev(a) for a in state]
+    _, hp = hp_of(None, 3, grad_scale=1.0, clip_coef=ps.ps_clip_coef(ss_inf, 0.0, 1.0))
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_step_update(spec, hp, shard_of(th, m, v, p, n), grads_of([dev(red)], "f32"), 0, n,
+                          stream_handle())
+    assert e.value.status == ps.PS_ERANGE
+    torch.cuda.synchronize()
+    for t_, a in zip((th, m, v, p), state):
+        assert np.array_equal(host(t_).view(np.uint8), a.view(np.uint8))
 
 
 def test_clipped_two_phase_step_matches_oracle():
