@@ -312,20 +312,24 @@ struct ReduceArgs {
     float *reduced; // may be null
     double *partials;
     uint64_t n_tiles; // whole tiles (tile kernel) or element count (tail kernel)
+    uint64_t first_group; // tile kernel: group handled by workgroup 0 of this launch
     uint32_t n_contrib;
     uint32_t partial_slot; // tail kernel: where its single partial goes
     float gs;
 };
 
 // Reduce the contributions, scale to the mean, optionally store it, and leave
-// one binary64 partial sum of squares per workgroup in partials[blockIdx.x].
-// Workgroup b owns tiles [4b, 4b+4); the grid covers all tiles.
+// one binary64 partial sum of squares per group of four tiles in partials[group].
+// Group b owns tiles [4b, 4b+4); a launch covers the groups from first_group on
+// (a long range goes out as several launches, which changes nothing in the
+// result: the partials land where one launch would put them).
 template <int N, typename G>
 __global__ __launch_bounds__(kWave) void reduce_sumsq_tiles(const ReduceArgs a)
 {
     const uint32_t n = N ? N : a.n_contrib;
     double ss = 0.0;
-    const uint64_t t0 = (uint64_t)blockIdx.x * kReduceTilesPerGroup;
+    const uint64_t group = a.first_group + blockIdx.x;
+    const uint64_t t0 = group * kReduceTilesPerGroup;
     const uint64_t t1 = t0 + kReduceTilesPerGroup < a.n_tiles ? t0 + kReduceTilesPerGroup : a.n_tiles;
     for (uint64_t tile = t0; tile < t1; ++tile) {
         const uint64_t e = tile * kTileElems + (uint64_t)threadIdx.x * 4;
@@ -354,7 +358,7 @@ __global__ __launch_bounds__(kWave) void reduce_sumsq_tiles(const ReduceArgs a)
     }
     const double t = wave_sum(ss);
     if (threadIdx.x == 0)
-        a.partials[blockIdx.x] = t;
+        a.partials[group] = t;
 }
 
 // Tail: a single wave strides over the leftover elements (fewer than one tile).
