@@ -370,7 +370,7 @@ ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
 /* ---- verification protocol (Section 7.1) ---- */
 
 /* Bytes of DEVICE workspace the two verification scans need for a buffer of
- * buffer_bytes bytes (about buffer_bytes / 128; host-only query). */
+ * buffer_bytes bytes (16 KiB + about buffer_bytes / 2048; host-only query). */
 uint64_t ps_verify_workspace_bytes(uint64_t buffer_bytes);
 
 /* Gradient integrity check: writes out2[0] = sum (a-b)^2 and out2[1] = sum a^2

@@ -286,22 +286,51 @@ __device__ __forceinline__ T wave_sum(T x)
     return x;
 }
 
-// Fixed-shape tree for a kThreads-wide workgroup: butterfly inside each wave,
+// Fixed-shape tree for a workgroup of THREADS lanes: butterfly inside each wave,
 // then the wave sums through LDS, added in wave order.  Every lane must call it.
-template <typename T>
-__device__ __forceinline__ T block_sum(T x)
+template <typename T, int THREADS>
+__device__ __forceinline__ T block_sum_n(T x)
 {
-    __shared__ T partial[kThreads / 64];
+    __shared__ T partial[THREADS / 64];
     x = wave_sum(x);
     if ((threadIdx.x & 63) == 0)
         partial[threadIdx.x >> 6] = x;
     __syncthreads();
     T t = partial[0];
 #pragma unroll
-    for (int w = 1; w < kThreads / 64; ++w)
+    for (int w = 1; w < THREADS / 64; ++w)
         t += partial[w];
     __syncthreads();
     return t;
+}
+
+template <typename T>
+__device__ __forceinline__ T block_sum(T x)
+{
+    return block_sum_n<T, kThreads>(x);
+}
+
+// The same tree for Q values at once with a single barrier; its LDS is not
+// protected against reuse, so a kernel calls it once, as its last collective.
+template <typename T, int THREADS, int Q>
+__device__ __forceinline__ void block_sum_once(T (&x)[Q])
+{
+    __shared__ T partial[Q][THREADS / 64];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        x[q] = wave_sum(x[q]);
+        if ((threadIdx.x & 63) == 0)
+            partial[q][threadIdx.x >> 6] = x[q];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        T t = partial[q][0];
+#pragma unroll
+        for (int w = 1; w < THREADS / 64; ++w)
+            t += partial[q][w];
+        x[q] = t;
+    }
 }
 
 // Tiles each workgroup of the reduce pass walks, one after the other.
@@ -417,28 +446,33 @@ struct ScanArgs {
     const void *b;
     void *partials0; // per-workgroup partial sums (first quantity)
     void *partials1; // second quantity, where there is one
-    uint64_t n_tiles; // tail kernels: leftover units; tile kernels take their extent from the grid
+    uint64_t n_tiles; // tail kernels: leftover units; group kernels take their extent from the grid
     uint64_t first_index;
     uint32_t partial_slot;
 };
 
-// Sums of (a-b)^2 and a^2 in binary64.  Read-only, so every lane takes 16 bytes
-// per buffer whatever the element type: a scan tile is 1 KiB per buffer (256
-// fp32 or 512 bf16 elements).  Workgroup b owns tiles [4b, 4b+4), all four whole
-// (the grid covers whole groups only; what is left goes to the tail kernel), so
-// the eight loads are unconditional and all in flight before the arithmetic.
+// The scans only read, and a read-only stream is fastest on this part with large
+// workgroups that keep four 16-byte loads per lane in flight: 1024 lanes, 64 KiB
+// per workgroup (7.0-7.3 TB/s; single-wave workgroups as in the update kernel
+// stay at 6.1-6.6).  A launch covers whole groups; what is left goes to the tail.
+constexpr int kScanThreads = 1024;
+constexpr int kDiffVecs = 2;     // 16-byte vectors per lane and buffer: a group is 32 KiB of each
+constexpr int kChecksumVecs = 4; // 16-byte vectors per lane: a group is 64 KiB = 8192 words
+
+// Sums of (a-b)^2 and a^2 in binary64.  Every lane takes 16 bytes per load
+// whatever the element type.  Fixed order: per lane by vector and element, then
+// the block tree, one pair of partials per workgroup.
 template <typename G>
-__global__ __launch_bounds__(kWave) void diff_sumsq_tiles(const ScanArgs s)
+__global__ __launch_bounds__(kScanThreads) void diff_sumsq_tiles(const ScanArgs s)
 {
-    constexpr int K = kReduceTilesPerGroup;
+    constexpr int K = kDiffVecs;
     double sd = 0.0, sa = 0.0;
-    const uint64_t t0 = (uint64_t)blockIdx.x * K;
+    const uint64_t v0 = (uint64_t)blockIdx.x * (kScanThreads * K) + threadIdx.x;
     u32x4 x[K], y[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-        const uint64_t vec = (t0 + k) * kWave + threadIdx.x;
-        x[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.a) + vec);
-        y[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.b) + vec);
+        x[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.a) + v0 + (uint64_t)k * kScanThreads);
+        y[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.b) + v0 + (uint64_t)k * kScanThreads);
     }
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -460,29 +494,31 @@ __global__ __launch_bounds__(kWave) void diff_sumsq_tiles(const ScanArgs s)
             }
         }
     }
-    sd = wave_sum(sd);
-    sa = wave_sum(sa);
+    double both[2] = {sd, sa};
+    block_sum_once<double, kScanThreads, 2>(both);
     if (threadIdx.x == 0) {
-        reinterpret_cast<double *>(s.partials0)[blockIdx.x] = sd;
-        reinterpret_cast<double *>(s.partials1)[blockIdx.x] = sa;
+        reinterpret_cast<double *>(s.partials0)[blockIdx.x] = both[0];
+        reinterpret_cast<double *>(s.partials1)[blockIdx.x] = both[1];
     }
 }
 
+// Tail: what is left (less than one group), one element per lane, one pair of
+// partials per workgroup of kThreads lanes from slot partial_slot on.
 template <typename G>
-__global__ __launch_bounds__(kWave) void diff_sumsq_tail(const ScanArgs s)
+__global__ __launch_bounds__(kThreads) void diff_sumsq_tail(const ScanArgs s)
 {
-    double sd = 0.0, sa = 0.0;
-    for (uint64_t e = threadIdx.x; e < s.n_tiles; e += kWave) {
+    double both[2] = {0.0, 0.0};
+    const uint64_t e = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e < s.n_tiles) {
         const double x = (double)load_contrib1<G>(s.a, e), y = (double)load_contrib1<G>(s.b, e);
         const double d = x - y;
-        sd += d * d;
-        sa += x * x;
+        both[0] = d * d;
+        both[1] = x * x;
     }
-    sd = wave_sum(sd);
-    sa = wave_sum(sa);
+    block_sum_once<double, kThreads, 2>(both);
     if (threadIdx.x == 0) {
-        reinterpret_cast<double *>(s.partials0)[s.partial_slot] = sd;
-        reinterpret_cast<double *>(s.partials1)[s.partial_slot] = sa;
+        reinterpret_cast<double *>(s.partials0)[s.partial_slot + blockIdx.x] = both[0];
+        reinterpret_cast<double *>(s.partials1)[s.partial_slot + blockIdx.x] = both[1];
     }
 }
 
@@ -504,44 +540,42 @@ __device__ __forceinline__ uint64_t checksum_term(uint64_t w, uint64_t index)
     return checksum_mix(w, (index + 1) * kGolden);
 }
 
-// Checksum over whole 128-word (1 KiB) tiles; lane t owns words 2t, 2t+1 of each
-// of the workgroup's four tiles (whole groups only, as in the scan above), all
-// loaded before the arithmetic.  One 64-bit multiply per lane forms (index + 1)
-// * increment for its first word; the others follow by adding multiples of the
-// increment (arithmetic modulo 2^64).
-__global__ __launch_bounds__(kWave) void checksum_tiles(const ScanArgs s)
+// Checksum over whole groups of 8192 words; lane t owns words 2t, 2t+1 of each of
+// the group's four 16-KiB rows, all loaded before the arithmetic.  One 64-bit
+// multiply per lane forms (index + 1) * increment for its first word; the
+// others follow by adding multiples of the increment (arithmetic modulo 2^64).
+__global__ __launch_bounds__(kScanThreads) void checksum_tiles(const ScanArgs s)
 {
-    constexpr int K = kReduceTilesPerGroup;
+    constexpr int K = kChecksumVecs;
     uint64_t c = 0;
-    const uint64_t t0 = (uint64_t)blockIdx.x * K;
+    const uint64_t v0 = (uint64_t)blockIdx.x * (kScanThreads * K) + threadIdx.x;
     u32x4 v[K];
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-        const uint64_t vec = (t0 + k) * kWave + threadIdx.x;
-        v[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.a) + vec);
-    }
-    const uint64_t w_first = (t0 * kWave + threadIdx.x) * 2; // this lane's first word in the buffer
-    uint64_t ramp = (s.first_index + w_first + 1) * kGolden;
+    for (int k = 0; k < K; ++k)
+        v[k] = load_vec<true>(reinterpret_cast<const u32x4 *>(s.a) + v0 + (uint64_t)k * kScanThreads);
+    uint64_t ramp = (s.first_index + v0 * 2 + 1) * kGolden; // this lane's first word in the buffer
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         c += checksum_mix((uint64_t)v[k].x | ((uint64_t)v[k].y << 32), ramp);
         c += checksum_mix((uint64_t)v[k].z | ((uint64_t)v[k].w << 32), ramp + kGolden);
-        ramp += (uint64_t)(kWave * 2) * kGolden; // next tile: 128 words further on
+        ramp += (uint64_t)(kScanThreads * 2) * kGolden; // next row: 2048 words further on
     }
-    c = wave_sum(c);
+    uint64_t one[1] = {c};
+    block_sum_once<uint64_t, kScanThreads, 1>(one);
     if (threadIdx.x == 0)
-        reinterpret_cast<uint64_t *>(s.partials0)[blockIdx.x] = c;
+        reinterpret_cast<uint64_t *>(s.partials0)[blockIdx.x] = one[0];
 }
 
-__global__ __launch_bounds__(kWave) void checksum_tail(const ScanArgs s)
+// Tail: one word per lane, one partial per workgroup from slot partial_slot on.
+__global__ __launch_bounds__(kThreads) void checksum_tail(const ScanArgs s)
 {
-    uint64_t c = 0;
-    const uint64_t *w = reinterpret_cast<const uint64_t *>(s.a);
-    for (uint64_t i = threadIdx.x; i < s.n_tiles; i += kWave)
-        c += checksum_term(w[i], s.first_index + i);
-    c = wave_sum(c);
+    uint64_t one[1] = {0};
+    const uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < s.n_tiles)
+        one[0] = checksum_term(reinterpret_cast<const uint64_t *>(s.a)[i], s.first_index + i);
+    block_sum_once<uint64_t, kThreads, 1>(one);
     if (threadIdx.x == 0)
-        reinterpret_cast<uint64_t *>(s.partials0)[s.partial_slot] = c;
+        reinterpret_cast<uint64_t *>(s.partials0)[s.partial_slot + blockIdx.x] = one[0];
 }
 
 // Plain copy with the update kernel's access shape: one wave per 1 KiB, 16 B

@@ -37,9 +37,6 @@ static uint32_t reduce_lds(int dtype) { return lds_for_waves(dtype == PS_BF16 ? 
 // source).  When it shares the device with the update kernel it asks for no LDS,
 // so that it never waits behind the update's own LDS reservations.
 constexpr uint32_t kStageAloneLdsBytes = lds_for_waves(8);
-// The read-only verification scans have one or two streams, 4-8 KiB in flight per
-// wave; they run with residency uncapped.
-constexpr uint32_t kScanLdsBytes = 0;
 // Largest grid used; beyond it the kernels loop (never reached below 5e11 elements).
 constexpr uint64_t kMaxGrid = 0x7fffffffull;
 // Second level of the sum-of-squares tree.
@@ -301,25 +298,22 @@ int launch_reduce_sumsq(int dtype, uint32_t n_contrib, const ContribPtrs &g, flo
                                   accumulate, st);
 }
 
-// Workspace of the verification scans, in 8-byte slots, for `units` tiles' worth
-// of input: two partial arrays, each with its own second level.
-static uint64_t scan_groups(uint64_t n_tiles)
-{
-    return (n_tiles + kReduceTilesPerGroup - 1) / kReduceTilesPerGroup;
-}
-
+// Workspace of the verification scans, in 8-byte slots, for a buffer of `bytes`
+// bytes: two partial arrays (one partial per 32 KiB at most, plus the tail's: one
+// per kThreads of the fewer than 16384 elements or 8192 words left), each with
+// its own second level.
 uint64_t verify_workspace_slots(uint64_t bytes)
 {
-    // the narrowest element is 2 bytes: at most bytes/2/256 tiles
-    return 2 * (kFoldBlocks + scan_groups(bytes / 2 / kTileElems) + 1);
+    const uint64_t group_bytes = (uint64_t)kScanThreads * kDiffVecs * 16;
+    const uint64_t tail_partials = group_bytes / 2 / kThreads; // narrowest element: 2 bytes
+    return 2 * (kFoldBlocks + bytes / group_bytes + tail_partials + 2);
 }
 
 template <typename G>
 static int launch_diff_t(const void *a, const void *b, uint64_t count, double *out2,
                          int accumulate, uint64_t *workspace, uint64_t slots, hipStream_t st)
 {
-    constexpr uint64_t kScanTile = kWave * (16 / sizeof(G)); // elements in 1 KiB
-    constexpr uint64_t kGroupElems = kScanTile * kReduceTilesPerGroup;
+    constexpr uint64_t kGroupElems = (uint64_t)kScanThreads * kDiffVecs * (16 / sizeof(G));
     const uint64_t groups = count / kGroupElems; // whole groups; the tail takes the rest
     const uint64_t body = groups * kGroupElems;
     if (groups > kMaxGrid)
@@ -336,9 +330,9 @@ static int launch_diff_t(const void *a, const void *b, uint64_t count, double *o
     s.partial_slot = 0;
     uint64_t n_partials = 0;
     if (groups) {
-        s.n_tiles = groups * kReduceTilesPerGroup;
-        hipLaunchKernelGGL((diff_sumsq_tiles<G>), dim3((uint32_t)groups), dim3(kWave),
-                           kScanLdsBytes, st, s);
+        s.n_tiles = groups;
+        hipLaunchKernelGGL((diff_sumsq_tiles<G>), dim3((uint32_t)groups), dim3(kScanThreads), 0,
+                           st, s);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return (int)e;
@@ -349,11 +343,12 @@ static int launch_diff_t(const void *a, const void *b, uint64_t count, double *o
         s.b = advance<G>(b, body);
         s.n_tiles = count - body;
         s.partial_slot = (uint32_t)n_partials;
-        hipLaunchKernelGGL((diff_sumsq_tail<G>), dim3(1), dim3(kWave), 0, st, s);
+        const uint32_t blocks = (uint32_t)((count - body + kThreads - 1) / kThreads);
+        hipLaunchKernelGGL((diff_sumsq_tail<G>), dim3(blocks), dim3(kThreads), 0, st, s);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return (int)e;
-        n_partials += 1;
+        n_partials += blocks;
     }
     int e = fold_to_one(l1a, l2a, n_partials, out2, accumulate, st);
     if (e != 0)
@@ -375,7 +370,7 @@ int launch_checksum(const void *buf, uint64_t n_words, uint64_t first_index, uin
                     int accumulate, void *workspace, void *stream)
 {
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    constexpr uint64_t kGroupWords = kWave * 2 * kReduceTilesPerGroup;
+    constexpr uint64_t kGroupWords = (uint64_t)kScanThreads * kChecksumVecs * 2;
     const uint64_t groups = n_words / kGroupWords; // whole groups; the tail takes the rest
     const uint64_t body = groups * kGroupWords;
     if (groups > kMaxGrid)
@@ -390,9 +385,8 @@ int launch_checksum(const void *buf, uint64_t n_words, uint64_t first_index, uin
     s.partial_slot = 0;
     uint64_t n_partials = 0;
     if (groups) {
-        s.n_tiles = groups * kReduceTilesPerGroup;
-        hipLaunchKernelGGL(checksum_tiles, dim3((uint32_t)groups), dim3(kWave), kScanLdsBytes, st,
-                           s);
+        s.n_tiles = groups;
+        hipLaunchKernelGGL(checksum_tiles, dim3((uint32_t)groups), dim3(kScanThreads), 0, st, s);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return (int)e;
@@ -403,11 +397,12 @@ int launch_checksum(const void *buf, uint64_t n_words, uint64_t first_index, uin
         s.first_index = first_index + body;
         s.n_tiles = n_words - body;
         s.partial_slot = (uint32_t)n_partials;
-        hipLaunchKernelGGL(checksum_tail, dim3(1), dim3(kWave), 0, st, s);
+        const uint32_t blocks = (uint32_t)((n_words - body + kThreads - 1) / kThreads);
+        hipLaunchKernelGGL(checksum_tail, dim3(blocks), dim3(kThreads), 0, st, s);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return (int)e;
-        n_partials += 1;
+        n_partials += blocks;
     }
     return fold_to_one(l1, l2, n_partials, out, accumulate, st);
 }
