@@ -6,6 +6,7 @@ patterns.
 """
 import ctypes as C
 import os
+import sys
 
 import numpy as np
 
@@ -25,9 +26,15 @@ class Scalars(C.Structure):
 def lib():
     global _lib
     if _lib is None:
-        path = _build.LIB
-        if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
-            _build.build()
+        path = os.environ.get("PS_ORACLE_LIB_UNDER_TEST")
+        if path:
+            # tests/test_oracle_mutants.py points this at a deliberately broken build to
+            # show that the pins notice; nothing else sets it
+            print("oracle: loading %s instead of the built oracle" % path, file=sys.stderr)
+        else:
+            path = _build.LIB
+            if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
+                _build.build()
         L = C.CDLL(path)
         pp = C.POINTER(C.c_void_p)
         L.oracle_widen_bf16.restype = C.c_float
