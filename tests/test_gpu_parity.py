@@ -214,6 +214,36 @@ def test_cast_exhaustive_over_all_binary32_patterns():
     assert not bool(m.view(torch.int32).any()) and not bool(v.view(torch.int32).any())
 
 
+@pytest.mark.parametrize("hpkw", [dict(beta1=0.0, beta2=0.0, eps=0.0),          # sign descent; 0/0 where g == 0
+                                  dict(lr=0.0, weight_decay=0.0),               # nothing moves but m and v
+                                  dict(weight_decay=0.0, eps=1.0),
+                                  dict(lr=10.0, weight_decay=0.5, eps=1e-30),   # wild step, 1 - lr*wd < 0
+                                  dict(beta1=0.999999, beta2=0.9999999)])       # bias corrections far from 1
+@pytest.mark.parametrize("t", [1, 7, 10 ** 6, 2 ** 40])
+def test_degenerate_hyperparameters_and_step_counts(hpkw, t):
+    """Corners of the hyper-parameter space: the scalars both sides derive in binary64 and
+    the special values they lead to (0/0, overflow, sign flips) must coincide."""
+    n, N = TILE + 300, 4
+    _say("hyper-parameter corner %s t=%d" % (hpkw, t))
+    spec = ps.ps_spec_preset("zero3", N, 1, n * N)
+    grads = [gen.gradient(n, 61, 0, r, "bf16") for r in range(N)]
+    for g in grads:
+        g[:32] = 0                                             # exact zero gradient in the first elements
+    state = [gen.master(n, 61), *gen.moments(n, 61, True), np.zeros(n, np.uint16)]
+    state[1][:16] = 0.0
+    state[2][:16] = 0.0                                        # ... and zero moments under half of them
+    base = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+    base.update(hpkw)
+    hp = ps.ps_adamw_t(base["lr"], base["beta1"], base["beta2"], base["eps"], base["weight_decay"], t, 0.0, 0.0)
+    want = [a.copy() for a in state]
+    orc.step_f32(grads, orc.derive_scalars(t=t, n_devices=N, **base), *want)
+    got = _run_gpu(spec, hp, state, grads, "bf16", n)
+    assert assert_state_parity(got, want, "corner") == 0
+    nan = np.isnan(want[0])
+    assert np.array_equal(got[3][~nan], want[3][~nan])
+    assert ((got[3][nan] & 0x7fff) == 0x7fc0).all()
+
+
 def test_run_twice_is_bitwise_identical():
     n, N = 7 * TILE + 99, 8
     _say("determinism n=%d" % n)
