@@ -305,6 +305,11 @@ ps_status_t ps_device_info(ps_device_info_t *info);
  *     PS_F32); n_contrib == 1, contrib[0] points at element 0 of that buffer and
  *     the library reads this shard's slice at shard_offset, as it writes the
  *     parameters' slice.  grad_scale <= 0 still means 1/N: the all-reduce sums.
+ *   Data parallelism (all four modes R): nothing is sharded, so every device
+ *     updates the whole state from the all-reduced gradient: shard->len ==
+ *     psi_padded, valid_len <= psi, all buffers full length and element-0 based,
+ *     n_contrib == 1 as for ZeRO-1.  (ps_cost_eval still reports the Eq. 2
+ *     geometry of shard_index; the step does not use it here.)
  * Anything else: PS_EUNSUPPORTED.  elem_offset must be a multiple of 8.
  * Deterministic: no atomics, results do not depend on launch shape (Theorem 5,
  * assumption 1).  The call only enqueues kernels on hip_stream: it allocates

@@ -81,12 +81,21 @@ ps_status_t check_hp(const ps_adamw_t *hp)
     return PS_OK;
 }
 
-// The placements this path executes: Omega sharded; G sharded with Theta R or S*
-// (ZeRO-2, ZeRO-3), or G and Theta both replicated (ZeRO-1).
+// The placements this path executes: Omega sharded with G sharded and Theta R or S*
+// (ZeRO-2, ZeRO-3); Omega sharded with G and Theta replicated (ZeRO-1); everything
+// replicated (data parallelism, where the "shard" is the whole tensor).
 bool is_zero1(const ps_spec_t *spec)
 {
     return spec->omega == PS_S && spec->grad == PS_R && spec->theta == PS_R;
 }
+
+bool is_dp(const ps_spec_t *spec)
+{
+    return spec->omega == PS_R && spec->grad == PS_R && spec->theta == PS_R;
+}
+
+// Under pi_G = R the gradient is a single all-reduced, full-length buffer.
+bool replicated_grad(const ps_spec_t *spec) { return is_zero1(spec) || is_dp(spec); }
 
 ps_status_t check_path(const ps_spec_t *spec)
 {
@@ -95,12 +104,26 @@ ps_status_t check_path(const ps_spec_t *spec)
         return st;
     const bool sharded_g = spec->omega == PS_S && spec->grad == PS_S &&
                            (spec->theta == PS_R || spec->theta == PS_SG);
-    if (!sharded_g && !is_zero1(spec)) {
+    if (!sharded_g && !replicated_grad(spec)) {
         set_error("step needs pi_Omega = S with (pi_G = S, pi_Theta in {R, S*}) or "
-                  "(pi_G = R, pi_Theta = R)");
+                  "(pi_G = R, pi_Theta = R), or all of them R");
         return PS_EUNSUPPORTED;
     }
     return PS_OK;
+}
+
+// The index range of the flat tensors this device updates: its shard (Eq. 2), or
+// under full replication the whole tensor.
+ps_status_t step_geometry(const ps_spec_t *spec, uint64_t *padded, uint64_t *off, uint64_t *len,
+                          uint64_t *valid)
+{
+    ps_status_t st = shard_geometry(spec, padded, off, len, valid);
+    if (st == PS_OK && is_dp(spec)) {
+        *off = 0;
+        *len = *padded;
+        *valid = spec->psi;
+    }
+    return st;
 }
 
 ps_status_t check_contribs(const void *const *ptrs, uint32_t n_contrib, int32_t dtype,
@@ -159,12 +182,12 @@ ps_status_t check_shard(const ps_spec_t *spec, const ps_shard_t *sh, uint64_t *o
         return PS_EALIGN;
     }
     uint64_t padded, off, len, valid;
-    ps_status_t st = shard_geometry(spec, &padded, &off, &len, &valid);
+    ps_status_t st = step_geometry(spec, &padded, &off, &len, &valid);
     if (st != PS_OK)
         return st;
     if (sh->len != len) {
-        set_error("shard.len %llu differs from psi_padded/N = %llu", (unsigned long long)sh->len,
-                  (unsigned long long)len);
+        set_error("shard.len %llu differs from %llu (psi_padded/N, or psi_padded under full "
+                  "replication)", (unsigned long long)sh->len, (unsigned long long)len);
         return PS_ERANGE;
     }
     if (sh->valid_len > sh->len) {
@@ -261,7 +284,7 @@ ps_status_t ps_step_update(const ps_spec_t *spec, const ps_adamw_t *hp, const ps
         set_error("grads is NULL");
         return PS_EINVAL;
     }
-    const bool z1 = is_zero1(spec);
+    const bool z1 = replicated_grad(spec);
     if ((st = check_contribs(grads->contrib, grads->n_contrib, grads->dtype, spec->n_devices,
                              "contribution", z1)) != PS_OK ||
         (st = check_range(elem_offset, elem_count, shard->len)) != PS_OK)
@@ -296,7 +319,7 @@ ps_status_t ps_step_accumulate(const ps_spec_t *spec, const ps_grads_t *grads, f
     ps_status_t st;
     if ((st = check_path(spec)) != PS_OK)
         return st;
-    if (is_zero1(spec)) {
+    if (replicated_grad(spec)) {
         set_error("accumulation reduces pi_G = S contributions; under pi_G = R the "
                   "all-reduce has already done it");
         return PS_EUNSUPPORTED;
@@ -351,7 +374,7 @@ ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
     ps_status_t st;
     if ((st = check_path(spec)) != PS_OK)
         return st;
-    if (is_zero1(spec) && grads && grads->n_contrib != 1) {
+    if (replicated_grad(spec) && grads && grads->n_contrib != 1) {
         set_error("under pi_G = R the gradient is one all-reduced buffer");
         return PS_EINVAL;
     }
@@ -374,12 +397,12 @@ ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
         set_error("workspace, sumsq_out or reduced_out is misaligned");
         return PS_EALIGN;
     }
-    const bool z1 = is_zero1(spec);
+    const bool z1 = replicated_grad(spec);
     if ((st = check_contribs(grads->contrib, grads->n_contrib, grads->dtype, spec->n_devices,
                              "contribution", z1)) != PS_OK)
         return st;
     uint64_t padded, off, len, valid;
-    if ((st = shard_geometry(spec, &padded, &off, &len, &valid)) != PS_OK ||
+    if ((st = step_geometry(spec, &padded, &off, &len, &valid)) != PS_OK ||
         (st = check_range(elem_offset, elem_count, len)) != PS_OK)
         return st;
     if (valid_len > len) {
@@ -426,7 +449,7 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
         set_error("plan is NULL");
         return PS_EINVAL;
     }
-    if (is_zero1(spec)) {
+    if (replicated_grad(spec)) {
         set_error("the bucket pipeline stages pi_G = S contributions");
         return PS_EUNSUPPORTED;
     }

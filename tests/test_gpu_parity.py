@@ -523,6 +523,33 @@ def test_zero1_replicated_gradient_slice(dtype):
     assert np.array_equal(host(gd).view(np.uint8), before.view(np.uint8))
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_data_parallel_every_replica_updates_the_whole_tensor(dtype):
+    """Data parallelism (all R): each of the N devices applies the all-reduced gradient
+    to the whole state.  One call per device with its own copy of the state: all copies
+    end up identical to the oracle's single unsharded update (state consistency for
+    replicated state), in two ranges that split the tensor at an odd tile."""
+    psi, N = 3 * TILE + 1000, 4
+    _say("data parallel psi=%d N=%d %s" % (psi, N, dtype))
+    g_sum = gen.gradient(psi, 19, 0, 0, dtype, std=4e-3)             # stands for the all-reduced sum
+    state = [gen.master(psi, 19), *gen.moments(psi, 19, True), np.zeros(psi, np.uint16)]
+    hpd, hp = hp_of(None, 4)
+    want = [a.copy() for a in state]
+    orc.step_f32([g_sum], orc.derive_scalars(t=4, n_devices=N, **hpd), *want)     # mean = sum / N
+    gd = dev(g_sum)
+    cut = TILE + 8
+    for i in range(N):
+        spec = ps.ps_spec_preset("dp", N, i, psi)
+        t = [dev(a) for a in state]
+        sh = shard_of(*t, psi)
+        ps.ps_step_update(spec, hp, sh, grads_of([gd], dtype), 0, cut, stream_handle())
+        ps.ps_step_update(spec, hp, sh, grads_of([gd], dtype), cut, psi - cut, stream_handle())
+        torch.cuda.synchronize()
+        got = [host(x) for x in t]
+        assert assert_state_parity(got, want, "dp replica %d" % i) == 0
+        assert np.array_equal(got[3], want[3])
+
+
 @pytest.mark.parametrize("dtype,N", [("bf16", 8), ("f32", 6), ("bf16", 3)])
 def test_gradient_accumulation_then_update(dtype, N):
     """k micro-batches accumulate into the FP32 shard (fixed order inside a micro-batch,

@@ -34,7 +34,7 @@ def test_update_rejects_bad_arguments():
     assert _status(lambda: upd(spec, hp, None, grads, 0, 8)) == ps.PS_EINVAL
     assert _status(lambda: upd(spec, hp, shard, None, 0, 8)) == ps.PS_EINVAL
     # placements this path does not execute
-    for name in ("dp", "zero_offload", "tp"):
+    for name in ("zero_offload", "tp", "pp"):
         other = ps.ps_spec_preset(name, 4, 1, 4096)
         assert _status(lambda: upd(other, hp, shard, grads, 0, 8)) == ps.PS_EUNSUPPORTED
     # step count, betas
@@ -96,6 +96,22 @@ def test_zero1_takes_one_replicated_gradient():
     assert _status(lambda: ps.ps_step_accumulate(spec, one, FAKE, 1, 0, 8, 1024)) == ps.PS_EUNSUPPORTED
     plan = ps.ps_bucket_plan_t()
     assert _status(lambda: ps.ps_step_update_bucketed(spec, hp, shard, plan)) == ps.PS_EUNSUPPORTED
+
+
+def test_data_parallel_updates_the_whole_tensor():
+    """All four states R: the "shard" is everything, the gradient one all-reduced buffer."""
+    spec = ps.ps_spec_preset("dp", 4, 1, 4096)
+    _, hp, shard, grads4 = _valid()
+    upd = ps.ps_step_update
+    one = ps.make_grads([FAKE], ps.PS_BF16)
+    assert _status(lambda: upd(spec, hp, shard, one, 0, 8)) == ps.PS_ERANGE         # a quarter is not the whole
+    whole = ps.ps_shard_t(FAKE, FAKE * 2, FAKE * 3, FAKE * 4, 4096, 4096)
+    assert _status(lambda: upd(spec, hp, whole, grads4, 0, 8)) == ps.PS_EINVAL       # N buffers: no
+    upd(spec, hp, whole, one, 0, 0)                                                  # valid, empty
+    assert _status(lambda: upd(spec, hp, whole, one, 4096, 8)) == ps.PS_ERANGE
+    assert _status(lambda: ps.ps_step_accumulate(spec, one, FAKE, 1, 0, 8, 4096)) == ps.PS_EUNSUPPORTED
+    plan = ps.ps_bucket_plan_t()
+    assert _status(lambda: ps.ps_step_update_bucketed(spec, hp, whole, plan)) == ps.PS_EUNSUPPORTED
 
 
 def test_accumulate_rejects_bad_arguments():
