@@ -362,7 +362,12 @@ uint64_t ps_workspace_bytes(uint64_t elem_count);
  * already there, so several buckets called in order give a reproducible total.
  * The caller combines it with the other devices' sums, forms the clip
  * coefficient and calls ps_step_update with the reduced gradient as a single
- * PS_F32 contribution, grad_scale = 1 and that coefficient.  Like
+ * PS_F32 contribution, grad_scale = 1 and that coefficient.  Under pi_G = R
+ * (ZeRO-1, data parallelism) contrib[0] is the all-reduced full-length buffer
+ * and this device's range of it is read; reduced_out is still based at the
+ * first element of that range, i.e. the mean leaves this call in sharded form,
+ * so under ZeRO-1 the second phase is a pi_G = S call on the same geometry (the
+ * ZeRO-2 row of Table 2).  Like
  * ps_step_update the call only enqueues kernels (the partial sums live in the
  * caller's workspace, which a later call on another stream must not share while
  * this one is in flight) and may be recorded by a stream capture. */

@@ -550,6 +550,51 @@ def test_data_parallel_every_replica_updates_the_whole_tensor(dtype):
         assert np.array_equal(got[3], want[3])
 
 
+@pytest.mark.parametrize("strategy", ["zero1", "dp"])
+def test_clip_phases_on_a_replicated_gradient(strategy):
+    """Clipping under pi_G = R: phase 1 reads this device's range of the all-reduced
+    buffer (its slice under ZeRO-1, everything under data parallelism), phase 2 updates
+    from the reduced mean with the coefficient."""
+    N, i = 4, 3
+    psi = N * (2 * TILE + 520)
+    spec = ps.ps_spec_preset(strategy, N, i, psi)
+    c = ps.ps_cost_eval(spec)
+    off, n = (0, psi) if strategy == "dp" else (c.shard_offset, c.shard_len)
+    _say("clip on a replicated gradient, %s: range [%d,+%d) of %d" % (strategy, off, n, psi))
+    g_sum = gen.gradient(psi, 29, 0, 0, "f32", std=5e-2)
+    mine = np.ascontiguousarray(g_sum[off:off + n])
+    mean, ss = orc.mean_sumsq([mine], 1.0 / N)
+    coef = orc.clip_coef(ss, 0.0 if strategy == "dp" else 3 * ss, 1.0)
+    assert coef < 1.0
+    state = [gen.master(n, 29), *gen.moments(n, 29, True), np.zeros(n, np.uint16)]
+    hpd, _ = hp_of(None, 6)
+    want = [a.copy() for a in state]
+    orc.step_f32([mine], orc.derive_scalars(t=6, n_devices=N, clip_coef=coef, **hpd), *want)
+    gd = dev(g_sum)
+    red = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+    ssd = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ws = torch.empty(ps.ps_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    ps.ps_step_reduce_sumsq(spec, grads_of([gd], "f32"), 0.0, red.data_ptr(), ssd.data_ptr(), 0,
+                            ws.data_ptr(), ws.numel(), 0, n, n, stream_handle())
+    torch.cuda.synchronize()
+    assert np.array_equal(host(red).view(np.uint32), mean.view(np.uint32))
+    assert abs(float(ssd.item()) - ss) <= 1e-12 * ss
+    th, m, v = [dev(a) for a in state[:3]]
+    full_p = dev(np.full(psi, 0x6666, np.uint16))
+    _, hp = hp_of(None, 6, grad_scale=1.0, clip_coef=coef)
+    # Phase 1 leaves the mean in sharded form (element 0 = first element of this device's
+    # range), so under ZeRO-1 phase 2 is a pi_G = S call on the same geometry (the ZeRO-2
+    # row); under data parallelism the range is the whole tensor and the spec stays.
+    spec2 = ps.ps_spec_preset("zero2", N, i, psi) if strategy == "zero1" else spec
+    ps.ps_step_update(spec2, hp, shard_of(th, m, v, full_p, n), grads_of([red], "f32"), 0, n,
+                      stream_handle())
+    torch.cuda.synchronize()
+    p = host(full_p)
+    got = [host(th), host(m), host(v), p[off:off + n]]
+    assert assert_state_parity(got, want, "clip %s" % strategy) == 0
+    assert (p[:off] == 0x6666).all() and (p[off + n:] == 0x6666).all()
+
+
 @pytest.mark.parametrize("dtype,N", [("bf16", 8), ("f32", 6), ("bf16", 3)])
 def test_gradient_accumulation_then_update(dtype, N):
     """k micro-batches accumulate into the FP32 shard (fixed order inside a micro-batch,
