@@ -57,6 +57,9 @@ def main():
                     help="keep the bucket source in pinned host memory (the step is then bound by "
                          "the host link; reported for reference, never the headline value)")
     ap.add_argument("--bucket-elems", type=int, default=0, help="override the workload's bucket size")
+    ap.add_argument("--clip-on-host", action="store_true",
+                    help="clipped workload: read the sum of squares back and form the coefficient "
+                         "on the host (one device->host sync per step) instead of on the device")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-baseline-seconds", type=float, default=15.0,
                     help="about how much CPU work the oracle baseline may take")
@@ -159,6 +162,8 @@ def main():
             ssd = torch.zeros(1, dtype=torch.float64, device="cuda")
             ws = torch.empty(ps.ps_workspace_bytes(n), dtype=torch.uint8, device="cuda")
             gred = ps.make_grads([red.data_ptr()], ps.PS_F32)
+            others = torch.zeros(1, dtype=torch.float64, device="cuda")
+            coef_dev = torch.zeros(1, dtype=torch.float32, device="cuda")
         rec = [0]
 
         def step(record):
@@ -169,9 +174,17 @@ def main():
                 if clip:
                     ps.ps_step_reduce_sumsq(spec, g, 0.0, red.data_ptr(), ssd.data_ptr(), 0,
                                             ws.data_ptr(), ws.numel(), 0, n, cost.valid_len, s)
-                    ss = float(ssd.item())      # the one device->host sync of a clipped step
-                    coef = ps.ps_clip_coef(ss, 5.0 * ss, w.max_grad_norm)   # five iid peer shards
-                    ps.ps_step_update(spec, hp(coef, 1.0), shard, gred, 0, n, s)
+                    if args.clip_on_host:
+                        ss = float(ssd.item())      # the one device->host sync of such a step
+                        coef = ps.ps_clip_coef(ss, 5.0 * ss, w.max_grad_norm)   # five iid peer shards
+                        ps.ps_step_update(spec, hp(coef, 1.0), shard, gred, 0, n, s)
+                    else:                           # everything stays on the stream
+                        torch.mul(ssd, 5.0, out=others)     # stands for the peers' all-reduced sums
+                        ps.ps_step_clip_coef(ssd.data_ptr(), others.data_ptr(), w.max_grad_norm,
+                                             coef_dev.data_ptr(), s)
+                        h = hp(0.0, 1.0)
+                        h.clip_coef_device = coef_dev.data_ptr()
+                        ps.ps_step_update(spec, h, shard, gred, 0, n, s)
                 elif k_mb > 1:
                     for j in range(k_mb):   # the same resident contributions stand for each micro-batch
                         ps.ps_step_accumulate(spec, g, accum.data_ptr(), j == 0, 0, n,
@@ -264,6 +277,8 @@ def main():
                                      (args.pool_elems, args.copy_engine, args.schedule)) +
                                     (" (source in pinned HOST memory)" if args.source_host else "")
                                     if bucketed else None,
+                   "clip_coefficient": (("host (one sync per step)" if args.clip_on_host
+                                         else "device (no host round trip)") if clip else None),
                    "bytes_per_elem": bpe, "step_GBps": bpe * elems_per_step / (ms_per_step * 1e-3) / 1e9,
                    "device": info.name.decode(), "arch": info.arch.decode(),
                    "compute_units": info.compute_units, "memory_clock_khz": info.memory_clock_khz,

@@ -37,7 +37,7 @@
 extern "C" {
 #endif
 
-#define PS_ABI_VERSION 1u
+#define PS_ABI_VERSION 2u
 /* Largest number of gradient contributions one call can reduce. */
 #define PS_MAX_CONTRIB 16u
 
@@ -97,6 +97,12 @@ typedef struct ps_adamw_t {
     uint64_t step;     /* t >= 1, the step being taken (bias correction 1-beta^t)     */
     double grad_scale; /* <= 0: 1/N, the mean over devices (proof of Theorem 5)       */
     double clip_coef;  /* <= 0: 1 (no clipping); else multiplies the mean gradient    */
+    const float *clip_coef_device; /* DEVICE, optional (NULL: use clip_coef).  When set,
+                          the kernels read the coefficient from this address when they
+                          run (so it may be written earlier on the same stream, e.g. by
+                          ps_step_clip_coef, with no host round trip), clip_coef must be
+                          0, and a NaN found there makes the launch a no-op: nothing is
+                          read or written (the step is skipped).                       */
 } ps_adamw_t;
 
 /* This device's shard of Omega and its output slot.  All DEVICE pointers. */
@@ -231,6 +237,16 @@ ps_status_t ps_cost_eval(const ps_spec_t *spec, ps_cost_t *cost);
  * or negative sum, or max_norm <= 0, gives NaN (the caller should skip the
  * step).  Pass the result as ps_adamw_t.clip_coef. */
 double ps_clip_coef(double sumsq_local, double sumsq_others, double max_norm);
+
+/* The same coefficient formed on the device, for callers that keep the two
+ * phases of a clipped step on the stream: *coef_out (DEVICE float) =
+ * ps_clip_coef(*sumsq_local, sumsq_others ? *sumsq_others : 0, max_norm) rounded
+ * to binary32, NaN where ps_clip_coef gives NaN.  sumsq_local and sumsq_others
+ * are DEVICE doubles (the result of ps_step_reduce_sumsq; the other devices'
+ * total as an all-reduce leaves it; NULL: none).  Enqueued on `stream`; pass
+ * coef_out as ps_adamw_t.clip_coef_device of the following ps_step_update. */
+ps_status_t ps_step_clip_coef(const double *sumsq_local, const double *sumsq_others,
+                              double max_norm, float *coef_out, void *stream);
 
 /* Illustrative strategy selection (Algorithm 1) with its printed thresholds:
  * 16 psi < 0.7 device_mem_bytes -> data parallel (R,R,R,R); else ZeRO-3

@@ -24,7 +24,7 @@ __all__ = [
     "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
     "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum",
     "ps_select_strategy", "ps_compose_index", "ps_compose_cost", "ps_step_update_offloaded",
-    "EXPORTED_SYMBOLS",
+    "ps_step_clip_coef", "EXPORTED_SYMBOLS",
 ]
 
 PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
@@ -40,6 +40,7 @@ EXPORTED_SYMBOLS = (
     "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
     "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum",
     "ps_select_strategy", "ps_compose_index", "ps_compose_cost", "ps_step_update_offloaded",
+    "ps_step_clip_coef",
 )
 
 
@@ -71,7 +72,8 @@ class ps_cost_t(C.Structure):
 class ps_adamw_t(C.Structure):
     _fields_ = [("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double),
                 ("eps", C.c_double), ("weight_decay", C.c_double), ("step", C.c_uint64),
-                ("grad_scale", C.c_double), ("clip_coef", C.c_double)]
+                ("grad_scale", C.c_double), ("clip_coef", C.c_double),
+                ("clip_coef_device", C.c_void_p)]
 
 
 class ps_shard_t(C.Structure):
@@ -140,6 +142,8 @@ def library():
                                          C.POINTER(C.c_int32)]
         L.ps_compose_index.restype = C.c_int
         L.ps_compose_index.argtypes = [C.c_uint32] * 3 + [C.POINTER(C.c_uint32)] * 4
+        L.ps_step_clip_coef.restype = C.c_int
+        L.ps_step_clip_coef.argtypes = [C.c_void_p, C.c_void_p, C.c_double, C.c_void_p, C.c_void_p]
         L.ps_compose_cost.restype = C.c_int
         L.ps_compose_cost.argtypes = [C.POINTER(ps_spec_t), C.c_uint32, C.POINTER(ps_cost_t)]
         L.ps_device_info.restype = C.c_int
@@ -178,8 +182,8 @@ def library():
                                          C.c_void_p, C.c_uint64, C.c_void_p]
         L.ps_probe_copy.restype = C.c_int
         L.ps_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
-        if L.ps_abi_version() != 1:
-            raise ImportError("libps_step.so has ABI %d, binding wants 1" % L.ps_abi_version())
+        if L.ps_abi_version() != 2:
+            raise ImportError("libps_step.so has ABI %d, binding wants 2" % L.ps_abi_version())
         _lib = L
     return _lib
 
@@ -277,6 +281,11 @@ def ps_step_update_bucketed(spec, hp, shard, plan):
 
 def ps_step_update_offloaded(spec, hp, plan, grads):
     _check(library().ps_step_update_offloaded(_ref(spec), _ref(hp), _ref(plan), _ref(grads)))
+
+
+def ps_step_clip_coef(sumsq_local, sumsq_others, max_norm, coef_out, stream=0):
+    _check(library().ps_step_clip_coef(sumsq_local or None, sumsq_others or None, max_norm,
+                                       coef_out or None, stream or None))
 
 
 def ps_workspace_bytes(elem_count):

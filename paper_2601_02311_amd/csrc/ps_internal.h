@@ -25,6 +25,7 @@ struct StepScalars {
     float step; // lr / (1 - beta1^t)
     float isb2; // 1 / sqrt(1 - beta2^t)
     float lw;   // lr * weight_decay
+    const float *cc_device; // when set: the clip coefficient is read from here at run time
 };
 
 struct ContribPtrs {
@@ -41,6 +42,8 @@ uint64_t reduce_workspace_doubles(uint64_t count);
 // They return the hipError_t of the launch as int (0 = success).
 int launch_update(int dtype, uint32_t n_contrib, const ContribPtrs &g, float *master, float *m,
                   float *v, uint16_t *out, uint64_t count, const StepScalars &s, void *stream);
+int launch_clip_coef(const double *sumsq_local, const double *sumsq_others, double max_norm,
+                     float *coef_out, void *stream);
 int launch_reduce_sumsq(int dtype, uint32_t n_contrib, const ContribPtrs &g, float gs,
                         float *reduced_out, uint64_t count, double *partials,
                         double *sumsq_out, int accumulate, void *stream);

@@ -145,6 +145,35 @@ __device__ __forceinline__ float load_contrib1(const void *base, uint64_t elem)
         return reinterpret_cast<const float *>(base)[elem];
 }
 
+// The clip coefficient of a launch: the host's value, or what the device holds at
+// clip_coef_device by now.  Returns false when that is NaN: the step is skipped.
+__device__ __forceinline__ bool resolve_clip(StepScalars &s)
+{
+    if (s.cc_device) {
+        const float c = *s.cc_device;
+        if (!(c == c))
+            return false;
+        s.cc = c;
+    }
+    return true;
+}
+
+// Clip coefficient from the sums of squares (one lane), the host formula in binary64.
+__global__ void clip_coef_kernel(const double *sumsq_local, const double *sumsq_others,
+                                 double max_norm, float *coef_out)
+{
+    const double a = *sumsq_local, b = sumsq_others ? *sumsq_others : 0.0;
+    const double total = a + b;
+    double coef;
+    if (!(total - total == 0.0) || a < 0.0 || b < 0.0 || !(max_norm > 0.0)) {
+        coef = __builtin_nan("");
+    } else {
+        coef = max_norm / (__builtin_sqrt(total) + 1e-6);
+        coef = coef < 1.0 ? coef : 1.0;
+    }
+    *coef_out = (float)coef;
+}
+
 struct UpdateArgs {
     ContribPtrs g;
     float *master, *m, *v;
@@ -165,6 +194,9 @@ template <int N, typename G>
 __global__ __launch_bounds__(kWave) void update_tiles(const UpdateArgs a)
 {
     const uint32_t n = N ? N : a.n_contrib;
+    StepScalars s = a.s;
+    if (!resolve_clip(s))
+        return;
     for (uint64_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
         const uint64_t e = tile * kTileElems + (uint64_t)threadIdx.x * 4;
         f32x4 acc, th, mm, vv;
@@ -188,7 +220,7 @@ __global__ __launch_bounds__(kWave) void update_tiles(const UpdateArgs a)
             for (uint32_t r = 1; r < n; ++r)
                 acc = acc + load_contrib4<G, true>(a.g.p[r], e);
         }
-        step_element4(acc, th, mm, vv, a.s);
+        step_element4(acc, th, mm, vv, s);
         u32x2 pk;
         pk.x = narrow_bf16(th.x) | (narrow_bf16(th.y) << 16);
         pk.y = narrow_bf16(th.z) | (narrow_bf16(th.w) << 16);
@@ -205,13 +237,14 @@ template <typename G>
 __global__ __launch_bounds__(kWave) void update_tail(const UpdateArgs a)
 {
     const uint64_t e = (uint64_t)blockIdx.x * kWave + threadIdx.x;
-    if (e >= a.n_tiles)
+    StepScalars s = a.s;
+    if (e >= a.n_tiles || !resolve_clip(s))
         return;
     float acc = load_contrib1<G>(a.g.p[0], e);
     for (uint32_t r = 1; r < a.n_contrib; ++r)
         acc = acc + load_contrib1<G>(a.g.p[r], e);
     float th = a.master[e], m = a.m[e], v = a.v[e];
-    step_element(acc, th, m, v, a.s);
+    step_element(acc, th, m, v, s);
     a.master[e] = th;
     a.m[e] = m;
     a.v[e] = v;

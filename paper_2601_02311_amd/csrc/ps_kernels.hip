@@ -298,6 +298,14 @@ int launch_reduce_sumsq(int dtype, uint32_t n_contrib, const ContribPtrs &g, flo
                                   accumulate, st);
 }
 
+int launch_clip_coef(const double *sumsq_local, const double *sumsq_others, double max_norm,
+                     float *coef_out, void *stream)
+{
+    hipLaunchKernelGGL(clip_coef_kernel, dim3(1), dim3(1), 0, reinterpret_cast<hipStream_t>(stream),
+                       sumsq_local, sumsq_others, max_norm, coef_out);
+    return (int)hipGetLastError();
+}
+
 // Workspace of the verification scans, in 8-byte slots, for a buffer of `bytes`
 // bytes: two partial arrays (one partial per 32 KiB at most, plus the tail's: one
 // per kThreads of the fewer than 16384 elements or 8192 words left), each with

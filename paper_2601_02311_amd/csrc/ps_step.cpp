@@ -52,6 +52,7 @@ StepScalars derive_scalars(const ps_adamw_t &hp, uint32_t n_devices)
     s.step = (float)(hp.lr / bias1);
     s.isb2 = (float)(1.0 / std::sqrt(bias2));
     s.lw = (float)(hp.lr * hp.weight_decay);
+    s.cc_device = hp.clip_coef_device;
     return s;
 }
 
@@ -77,6 +78,16 @@ ps_status_t check_hp(const ps_adamw_t *hp)
     if (std::isnan(hp->grad_scale) || std::isnan(hp->clip_coef)) {
         set_error("grad_scale or clip_coef is NaN");
         return PS_ERANGE;
+    }
+    if (hp->clip_coef_device) {
+        if (hp->clip_coef != 0.0) {
+            set_error("clip_coef must be 0 when clip_coef_device is set");
+            return PS_EINVAL;
+        }
+        if (reinterpret_cast<uintptr_t>(hp->clip_coef_device) & 3u) {
+            set_error("clip_coef_device is not 4-byte aligned");
+            return PS_EALIGN;
+        }
     }
     return PS_OK;
 }
@@ -432,6 +443,29 @@ ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
                                 stream);
     if (e != 0)
         return hip_fail((hipError_t)e, "reduce kernel launch");
+    return PS_OK;
+}
+
+ps_status_t ps_step_clip_coef(const double *sumsq_local, const double *sumsq_others,
+                              double max_norm, float *coef_out, void *stream)
+{
+    clear_error();
+    if (!sumsq_local || !coef_out) {
+        set_error("sumsq_local or coef_out is NULL");
+        return PS_EINVAL;
+    }
+    if ((reinterpret_cast<uintptr_t>(sumsq_local) & 7u) ||
+        (reinterpret_cast<uintptr_t>(sumsq_others) & 7u) ||
+        (reinterpret_cast<uintptr_t>(coef_out) & 3u)) {
+        set_error("sumsq pointers need 8-byte and coef_out 4-byte alignment");
+        return PS_EALIGN;
+    }
+    ps_status_t st = need_device();
+    if (st != PS_OK)
+        return st;
+    int e = launch_clip_coef(sumsq_local, sumsq_others, max_norm, coef_out, stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "clip coefficient kernel launch");
     return PS_OK;
 }
 

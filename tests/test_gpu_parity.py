@@ -370,23 +370,113 @@ def test_clipped_two_phase_step_matches_oracle():
     assert np.float32(ps.ps_clip_coef(ss_gpu, 5 * ss_gpu, w.max_grad_norm)) == np.float32(coef)
 
 
+def test_clip_coefficient_formed_on_the_device():
+    """ps_step_clip_coef against the oracle's binary64 formula on the same sums: the
+    binary32 coefficient must be the same bit pattern (sqrt and division in binary64 are
+    correctly rounded on both sides), NaN exactly where the host function reports NaN."""
+    rng = np.random.default_rng(7)
+    a = np.concatenate([10.0 ** rng.uniform(-30, 30, 40), [0.0, 1e-300, 4.0, np.inf, np.nan, -1.0, 1.0]])
+    b = np.concatenate([10.0 ** rng.uniform(-30, 30, 40), [0.0, 0.0, 12.0, 1.0, 1.0, 1.0, np.inf]])
+    mx = np.concatenate([10.0 ** rng.uniform(-3, 3, 40), [1.0, 1.0, 1.0, 1.0, 1.0, 1.0, 1.0]])
+    _say("device clip coefficient on %d (local, others, max_norm) triples" % a.size)
+    da, db = dev(a), dev(b)
+    out = torch.full((a.size,), -7.0, dtype=torch.float32, device="cuda")
+    for k in range(a.size):
+        ps.ps_step_clip_coef(da.data_ptr() + 8 * k, db.data_ptr() + 8 * k, float(mx[k]),
+                             out.data_ptr() + 4 * k, stream_handle())
+    lone = torch.full((1,), -7.0, dtype=torch.float32, device="cuda")
+    ps.ps_step_clip_coef(da.data_ptr() + 8 * 42, 0, 1.0, lone.data_ptr(), stream_handle())   # no others: 4.0 alone
+    torch.cuda.synchronize()
+    got = host(out)
+    for k in range(a.size):
+        lib = ps.ps_clip_coef(float(a[k]), float(b[k]), float(mx[k]))
+        if np.isnan(lib):
+            assert np.isnan(got[k]), k
+        else:
+            want = np.float32(orc.clip_coef(float(a[k]), float(b[k]), float(mx[k])))
+            assert got[k].view(np.uint32) == want.view(np.uint32), (k, a[k], b[k], mx[k])
+            assert np.float32(lib).view(np.uint32) == want.view(np.uint32)
+    assert np.isnan(got[-4:]).all() and not np.isnan(got[:43]).any()
+    assert host(lone)[0] == np.float32(orc.clip_coef(4.0, 0.0, 1.0))
+
+
+def test_clipped_step_without_a_host_round_trip():
+    """Phase 1, the coefficient and phase 2 all enqueued on one stream; the update reads
+    the coefficient the device wrote.  Compared with the oracle given the same sums; a
+    second run with an infinite gradient must leave every buffer as it was."""
+    w = WORKLOADS["13b_clip"]
+    N = w.n_devices
+    n = 7 * TILE + 1536 + 40
+    valid = n - 9
+    _say("clip on the stream n=%d valid=%d N=%d" % (n, valid, N))
+    spec = ps.ps_spec_preset(w.strategy, N, 0, n * N)
+    grads = [gen.gradient(n, w.seed, 2, r, "f32", 1e-2, student_t_dof=3) for r in range(N)]
+    state = [gen.master(n, w.seed), *gen.moments(n, w.seed, True), np.full(n, 0xABCD, np.uint16)]
+    hpd, _ = hp_of(w, 11)
+    gd = [dev(g) for g in grads]
+    th, m, v, p = [dev(a) for a in state]
+    red = torch.zeros(n, dtype=torch.float32, device="cuda")
+    ssd = torch.zeros(1, dtype=torch.float64, device="cuda")
+    others = torch.zeros(1, dtype=torch.float64, device="cuda")
+    coef = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = torch.empty(ps.ps_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    hp = ps.ps_adamw_t(hpd["lr"], hpd["beta1"], hpd["beta2"], hpd["eps"], hpd["weight_decay"], 11,
+                       1.0, 0.0, coef.data_ptr())
+
+    def enqueue():
+        ps.ps_step_reduce_sumsq(spec, grads_of(gd, "f32"), 0.0, red.data_ptr(), ssd.data_ptr(), 0,
+                                ws.data_ptr(), ws.numel(), 0, n, valid, stream_handle())
+        torch.mul(ssd, 5.0, out=others)                  # stands for the all-reduce of the peers' sums
+        ps.ps_step_clip_coef(ssd.data_ptr(), others.data_ptr(), w.max_grad_norm, coef.data_ptr(),
+                             stream_handle())
+        ps.ps_step_update(spec, hp, shard_of(th, m, v, p, n, valid), grads_of([red], "f32"), 0, n,
+                          stream_handle())
+    enqueue()
+    torch.cuda.synchronize()
+    ss = float(ssd.item())
+    c = orc.clip_coef(ss, 5.0 * ss, w.max_grad_norm)
+    assert c < 1.0 and host(coef)[0] == np.float32(c)
+    want = [a.copy() for a in state]
+    orc.step_f32(grads, orc.derive_scalars(t=11, n_devices=N, clip_coef=c, **hpd), *want, lo=0, hi=valid)
+    got = [host(x) for x in (th, m, v, p)]
+    assert assert_state_parity(got, want, "clip on the stream") == 0
+    # a non-finite gradient: NaN coefficient, the update launches turn into no-ops
+    bad = grads[2].copy()
+    bad[n // 2] = np.inf
+    gd[2].copy_(dev(bad))
+    enqueue()
+    torch.cuda.synchronize()
+    assert np.isinf(float(ssd.item())) and np.isnan(host(coef)[0])
+    for x, a in zip((th, m, v, p), got):
+        assert np.array_equal(host(x).view(np.uint8), a.view(np.uint8))
+    # the host coefficient and the device coefficient exclude each other
+    both = ps.ps_adamw_t(hpd["lr"], hpd["beta1"], hpd["beta2"], hpd["eps"], hpd["weight_decay"], 11,
+                         1.0, 0.5, coef.data_ptr())
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_step_update(spec, both, shard_of(th, m, v, p, n, valid), grads_of([red], "f32"), 0, n,
+                          stream_handle())
+    assert e.value.status == ps.PS_EINVAL
+
+
 def test_both_phases_captured_in_a_hip_graph_and_replayed():
-    """The two launch-only entry points allocate nothing and synchronise nothing, so a
-    caller may capture them.  One graph holds phase 1 (reduce + sum of squares) and
-    phase 2 (update from the reduced gradient, fixed coefficient); it is replayed three
-    times with eager work and synchronisation between the replays, and every replay is
-    compared with the oracle advanced by one more step."""
+    """The launch-only entry points allocate nothing and synchronise nothing, so a caller
+    may capture them.  One graph holds a whole clipped step: phase 1 (reduce + sum of
+    squares), the coefficient formed on the device, phase 2 (update from the reduced
+    gradient).  It is replayed three times with eager work and synchronisation between
+    the replays, and every replay is compared with the oracle advanced by one more step."""
     N, n = 6, 5 * TILE + 777
     valid = n - 3
     _say("graph capture: phases 1+2, n=%d N=%d, 3 replays" % (n, N))
     spec = ps.ps_spec_preset("zero3", N, 0, n * N)
     grads = [gen.gradient(n, 41, 0, r, "f32", 1e-2) for r in range(N)]
     state = [gen.master(n, 41), *gen.moments(n, 41, True), np.full(n, 0x7777, np.uint16)]
-    t, coef = 9, 0.37
-    hpd, hp = hp_of(None, t, grad_scale=1.0, clip_coef=coef)
+    t, max_norm = 9, 0.05
+    hpd, _ = hp_of(None, t)
     _, ss = orc.mean_sumsq(grads, 1.0 / N, 0, valid)
     want = [a.copy() for a in state]
-    s = orc.derive_scalars(t=t, n_devices=N, clip_coef=coef, **hpd)
+    cdev = torch.zeros(1, dtype=torch.float32, device="cuda")
+    hp = ps.ps_adamw_t(hpd["lr"], hpd["beta1"], hpd["beta2"], hpd["eps"], hpd["weight_decay"], t,
+                       1.0, 0.0, cdev.data_ptr())
     gd = [dev(g) for g in grads]
     th, m, v, p = [dev(a) for a in state]
     red = torch.zeros(n, dtype=torch.float32, device="cuda")
@@ -398,18 +488,26 @@ def test_both_phases_captured_in_a_hip_graph_and_replayed():
     with torch.cuda.graph(graph):
         ps.ps_step_reduce_sumsq(spec, gl, 0.0, red.data_ptr(), ssd.data_ptr(), 0, ws.data_ptr(),
                                 ws.numel(), 0, n, valid, stream_handle())
+        ps.ps_step_clip_coef(ssd.data_ptr(), 0, max_norm, cdev.data_ptr(), stream_handle())
         ps.ps_step_update(spec, hp, shard, gr, 0, n, stream_handle())
     torch.cuda.synchronize()
     assert np.array_equal(host(th).view(np.uint32), state[0].view(np.uint32))   # capture ran nothing
+    # the oracle's coefficient from the device's own sum (the two sums agree to 1e-12, the
+    # coefficient must not depend on which one is rounded)
+    ps.ps_step_reduce_sumsq(spec, gl, 0.0, 0, ssd.data_ptr(), 0, ws.data_ptr(), ws.numel(), 0, n, valid,
+                            stream_handle())
+    coef = orc.clip_coef(float(ssd.item()), 0.0, max_norm)
+    assert coef < 1.0
+    s = orc.derive_scalars(t=t, n_devices=N, clip_coef=coef, **hpd)
     for k in range(3):
-        red.fill_(float("nan")); ssd.fill_(-1.0)           # eager work between the replays
+        red.fill_(float("nan")); ssd.fill_(-1.0); cdev.fill_(float("nan"))   # eager work between the replays
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
         orc.step_f32(grads, s, *want, lo=0, hi=valid)
         got = [host(x) for x in (th, m, v, p)]
         assert assert_state_parity(got, want, "replay %d" % k) == 0
-        assert abs(float(ssd.item()) - ss) <= 1e-12 * ss
+        assert abs(float(ssd.item()) - ss) <= 1e-12 * ss and host(cdev)[0] == np.float32(coef)
         for g_, a in zip(got, state):
             assert np.array_equal(g_[valid:].view(np.uint8), a[valid:].view(np.uint8))
 

@@ -270,3 +270,20 @@ def test_valid_calls_report_no_device():
     assert _status(lambda: ps.ps_probe_copy(FAKE, FAKE * 2, 4096)) == ps.PS_ENODEVICE
     assert _status(lambda: ps.ps_step_reduce_sumsq(
         spec, grads, 0.0, FAKE, FAKE, 0, FAKE, ps.ps_workspace_bytes(8), 0, 8, 1024)) == ps.PS_ENODEVICE
+
+
+def test_device_clip_coefficient_arguments():
+    spec, _, shard, grads = _valid()
+    upd = ps.ps_step_update
+    hp = ps.ps_adamw_t(1e-4, 0.9, 0.999, 1e-8, 0.01, 1, 0.0, 0.0, FAKE + 2)
+    assert _status(lambda: upd(spec, hp, shard, grads, 0, 8)) == ps.PS_EALIGN
+    hp = ps.ps_adamw_t(1e-4, 0.9, 0.999, 1e-8, 0.01, 1, 0.0, 0.5, FAKE)
+    assert _status(lambda: upd(spec, hp, shard, grads, 0, 8)) == ps.PS_EINVAL         # both given
+    hp = ps.ps_adamw_t(1e-4, 0.9, 0.999, 1e-8, 0.01, 1, 0.0, 0.0, FAKE)
+    upd(spec, hp, shard, grads, 0, 0)                                                 # valid, empty
+    cc = ps.ps_step_clip_coef
+    assert _status(lambda: cc(0, 0, 1.0, FAKE)) == ps.PS_EINVAL
+    assert _status(lambda: cc(FAKE, 0, 1.0, 0)) == ps.PS_EINVAL
+    assert _status(lambda: cc(FAKE + 4, 0, 1.0, FAKE)) == ps.PS_EALIGN
+    assert _status(lambda: cc(FAKE, FAKE + 4, 1.0, FAKE)) == ps.PS_EALIGN
+    assert _status(lambda: cc(FAKE, 0, 1.0, FAKE + 2)) == ps.PS_EALIGN
