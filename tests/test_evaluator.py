@@ -211,3 +211,20 @@ def test_composed_cost_per_device_and_per_group(golden):
     with pytest.raises(ps.PsError) as e:
         ps.ps_compose_cost(spec, 3)            # 70e9 is not a multiple of 3
     assert e.value.status == ps.PS_ERANGE
+
+
+def test_corollary1_on_the_library():
+    """Corollary 1 on the evaluator's integer fields, for several N and sizes: sharding Omega
+    leaves communication alone and saves (N-1)/N of 12 psi; sharding G halves gradient
+    synchronisation; S* for Theta adds exactly two All-Gathers of |Theta|."""
+    rnd = random.Random(11)
+    for _ in range(50):
+        N = rnd.choice([2, 3, 4, 6, 8, 16, 64, 512])
+        P = N * rnd.randrange(1, 10 ** 9)
+        dp, z1, z2, z3 = (ps.ps_cost_eval(ps.ps_spec_preset(k, N, 0, P)) for k in ("dp", "zero1", "zero2", "zero3"))
+        total = lambda c: c.comm_grad_sync_xN + c.comm_param_gather_xN
+        assert total(z1) == total(dp)
+        assert (dp.peak_total - z1.peak_total) * N == 12 * P * (N - 1)
+        assert 2 * total(z2) == total(z1)
+        assert total(z3) - total(z2) == 2 * (N - 1) * 2 * P
+        assert z3.peak_total * N == 16 * P and z2.peak_total * N == 2 * P * N + 14 * P
