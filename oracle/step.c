@@ -5,7 +5,7 @@
  * data-parallel job computes on the *unsharded* flat state: sum the N
  * per-device gradient contributions in a fixed order, take the mean, and apply
  * mixed-precision Adam with decoupled weight decay to the FP32 master weights
- * and moments, then round the new weights to bf16.  Only tests, the smoke
+ * and moments, then round the new weights to 16 bits (bf16 or binary16).  Only tests, the smoke
  * check and the benchmark's CPU-baseline leg may call into this file.  It
  * shares no code, header, table or helper with the GPU library.
  *
@@ -73,6 +73,62 @@ void oracle_bf16_rne_array(const float *x, uint16_t *out, uint64_t n)
         out[i] = oracle_bf16_rne(x[i]);
 }
 
+/* IEEE binary16 (1 sign, 5 exponent, 10 fraction bits; the paper's FP16 of
+ * Table 1) to binary32: exact for every pattern, subnormals included. */
+static float widen_f16(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    uint32_t ex = (h >> 10) & 0x1fu, frac = h & 0x3ffu;
+    uint32_t u;
+    float f;
+    if (ex == 0) { /* zero or subnormal: frac * 2^-24 */
+        f = ldexpf((float)frac, -24);
+        memcpy(&u, &f, sizeof u);
+        u |= sign;
+    } else if (ex == 31) { /* infinity or NaN: payload moved to the top of the fraction */
+        u = sign | 0x7f800000u | (frac << 13);
+    } else { /* normal: rebias 15 -> 127 */
+        u = sign | ((ex + 112u) << 23) | (frac << 13);
+    }
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+float oracle_widen_f16(uint16_t h) { return widen_f16(h); }
+
+/* Round a binary32 to the nearest binary16, ties to the even fraction.  Values
+ * of magnitude >= 65520 (the largest binary16 plus half a unit in its last
+ * place) go to infinity, magnitudes below 2^-14 land on the subnormal grid of
+ * spacing 2^-24 (or on zero, or on 2^-14 itself), -0 keeps its sign, any NaN
+ * becomes the quiet NaN 0x7E00 with the input's sign. */
+uint16_t oracle_f16_rne(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, sizeof u);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    uint32_t a = u & 0x7fffffffu;
+    if (a > 0x7f800000u)
+        return (uint16_t)(sign | 0x7e00u);
+    if (a >= 0x477ff000u) /* 65520.0f and beyond, infinity included */
+        return (uint16_t)(sign | 0x7c00u);
+    if (a < 0x38800000u) { /* below 2^-14: count units of 2^-24, nearest, ties to even */
+        float mag;
+        memcpy(&mag, &a, sizeof mag);
+        float units = nearbyintf(mag * 16777216.0f); /* the product is exact */
+        return (uint16_t)(sign | (uint16_t)units);
+    }
+    uint32_t keep_lsb = (a >> 13) & 1u;
+    a += 0xfffu + keep_lsb;                         /* may carry into the exponent: intended */
+    return (uint16_t)(sign | (uint16_t)((a >> 13) - (112u << 10)));
+}
+
+/* The same cast over an array (used by the exhaustive cast checks). */
+void oracle_f16_rne_array(const float *x, uint16_t *out, uint64_t n)
+{
+    for (uint64_t i = 0; i < n; ++i)
+        out[i] = oracle_f16_rne(x[i]);
+}
+
 /* ---- scalars ---- */
 
 typedef struct {
@@ -113,11 +169,15 @@ void oracle_derive_scalars(double lr, double beta1, double beta2, double eps,
 /* ---- gradient contributions ---- */
 
 /* Contribution r's element e, widened to binary32.  All contributions carry
- * one data type (Theorem 4: identical data types). */
+ * one data type (Theorem 4: identical data types); dtype 0 = bf16, 1 = binary32,
+ * 2 = binary16 (in the functions below the parameter keeps its first name,
+ * is_f32, from when there were two). */
 static float contribution(const void *const *g, int is_f32, uint32_t r, uint64_t e)
 {
-    if (is_f32)
+    if (is_f32 == 1)
         return ((const float *)g[r])[e];
+    if (is_f32 == 2)
+        return widen_f16(((const uint16_t *)g[r])[e]);
     return widen_bf16(((const uint16_t *)g[r])[e]);
 }
 
@@ -181,10 +241,11 @@ double oracle_clip_coef(double sumsq_local, double sumsq_others, double max_norm
 /* ---- the step, binary32 (the parity target) ---- */
 
 /* One step on elements [lo, hi) of the full-length arrays.  theta, m, v are
- * updated in place; p receives the bf16 image of the new theta. */
+ * updated in place; p receives the 16-bit image of the new theta: bf16, or
+ * binary16 when p_f16 != 0. */
 void oracle_step_f32(const void *const *g, uint32_t n_contrib, int is_f32,
                      const oracle_scalars *s, float *theta, float *m, float *v,
-                     uint16_t *p, uint64_t lo, uint64_t hi)
+                     uint16_t *p, int p_f16, uint64_t lo, uint64_t hi)
 {
     for (uint64_t e = lo; e < hi; ++e) {
         float acc = contribution(g, is_f32, 0, e);
@@ -201,7 +262,7 @@ void oracle_step_f32(const void *const *g, uint32_t n_contrib, int is_f32,
         m[e] = m1;
         v[e] = v1;
         theta[e] = t1;
-        p[e] = oracle_bf16_rne(t1);
+        p[e] = p_f16 ? oracle_f16_rne(t1) : oracle_bf16_rne(t1);
     }
 }
 

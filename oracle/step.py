@@ -43,6 +43,12 @@ def lib():
         L.oracle_bf16_rne.argtypes = [C.c_float]
         L.oracle_bf16_rne_array.restype = None
         L.oracle_bf16_rne_array.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
+        L.oracle_widen_f16.restype = C.c_float
+        L.oracle_widen_f16.argtypes = [C.c_uint16]
+        L.oracle_f16_rne.restype = C.c_uint16
+        L.oracle_f16_rne.argtypes = [C.c_float]
+        L.oracle_f16_rne_array.restype = None
+        L.oracle_f16_rne_array.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
         L.oracle_derive_scalars.restype = None
         L.oracle_derive_scalars.argtypes = [C.c_double] * 5 + [C.c_uint64, C.c_uint32,
                                                                C.c_double, C.c_double,
@@ -65,7 +71,7 @@ def lib():
         L.oracle_clip_coef.argtypes = [C.c_double] * 3
         L.oracle_step_f32.restype = None
         L.oracle_step_f32.argtypes = [pp, C.c_uint32, C.c_int, C.POINTER(Scalars),
-                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                       C.c_uint64, C.c_uint64]
         L.oracle_step_f64.restype = None
         L.oracle_step_f64.argtypes = ([pp, C.c_uint32, C.c_int] + [C.c_double] * 5 +
@@ -76,18 +82,20 @@ def lib():
 
 
 def _contrib_ptrs(grads):
-    """grads: list of equally long 1-D arrays, all uint16 (bf16 bits) or all float32."""
+    """grads: list of equally long 1-D arrays, all uint16 (bf16 bits), all float32 or all
+    float16.  Returns (pointer array, count, dtype code 0/1/2, length)."""
     if not grads:
         raise ValueError("need at least one contribution")
     dt = grads[0].dtype
-    if dt not in (np.dtype(np.uint16), np.dtype(np.float32)):
-        raise TypeError("contributions must be uint16 (bf16 bits) or float32")
+    codes = {np.dtype(np.uint16): 0, np.dtype(np.float32): 1, np.dtype(np.float16): 2}
+    if dt not in codes:
+        raise TypeError("contributions must be uint16 (bf16 bits), float32 or float16")
     n = grads[0].shape[0]
     for g in grads:
         if g.dtype != dt or g.ndim != 1 or g.shape[0] != n or not g.flags.c_contiguous:
             raise ValueError("contributions must share dtype/length and be contiguous")
     arr = (C.c_void_p * len(grads))(*[g.ctypes.data for g in grads])
-    return arr, len(grads), int(dt == np.dtype(np.float32)), n
+    return arr, len(grads), codes[dt], n
 
 
 def _check(a, dtype, n):
@@ -116,6 +124,18 @@ def bf16_rne_bits(u32):
     u32 = np.ascontiguousarray(u32, dtype=np.uint32)
     out = np.empty(u32.shape[0], dtype=np.uint16)
     lib().oracle_bf16_rne_array(u32.ctypes.data, out.ctypes.data, u32.shape[0])
+    return out
+
+
+def widen_f16(bits):
+    return lib().oracle_widen_f16(int(bits))
+
+
+def f16_rne_bits(u32):
+    """Cast arbitrary binary32 bit patterns (uint32 array) -> binary16 bit patterns (uint16)."""
+    u32 = np.ascontiguousarray(u32, dtype=np.uint32)
+    out = np.empty(u32.shape[0], dtype=np.uint16)
+    lib().oracle_f16_rne_array(u32.ctypes.data, out.ctypes.data, u32.shape[0])
     return out
 
 
@@ -149,16 +169,18 @@ def clip_coef(sumsq_local, sumsq_others, max_norm):
 
 
 def step_f32(grads, scalars, theta, m, v, p, lo=0, hi=None):
-    """In-place binary32 step on [lo, hi) of the full-length arrays."""
+    """In-place binary32 step on [lo, hi) of the full-length arrays.  p is uint16 (receives
+    bf16 bit patterns) or float16 (receives the binary16 image)."""
     ptrs, n_c, is_f32, n = _contrib_ptrs(grads)
     hi = n if hi is None else hi
     for a in (theta, m, v):
         _check(a, np.float32, n)
-    _check(p, np.uint16, n)
+    p_f16 = p.dtype == np.dtype(np.float16)
+    _check(p, np.float16 if p_f16 else np.uint16, n)
     if not (0 <= lo <= hi <= n):
         raise ValueError("bad range")
     lib().oracle_step_f32(ptrs, n_c, is_f32, C.byref(scalars), theta.ctypes.data,
-                          m.ctypes.data, v.ctypes.data, p.ctypes.data, lo, hi)
+                          m.ctypes.data, v.ctypes.data, p.ctypes.data, int(p_f16), lo, hi)
 
 
 def step_f64(grads, lr, beta1, beta2, eps, weight_decay, t, theta, m, v,

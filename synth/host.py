@@ -28,7 +28,9 @@ def moments(n, seed, warm):
 
 def gradient(n, seed, step, replica, dtype="bf16", std=1e-3, outlier_frac=0.0,
              outlier_mult=1.0, student_t_dof=0):
-    """One device's gradient contribution for one step, as uint16 bf16 bits or float32."""
+    """One device's gradient contribution for one step, as uint16 bf16 bits, float32, or
+    float16 (dtype "f16": rounded to nearest, values past 65504 saturate to infinity as
+    they would in an unscaled FP16 backward pass)."""
     r = rng_for(seed, 4, step, replica)
     if student_t_dof > 0:
         z = r.standard_normal(n)
@@ -41,6 +43,9 @@ def gradient(n, seed, step, replica, dtype="bf16", std=1e-3, outlier_frac=0.0,
         x = np.where(mask, x * np.float32(outlier_mult), x).astype(np.float32)
     if dtype == "bf16":
         return _bf16_bits(x)
+    if dtype == "f16":
+        with np.errstate(over="ignore"):
+            return np.ascontiguousarray(x.astype(np.float16))
     return np.ascontiguousarray(x, dtype=np.float32)
 
 

@@ -27,7 +27,7 @@ MUTANTS = [
     ("a contribution skipped", "for (uint32_t r = 1; r < n_contrib; ++r)", "for (uint32_t r = 2; r < n_contrib; ++r)"),
     ("cast truncates", "u += 0x7fffu + keep_lsb;", "u += 0;"),
     ("cast rounds half up", "u += 0x7fffu + keep_lsb;", "u += 0x8000u;"),
-    ("cast of the old weight", "p[e] = oracle_bf16_rne(t1);", "p[e] = oracle_bf16_rne(th);"),
+    ("cast of the old weight", "oracle_f16_rne(t1) : oracle_bf16_rne(t1);", "oracle_f16_rne(th) : oracle_bf16_rne(th);"),
     ("clip coefficient ignored", "gm = gm * s->cc;", "gm = gm;"),
     ("accumulation forgets the running total", "accum[e] = overwrite ? acc : accum[e] + acc;", "accum[e] = acc;"),
     ("difference taken as a sum", "double d = x - y;", "double d = x + y;"),

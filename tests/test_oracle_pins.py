@@ -98,6 +98,80 @@ def test_bf16_rne_specials():
     assert f(0x00000001) == 0x0000 and f(0x00008001) == 0x0001      # subnormals
 
 
+def _f16_value_f64(bits):
+    """Value of a binary16 pattern from the format's definition: 1 sign, 5 exponent, 10
+    fraction bits, bias 15, subnormals at exponent field 0."""
+    bits = np.asarray(bits, dtype=np.int64)
+    s = np.where(bits & 0x8000, -1.0, 1.0)
+    e = (bits >> 10) & 0x1f
+    f = (bits & 0x3ff).astype(np.float64)
+    normal = np.ldexp(1.0 + f / 1024.0, (e - 15).astype(np.int64))
+    sub = np.ldexp(f / 1024.0, -14)
+    return s * np.where(e == 0, sub, normal)
+
+
+def test_widen_f16_exhaustive():
+    bits = np.arange(65536, dtype=np.int64)
+    finite = ((bits >> 10) & 0x1f) != 0x1f
+    want = _f16_value_f64(bits[finite])
+    got = np.array([orc.widen_f16(int(b)) for b in bits[finite]], dtype=np.float64)
+    assert np.array_equal(got, want)
+    assert np.array_equal(np.signbit(got), (bits[finite] & 0x8000) != 0)
+    assert orc.widen_f16(0x7c00) == np.inf and orc.widen_f16(0xfc00) == -np.inf
+    assert np.isnan(orc.widen_f16(0x7c01)) and np.isnan(orc.widen_f16(0xfe00))
+    # the library's own widening agrees on every non-NaN pattern
+    lib = np.arange(65536, dtype=np.uint16).view(np.float16).astype(np.float64)
+    assert np.array_equal(got, lib[finite])
+
+
+def _nearest_even_f16(u32):
+    """Independent definition of the binary16 cast for finite inputs: the finite binary16
+    magnitudes are listed in order (pattern = rank), x is bracketed by two of them, the
+    nearer by exact comparison in binary64 wins, a tie goes to the even pattern; the
+    value one step past the largest finite one (65536, were the exponent range to go on)
+    stands for infinity."""
+    u32 = np.asarray(u32, dtype=np.uint32)
+    ax = np.abs(u32.view(np.float32).astype(np.float64))
+    sign = (u32 >> 31).astype(np.int64)
+    grid = np.concatenate([_f16_value_f64(np.arange(0x7c00)), [65536.0]])   # rank 0x7c00 = infinity
+    hi = np.minimum(np.searchsorted(grid, ax, side="left"), 0x7c00)         # first grid value >= |x|
+    lo = np.maximum(hi - 1, 0)
+    dlo, dhi = ax - grid[lo], grid[hi] - ax
+    pick_hi = (hi == lo) | (dhi < dlo) | ((dhi == dlo) & ((lo & 1) == 1))
+    pick_hi |= ax >= 65536.0
+    out = np.where(pick_hi, hi, lo) | (sign << 15)
+    return out.astype(np.uint16)
+
+
+def test_f16_rne_against_definition():
+    h = np.arange(0x7c00, dtype=np.int64)                     # every finite magnitude
+    v = _f16_value_f64(h)
+    nxt = np.concatenate([v[1:], [65536.0]])
+    tie = ((v + nxt) / 2).astype(np.float32)                  # exact midpoints (12 significant bits)
+    cases = [v.astype(np.float32), tie, np.nextafter(tie, np.float32(0)), np.nextafter(tie, np.float32(np.inf))]
+    mag = np.concatenate(cases).view(np.uint32)
+    rng = np.random.default_rng(17)
+    extra = rng.integers(0, 2 ** 32, size=1 << 20, dtype=np.uint64).astype(np.uint32)
+    extra = extra[((extra >> 23) & 0xff) != 0xff]
+    u = np.concatenate([mag, mag | np.uint32(0x80000000), extra])
+    assert np.array_equal(orc.f16_rne_bits(u), _nearest_even_f16(u))
+
+
+def test_f16_rne_specials():
+    f = lambda x: orc.f16_rne_bits(np.array([x], dtype=np.uint32))[0]
+    assert f(0x7f800000) == 0x7c00 and f(0xff800000) == 0xfc00      # infinities stay
+    assert f(0x80000000) == 0x8000 and f(0x00000000) == 0x0000      # signed zeros
+    assert f(0x477fe000) == 0x7bff                                  # 65504, the largest finite value
+    assert f(0x477fefff) == 0x7bff and f(0x477ff000) == 0x7c00      # just under / at 65520: the tie goes up
+    assert f(0x7f7fffff) == 0x7c00                                  # FLT_MAX overflows
+    assert f(0x7fc00001) == 0x7e00 and f(0xffc00001) == 0xfe00      # NaN: quiet, sign kept
+    assert f(0x7f800001) == 0x7e00                                  # signalling NaN
+    assert f(0x33800000) == 0x0001 and f(0x33000000) == 0x0000      # 2^-24 -> 1 unit; 2^-25 ties to even 0
+    assert f(0x33000001) == 0x0001 and f(0x33c00000) == 0x0002      # just over half; 1.5 units ties to even 2
+    assert f(0x387fc000) == 0x03ff and f(0x387fe000) == 0x0400      # largest subnormal; tie rolls into 2^-14
+    assert f(0x3f801000) == 0x3c00 and f(0x3f803000) == 0x3c02      # ties to even, both ways, at 1.0
+
+
 # --------------------------------------------------------------------------
 # gradient reduction (gradient integrity, Theorem 3)
 # --------------------------------------------------------------------------
@@ -107,6 +181,8 @@ def _np_fixed_order_sum(grads):
     def widen(g):
         if g.dtype == np.uint16:
             return (g.astype(np.uint32) << 16).view(np.float32)
+        if g.dtype == np.float16:
+            return g.astype(np.float32)          # the library's exact widening
         return g
     acc = widen(grads[0]).copy()
     for g in grads[1:]:
@@ -114,7 +190,7 @@ def _np_fixed_order_sum(grads):
     return acc
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 @pytest.mark.parametrize("N", [1, 2, 3, 6, 8])
 def test_reduce_is_the_fixed_order_sum(dtype, N):
     n = 4099
@@ -469,18 +545,57 @@ def load_tol():
     return load_golden()["grad_check_rel_tol"]
 
 
-def test_bf16_rne_exhaustive_against_library_conversion():
-    """All 2^32 binary32 patterns: the oracle's cast against the library's float32 ->
-    bfloat16 conversion (round to nearest even).  NaNs are compared as a class (the
-    oracle canonicalises them to 0x7FC0 with the sign, the library keeps payload bits)."""
+def _exhaustive_cast_check(oracle_cast, torch_dtype, quiet_nan, exp_mask):
+    """All 2^32 binary32 patterns in chunks (four at a time; the C loop and the library
+    conversion both release the interpreter lock): oracle cast == library conversion on
+    every non-NaN input; NaNs compared as a class (canonical quiet NaN with the sign)."""
+    from concurrent.futures import ThreadPoolExecutor
     chunk = 1 << 26
-    torch.set_num_threads(max(1, min(8, torch.get_num_threads())))
-    for lo in range(0, 1 << 32, chunk):
+
+    def one(lo):
         u = np.arange(lo, lo + chunk, dtype=np.uint32)
-        got = orc.bf16_rne_bits(u)
-        lib = torch.from_numpy(u.view(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        got = oracle_cast(u)
+        lib = torch.from_numpy(u.view(np.float32)).to(torch_dtype).view(torch.int16).numpy().view(np.uint16)
         nan = (u & 0x7fffffff) > 0x7f800000
         assert np.array_equal(got[~nan], lib[~nan]), hex(lo)
         if nan.any():
-            assert ((got[nan] & 0x7fff) == 0x7fc0).all() and ((lib[nan] & 0x7f80) == 0x7f80).all()
+            assert ((got[nan] & 0x7fff) == quiet_nan).all() and ((lib[nan] & exp_mask) == exp_mask).all()
             assert np.array_equal(got[nan] >> 15, (u[nan] >> 31).astype(np.uint16))
+        return True
+
+    torch.set_num_threads(2)
+    with ThreadPoolExecutor(max_workers=4) as pool:
+        assert all(pool.map(one, range(0, 1 << 32, chunk)))
+
+
+def test_bf16_rne_exhaustive_against_library_conversion():
+    """The oracle's bf16 cast against the library's float32 -> bfloat16 conversion (round
+    to nearest even) on all 2^32 binary32 patterns."""
+    _exhaustive_cast_check(orc.bf16_rne_bits, torch.bfloat16, 0x7fc0, 0x7f80)
+
+
+def test_f16_rne_exhaustive_against_library_conversion():
+    """The oracle's binary16 cast against the library's float32 -> float16 conversion on
+    all 2^32 binary32 patterns."""
+    _exhaustive_cast_check(orc.f16_rne_bits, torch.float16, 0x7e00, 0x7c00)
+
+
+def test_step_with_binary16_gradients_and_parameters():
+    """The FP16 flavour of the step (Table 1: FP16 parameters and gradients, with a loss
+    scale riding on grad_scale): same arithmetic as with bf16 once the contributions are
+    widened, and the 16-bit image is the binary16 cast of the new master weight."""
+    n, N, scale = 3001, 4, 1024.0
+    g16 = [gen.gradient(n, 23, 0, r, "f16", std=1e-3 * scale, outlier_frac=0.01, outlier_mult=100.0)
+           for r in range(N)]
+    assert all(np.isinf(g).sum() == 0 for g in g16) and any((np.abs(g) < 6e-5).any() for g in g16)
+    g32 = [g.astype(np.float32) for g in g16]                 # exact widening by the library
+    s = orc.derive_scalars(t=3, n_devices=N, grad_scale=1.0 / (N * scale), **HP)
+    a = [gen.master(n, 23), *gen.moments(n, 23, True), np.zeros(n, np.float16)]
+    b = [x.copy() for x in a[:3]] + [np.zeros(n, np.uint16)]
+    orc.step_f32(g16, s, *a)
+    orc.step_f32(g32, s, *b)
+    for x, y in zip(a[:3], b[:3]):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+    with np.errstate(over="ignore"):
+        assert np.array_equal(a[3].view(np.uint16), a[0].astype(np.float16).view(np.uint16))
+    assert np.array_equal(b[3], orc.bf16_rne_bits(b[0].view(np.uint32)))
