@@ -24,9 +24,10 @@ __all__ = [
     "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
     "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum",
     "ps_select_strategy", "ps_compose_index", "ps_compose_cost", "ps_step_update_offloaded",
-    "ps_step_clip_coef", "EXPORTED_SYMBOLS",
+    "ps_step_clip_coef", "EXPORTED_SYMBOLS", "ABI_VERSION",
 ]
 
+ABI_VERSION = 2   # PS_ABI_VERSION of include/ps_step.h this binding mirrors
 PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
 PS_BF16, PS_F32 = 0, 1
 PS_COPY_KERNEL, PS_COPY_MEMCPY = 0, 1
@@ -182,8 +183,9 @@ def library():
                                          C.c_void_p, C.c_uint64, C.c_void_p]
         L.ps_probe_copy.restype = C.c_int
         L.ps_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
-        if L.ps_abi_version() != 2:
-            raise ImportError("libps_step.so has ABI %d, binding wants 2" % L.ps_abi_version())
+        if L.ps_abi_version() != ABI_VERSION:
+            raise ImportError("libps_step.so has ABI %d, binding wants %d" %
+                              (L.ps_abi_version(), ABI_VERSION))
         _lib = L
     return _lib
 

@@ -16,7 +16,7 @@ typedef struct { float gs, cc, b1, omb1, b2, omb2, ep, step, isb2, lw; } oracle_
 void oracle_derive_scalars(double, double, double, double, double, uint64_t, uint32_t, double, double,
                            oracle_scalars *);
 void oracle_step_f32(const void *const *, uint32_t, int, const oracle_scalars *, float *, float *,
-                     float *, uint16_t *, uint64_t, uint64_t);
+                     float *, uint16_t *, int, uint64_t, uint64_t);
 double oracle_mean_sumsq(const void *const *, uint32_t, int, float, float *, uint64_t, uint64_t);
 uint16_t oracle_bf16_rne(float);
 }
@@ -62,7 +62,7 @@ int main()
     for (uint32_t r = 0; r < N; ++r) gp[r] = g[r].data();
     oracle_scalars s;
     oracle_derive_scalars(3e-4, 0.9, 0.999, 1e-8, 0.1, 1000, N, 0.0, 0.0, &s);
-    oracle_step_f32(gp, N, 1, &s, oth.data(), om.data(), ov.data(), op.data(), 0, valid);
+    oracle_step_f32(gp, N, 1, &s, oth.data(), om.data(), ov.data(), op.data(), 0, 0, valid);
     std::vector<float> omean(n, -1.0f);
     const double oss = oracle_mean_sumsq(gp, N, 1, s.gs, omean.data(), 0, valid);
 

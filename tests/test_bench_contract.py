@@ -17,6 +17,14 @@ def test_more_than_one_gpu_is_refused():
     assert p.returncode == 2 and "ONE GPU" in p.stderr and p.stdout.strip() == ""
 
 
+def test_build_entry_point_compiles_and_imports():
+    """__graft_entry__.build() as a fresh process runs it: compiles the library for gfx950,
+    the oracle and the native driver, imports the package and checks the ABI it loaded."""
+    p = subprocess.run([sys.executable, "-c", "import __graft_entry__ as g; g.build(); print('built')"],
+                       cwd=ROOT, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=600)
+    assert p.returncode == 0 and p.stdout.strip().endswith("built"), p.stderr[-2000:]
+
+
 def test_measured_traffic_matches_the_algorithmic_bytes_or_is_absent():
     sys.path.insert(0, ROOT)
     import bench

@@ -122,7 +122,7 @@ def test_header_symbols_are_exported_and_bound():
     L = ps.library()
     for name in declared:
         assert getattr(L, name) is not None
-    assert ps.ps_abi_version() == 2
+    assert ps.ps_abi_version() == ps.ABI_VERSION == int(re.search(r'#define PS_ABI_VERSION (\d+)u', text).group(1))
     assert ps.ps_status_string(ps.PS_EALIGN).startswith("pointer")
 
 

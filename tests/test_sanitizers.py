@@ -54,7 +54,8 @@ int main(void)
     oracle_scalars s;
     for (uint64_t t = 1; t <= 3; ++t) {
         oracle_derive_scalars(1e-4, 0.9, 0.999, 1e-8, 0.01, t, N, 0.0, 0.0, &s);
-        oracle_step_f32(gp, N, 0, &s, th, m, v, p, 0, n);
+        oracle_step_f32(gp, N, 0, &s, th, m, v, p, 0, 0, n);
+        oracle_step_f32(gp, N, 2, &s, th, m, v, p, 1, 0, n);   /* the same bits read as binary16 */
     }
     oracle_accumulate(gp, N, 0, acc, 1, 0, n);
     oracle_accumulate(gp, N, 0, acc, 0, 3, n - 3);
@@ -65,6 +66,7 @@ int main(void)
     oracle_step_f64(gp, N, 0, 1e-4, 0.9, 0.999, 1e-8, 0.01, 4, 0.0, 0.0, th, m, v, t64, m64, v64, 0, n);
     uint16_t edge[6]; float fe[6] = {3.4e38f, -3.4e38f, 1e-45f, -0.0f, 1.0f, 65504.0f};
     oracle_bf16_rne_array(fe, edge, 6);
+    oracle_f16_rne_array(fe, edge, 6);
     printf("oracle ok %g %g %llu %g %u\n", ss, out[0], (unsigned long long)c, t64[7], edge[0]);
     for (int r = 0; r < N; ++r) free(g[r]);
     free(th); free(m); free(v); free(acc); free(p); free(t64); free(m64); free(v64);
