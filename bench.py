@@ -30,7 +30,7 @@ def log(msg):
 
 def bytes_per_elem(w, clip=False):
     """Algorithmic bytes per element of one step: every byte touched once."""
-    g = 2 if w.grad_dtype == "bf16" else 4
+    g = 4 if w.grad_dtype == "f32" else 2
     if clip:   # phase 1: N reads + fp32 spill; phase 2: spill + state in, state + bf16 out
         return g * w.n_devices + 4 + 4 + 12 + 14
     if w.strategy == "zero1":          # one all-reduced gradient
@@ -48,7 +48,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="70b_zero3",
                     choices=["tiny", "gpt2s", "7b_zero2", "70b_zero3", "13b_clip", "7b_zero1",
-                             "7b_accum4", "7b_verify", "7b_offload"])
+                             "7b_accum4", "7b_verify", "7b_offload", "7b_zero2_f16"])
     ap.add_argument("--pool-elems", type=int, default=1 << 21,
                     help="elements per contribution of the resident, repeating bucket source")
     ap.add_argument("--copy-engine", choices=["kernel", "memcpy"], default="kernel")
@@ -90,9 +90,10 @@ def main():
     spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi, align_elems=w.align_elems)
     cost = ps.ps_cost_eval(spec)
     assert cost.shard_len == n
-    dt = ps.PS_BF16 if w.grad_dtype == "bf16" else ps.PS_F32
-    esz = 2 if w.grad_dtype == "bf16" else 4
-    tdt = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
+    dt = {"bf16": ps.PS_BF16, "f16": ps.PS_F16, "f32": ps.PS_F32}[w.grad_dtype]
+    esz = 4 if w.grad_dtype == "f32" else 2
+    tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[w.grad_dtype]
+    pdt, ptd = ((ps.PS_F16, torch.float16) if w.param_dtype == "f16" else (ps.PS_BF16, torch.bfloat16))
     log("device %s (%s), %d CUs, %.1f GB free" % (info.name.decode(), info.arch.decode(),
                                                   info.compute_units, info.free_bytes / 1e9))
     log("workload %s: shard of %d elements, N=%d, %s gradients" % (w.name, n, N, w.grad_dtype))
@@ -100,15 +101,17 @@ def main():
     t_setup = time.time()
     master, m, v = dgen.workload_state(w)
     out_len = cost.psi_padded if spec.theta == ps.PS_R else n
-    out = torch.zeros(out_len, dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros(out_len, dtype=ptd, device="cuda")
     shard = ps.ps_shard_t(master.data_ptr(), m.data_ptr(), v.data_ptr(), out.data_ptr(), n,
-                          cost.valid_len)
+                          cost.valid_len, pdt, 0)
     compute = torch.cuda.Stream()
     copy = torch.cuda.Stream()
     bucketed = w.bucket_elems > 0
     step_no = [w.first_step]
 
     def hp(clip_coef=0.0, grad_scale=0.0):
+        if grad_scale == 0.0 and w.loss_scale != 1.0:       # the mean and the loss scale in one factor
+            grad_scale = 1.0 / (N * w.loss_scale)
         return ps.ps_adamw_t(w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, step_no[0],
                              grad_scale, clip_coef)
 
@@ -270,7 +273,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "psi": w.psi, "n_devices": N, "shard_index": w.shard_index,
-                   "shard_elems": n, "grad_dtype": w.grad_dtype, "strategy": w.strategy,
+                   "shard_elems": n, "grad_dtype": w.grad_dtype, "param_dtype": w.param_dtype, "strategy": w.strategy,
                    "bucket_elems": (B if bucketed else 0), "launches_per_step": launches_per_step,
                    "bucket_source": ("resident pool of %d elements per contribution, repeating; "
                                      "copy engine %s, schedule %s" %
@@ -449,14 +452,15 @@ def cpu_baseline(w, bpe, seconds=15.0):
 
     cores = min(16, os.cpu_count() or 1)
     sample = min(w.shard_len, 1 << 25)
-    grads = [gen.gradient(sample, w.seed, w.first_step, r, w.grad_dtype, w.grad_std,
+    grads = [gen.gradient(sample, w.seed, w.first_step, r, w.grad_dtype, w.grad_std * w.loss_scale,
                           w.outlier_frac, w.outlier_mult, w.student_t_dof)
              for r in range(w.n_devices)]
     th = gen.master(sample, w.seed)
     m, v = gen.moments(sample, w.seed, True)
-    p = np.zeros(sample, np.uint16)
+    p = np.zeros(sample, np.float16 if w.param_dtype == "f16" else np.uint16)
     s = orc.derive_scalars(w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, w.first_step,
-                           w.n_devices)
+                           w.n_devices, grad_scale=(1.0 / (w.n_devices * w.loss_scale)
+                                                    if w.loss_scale != 1.0 else 0.0))
     bounds = [sample * k // cores for k in range(cores + 1)]
 
     def one_pass():

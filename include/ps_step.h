@@ -37,14 +37,17 @@
 extern "C" {
 #endif
 
-#define PS_ABI_VERSION 2u
+#define PS_ABI_VERSION 3u
 /* Largest number of gradient contributions one call can reduce. */
 #define PS_MAX_CONTRIB 16u
 
 /* Placement modes (Definition 1, Eq. 1-5). */
 enum { PS_R = 0, PS_S = 1, PS_SG = 2 /* S*: sharded with gather */, PS_M = 3, PS_O = 4 };
-/* Element type of the gradient contributions. */
-enum { PS_BF16 = 0, PS_F32 = 1 };
+/* Element types.  Gradient contributions: any of the three.  Parameters (the
+ * 16-bit image of the master weights): PS_BF16 or PS_F16, the "FP16" of the
+ * paper's Table 1 and Remark 1 being either 2-byte format.  PS_F16 is IEEE
+ * binary16; with it a loss scale usually rides on ps_adamw_t.grad_scale. */
+enum { PS_BF16 = 0, PS_F32 = 1, PS_F16 = 2 };
 
 typedef enum {
     PS_OK = 0,
@@ -110,12 +113,16 @@ typedef struct ps_shard_t {
     float *master;     /* DEVICE, len floats: FP32 master weights, updated in place   */
     float *m;          /* DEVICE, len floats: Adam first moment, updated in place     */
     float *v;          /* DEVICE, len floats: Adam second moment, updated in place    */
-    void *gather_out;  /* DEVICE, bf16.  pi_Theta = S*: the persistent parameter shard
-                          (len elements) that the All-Gather reads.  pi_Theta = R: the
-                          full replicated parameter buffer (psi_padded elements); the
-                          library writes this shard's slice at shard_offset.          */
+    void *gather_out;  /* DEVICE, 16-bit elements of type param_dtype.  pi_Theta = S*:
+                          the persistent parameter shard (len elements) that the
+                          All-Gather reads.  pi_Theta = R: the full replicated parameter
+                          buffer (psi_padded elements); the library writes this shard's
+                          slice at shard_offset.                                      */
     uint64_t len;      /* shard length n = psi_padded / N, in elements                */
     uint64_t valid_len;/* elements [valid_len, len) are padding and are never written */
+    int32_t param_dtype; /* PS_BF16 (0, the default of a zeroed field) or PS_F16.  16-bit
+                          gradient contributions must be of the same type            */
+    int32_t reserved;  /* must be 0                                                   */
 } ps_shard_t;
 
 /* The N gradient contributions for this shard (the inputs of the Reduce-Scatter
@@ -125,7 +132,8 @@ typedef struct ps_grads_t {
                                    is element 0 of device r's contribution for the range
                                    being processed (the shard, or the current bucket)  */
     uint32_t n_contrib;         /* = n_devices, or 1 for an already reduced gradient   */
-    int32_t dtype;              /* PS_BF16 or PS_F32, one type for all (Theorem 4)     */
+    int32_t dtype;              /* PS_BF16, PS_F16 or PS_F32, one type for all
+                                   (Theorem 4)                                         */
 } ps_grads_t;
 
 /* How ps_step_update_bucketed moves a bucket into its staging slot. */
@@ -180,21 +188,22 @@ typedef struct ps_bucket_plan_t {
 } ps_bucket_plan_t;
 
 /* Offloaded optimizer state (Table 2, ZeRO-Offload: Theta and Omega in mode O,
- * G sharded): master, m, v and the bf16 parameters of this shard live in pinned
+ * G sharded): master, m, v and the 16-bit parameters of this shard live in pinned
  * HOST memory and stream through the device in buckets. */
 typedef struct ps_offload_plan_t {
     float *host_master;     /* pinned HOST, len floats, updated in place                 */
     float *host_m;          /* pinned HOST, len floats                                   */
     float *host_v;          /* pinned HOST, len floats                                   */
-    void *host_param_out;   /* pinned HOST, len bf16: the updated 16-bit parameters      */
+    void *host_param_out;   /* pinned HOST, len 16-bit elements of type param_dtype:
+                               the updated parameters                                    */
     uint64_t len;           /* shard length n = psi_padded / N                           */
     uint64_t valid_len;     /* elements [valid_len, len) are never read or written       */
     uint64_t bucket_elems;  /* multiple of 8                                             */
     uint32_t n_slots;       /* 2 or 3 DEVICE slots; 3 lets upload, update and download
                                of neighbouring buckets run at the same time             */
-    uint32_t reserved;      /* must be 0                                                 */
+    int32_t param_dtype;    /* PS_BF16 (0) or PS_F16, as in ps_shard_t                   */
     void *slot[3];          /* DEVICE, each 14 * bucket_elems bytes, 16-byte aligned:
-                               master | m | v (FP32) | parameters (bf16) of one bucket  */
+                               master | m | v (FP32) | 16-bit parameters of one bucket  */
     void *h2d_stream;       /* hipStream_t; the three streams must differ                */
     void *compute_stream;
     void *d2h_stream;
@@ -308,7 +317,9 @@ ps_status_t ps_device_info(ps_device_info_t *info);
  *   v'  = fma(beta2, v, ((1-beta2) * g) * g)
  *   u   = m' / fma(sqrt(v'), 1/sqrt(1-beta2^t), eps)
  *   th' = fma(-lr/(1-beta1^t), u, fma(-lr*wd, th, th))
- *   out = bf16 round-to-nearest-even of th'  (NaN -> 0x7FC0 with the sign)
+ *   out = th' rounded to nearest even in the parameters' 16-bit format (bf16:
+ *         NaN -> 0x7FC0 with the sign; binary16: NaN -> 0x7E00 with the sign,
+ *         |th'| >= 65520 -> infinity, subnormals kept)
  *
  * each line one correctly rounded binary32 operation.  State pointers in *shard
  * are shard-based (element 0 of the shard); grads->contrib[r] points at element
@@ -400,7 +411,7 @@ ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
 uint64_t ps_verify_workspace_bytes(uint64_t buffer_bytes);
 
 /* Gradient integrity check: writes out2[0] = sum (a-b)^2 and out2[1] = sum a^2
- * over elem_count elements of the DEVICE buffers a and b (PS_BF16 or PS_F32,
+ * over elem_count elements of the DEVICE buffers a and b (PS_BF16, PS_F16 or PS_F32,
  * one type for both), accumulated in binary64 in a fixed tree (reproducible bit
  * for bit).  The caller forms ||a-b|| / ||a|| = sqrt(out2[0] / out2[1]) and
  * compares it with the protocol's 1e-5.  accumulate != 0 adds to the values

@@ -15,7 +15,7 @@ import torch  # noqa: F401
 from . import build as _build
 
 __all__ = [
-    "PS_R", "PS_S", "PS_SG", "PS_M", "PS_O", "PS_BF16", "PS_F32", "PS_MAX_CONTRIB", "PS_COPY_KERNEL", "PS_COPY_MEMCPY", "PS_SCHED_AUTO", "PS_SCHED_OVERLAP", "PS_SCHED_ALTERNATE",
+    "PS_R", "PS_S", "PS_SG", "PS_M", "PS_O", "PS_BF16", "PS_F32", "PS_F16", "PS_MAX_CONTRIB", "PS_COPY_KERNEL", "PS_COPY_MEMCPY", "PS_SCHED_AUTO", "PS_SCHED_OVERLAP", "PS_SCHED_ALTERNATE",
     "PS_OK", "PS_EINVAL", "PS_EUNSUPPORTED", "PS_EALIGN", "PS_ERANGE", "PS_ENODEVICE", "PS_EHIP",
     "PsError", "ps_spec_t", "ps_cost_t", "ps_adamw_t", "ps_shard_t", "ps_grads_t",
     "ps_bucket_plan_t", "ps_offload_plan_t", "ps_device_info_t", "library", "library_path",
@@ -27,9 +27,9 @@ __all__ = [
     "ps_step_clip_coef", "EXPORTED_SYMBOLS", "ABI_VERSION",
 ]
 
-ABI_VERSION = 2   # PS_ABI_VERSION of include/ps_step.h this binding mirrors
+ABI_VERSION = 3   # PS_ABI_VERSION of include/ps_step.h this binding mirrors
 PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
-PS_BF16, PS_F32 = 0, 1
+PS_BF16, PS_F32, PS_F16 = 0, 1, 2
 PS_COPY_KERNEL, PS_COPY_MEMCPY = 0, 1
 PS_SCHED_AUTO, PS_SCHED_OVERLAP, PS_SCHED_ALTERNATE = 0, 1, 2
 PS_MAX_CONTRIB = 16
@@ -79,7 +79,8 @@ class ps_adamw_t(C.Structure):
 
 class ps_shard_t(C.Structure):
     _fields_ = [("master", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
-                ("gather_out", C.c_void_p), ("len", C.c_uint64), ("valid_len", C.c_uint64)]
+                ("gather_out", C.c_void_p), ("len", C.c_uint64), ("valid_len", C.c_uint64),
+                ("param_dtype", C.c_int32), ("reserved", C.c_int32)]
 
 
 class ps_grads_t(C.Structure):
@@ -99,7 +100,7 @@ class ps_bucket_plan_t(C.Structure):
 class ps_offload_plan_t(C.Structure):
     _fields_ = [("host_master", C.c_void_p), ("host_m", C.c_void_p), ("host_v", C.c_void_p),
                 ("host_param_out", C.c_void_p), ("len", C.c_uint64), ("valid_len", C.c_uint64),
-                ("bucket_elems", C.c_uint64), ("n_slots", C.c_uint32), ("reserved", C.c_uint32),
+                ("bucket_elems", C.c_uint64), ("n_slots", C.c_uint32), ("param_dtype", C.c_int32),
                 ("slot", C.c_void_p * 3), ("h2d_stream", C.c_void_p),
                 ("compute_stream", C.c_void_p), ("d2h_stream", C.c_void_p)]
 

@@ -26,6 +26,7 @@ struct StepScalars {
     float isb2; // 1 / sqrt(1 - beta2^t)
     float lw;   // lr * weight_decay
     const float *cc_device; // when set: the clip coefficient is read from here at run time
+    uint32_t out_f16;       // parameters are written as binary16 instead of bf16
 };
 
 struct ContribPtrs {

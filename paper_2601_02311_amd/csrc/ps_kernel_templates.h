@@ -1,8 +1,8 @@
 // Device code of the sharded optimizer step for gfx950 (CDNA4, wave64).
 //
 // The step is a pure stream: per element it reads N gradient contributions and
-// three FP32 state words, and writes three FP32 state words and one bf16
-// parameter, each byte exactly once.  There is no reuse and no contraction, so
+// three FP32 state words, and writes three FP32 state words and one 16-bit
+// parameter (bf16 or binary16), each byte exactly once.  There is no reuse and no contraction, so
 // nothing here uses MFMA, and LDS only serves the sum-of-squares tree.  What
 // decides the speed is how the request stream looks to the HBM controllers.
 // Measured on MI355X, in this order of importance:
@@ -63,11 +63,42 @@ __device__ __forceinline__ void store_vec(T *p, T x)
         *p = x;
 }
 
+// Element types of the 16-bit buffers: uint16_t stands for bf16 bit patterns,
+// f16_bits for IEEE binary16 (the FP16 of the paper's Table 1); float is float.
+struct f16_bits {
+    uint16_t v;
+};
+
 // bf16 -> binary32 is a 16-bit shift of the pattern (exact).
 __device__ __forceinline__ float widen_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
 __device__ __forceinline__ float widen_hi(uint32_t pair)
 {
     return __uint_as_float(pair & 0xffff0000u);
+}
+
+// binary16 -> binary32 (exact, subnormals included: the conversion instruction
+// does not flush them).
+__device__ __forceinline__ float widen_f16(uint32_t bits16)
+{
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
+}
+
+// The two 16-bit values packed in one 32-bit word, widened according to G.
+template <typename G>
+__device__ __forceinline__ float widen16_lo(uint32_t pair)
+{
+    if constexpr (sizeof(G) == 2 && !__is_same(G, uint16_t))
+        return widen_f16(pair & 0xffffu);
+    else
+        return widen_lo(pair);
+}
+template <typename G>
+__device__ __forceinline__ float widen16_hi(uint32_t pair)
+{
+    if constexpr (sizeof(G) == 2 && !__is_same(G, uint16_t))
+        return widen_f16(pair >> 16);
+    else
+        return widen_hi(pair);
 }
 
 // binary32 -> bf16, round to nearest, ties to even; NaN -> quiet NaN, sign kept.
@@ -77,6 +108,23 @@ __device__ __forceinline__ uint32_t narrow_bf16(float x)
     uint32_t r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
     uint32_t nan = ((u >> 16) & 0x8000u) | 0x7fc0u;
     return (u & 0x7fffffffu) > 0x7f800000u ? nan : r;
+}
+
+// binary32 -> binary16, round to nearest, ties to even (the conversion
+// instruction under the default rounding mode; overflow goes to infinity, small
+// magnitudes to subnormals); NaN -> quiet NaN 0x7E00, sign kept.
+__device__ __forceinline__ uint32_t narrow_f16(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    const uint32_t nan = ((u >> 16) & 0x8000u) | 0x7e00u;
+    const uint32_t r = __builtin_bit_cast(uint16_t, (_Float16)x);
+    return (u & 0x7fffffffu) > 0x7f800000u ? nan : r;
+}
+
+// The 16-bit image of a new master weight in the parameters' format.
+__device__ __forceinline__ uint32_t narrow16(float x, uint32_t out_f16)
+{
+    return out_f16 ? narrow_f16(x) : narrow_bf16(x);
 }
 
 // The per-element update.  acc is the fixed-order sum of the N per-device
@@ -125,10 +173,10 @@ __device__ __forceinline__ f32x4 load_contrib4(const void *base, uint64_t elem)
         u32x2 w = load_vec<NT>(reinterpret_cast<const u32x2 *>(
             reinterpret_cast<const uint16_t *>(base) + elem));
         f32x4 r;
-        r.x = widen_lo(w.x);
-        r.y = widen_hi(w.x);
-        r.z = widen_lo(w.y);
-        r.w = widen_hi(w.y);
+        r.x = widen16_lo<G>(w.x);
+        r.y = widen16_hi<G>(w.x);
+        r.z = widen16_lo<G>(w.y);
+        r.w = widen16_hi<G>(w.y);
         return r;
     } else {
         return load_vec<NT>(
@@ -140,7 +188,7 @@ template <typename G>
 __device__ __forceinline__ float load_contrib1(const void *base, uint64_t elem)
 {
     if constexpr (sizeof(G) == 2)
-        return __uint_as_float((uint32_t) reinterpret_cast<const uint16_t *>(base)[elem] << 16);
+        return widen16_lo<G>(reinterpret_cast<const uint16_t *>(base)[elem]);
     else
         return reinterpret_cast<const float *>(base)[elem];
 }
@@ -188,7 +236,7 @@ struct UpdateArgs {
 // image it writes is the persistent S* shard that the next All-Gather reads
 // (Definition 1, Eq. 3), or this shard's slice of the replicated parameters.
 //   N : contribution count known at compile time, 0 = read it from args
-//   G : uint16_t (bf16 bits) or float
+//   G : uint16_t (bf16 bits), f16_bits (binary16) or float
 // The loop only repeats when there are more tiles than the grid can hold.
 template <int N, typename G>
 __global__ __launch_bounds__(kWave) void update_tiles(const UpdateArgs a)
@@ -222,8 +270,8 @@ __global__ __launch_bounds__(kWave) void update_tiles(const UpdateArgs a)
         }
         step_element4(acc, th, mm, vv, s);
         u32x2 pk;
-        pk.x = narrow_bf16(th.x) | (narrow_bf16(th.y) << 16);
-        pk.y = narrow_bf16(th.z) | (narrow_bf16(th.w) << 16);
+        pk.x = narrow16(th.x, s.out_f16) | (narrow16(th.y, s.out_f16) << 16);
+        pk.y = narrow16(th.z, s.out_f16) | (narrow16(th.w, s.out_f16) << 16);
         store_vec<true>(reinterpret_cast<f32x4 *>(a.master + e), th);
         store_vec<true>(reinterpret_cast<f32x4 *>(a.m + e), mm);
         store_vec<true>(reinterpret_cast<f32x4 *>(a.v + e), vv);
@@ -248,7 +296,7 @@ __global__ __launch_bounds__(kWave) void update_tail(const UpdateArgs a)
     a.master[e] = th;
     a.m[e] = m;
     a.v[e] = v;
-    a.out[e] = (uint16_t)narrow_bf16(th);
+    a.out[e] = (uint16_t)narrow16(th, s.out_f16);
 }
 
 struct AccumArgs {
@@ -513,8 +561,9 @@ __global__ __launch_bounds__(kScanThreads) void diff_sumsq_tiles(const ScanArgs 
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if constexpr (sizeof(G) == 2) {
-                const double xl = (double)widen_lo(xw[i]), xh = (double)widen_hi(xw[i]);
-                const double dl = xl - (double)widen_lo(yw[i]), dh = xh - (double)widen_hi(yw[i]);
+                const double xl = (double)widen16_lo<G>(xw[i]), xh = (double)widen16_hi<G>(xw[i]);
+                const double dl = xl - (double)widen16_lo<G>(yw[i]);
+                const double dh = xh - (double)widen16_hi<G>(yw[i]);
                 sd += dl * dl;
                 sa += xl * xl;
                 sd += dh * dh;

@@ -119,6 +119,8 @@ int launch_update(int dtype, uint32_t n_contrib, const ContribPtrs &g, float *ma
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     if (dtype == PS_BF16)
         return launch_update_t<uint16_t>(n_contrib, g, master, m, v, out, count, s, st);
+    if (dtype == PS_F16)
+        return launch_update_t<f16_bits>(n_contrib, g, master, m, v, out, count, s, st);
     return launch_update_t<float>(n_contrib, g, master, m, v, out, count, s, st);
 }
 
@@ -181,6 +183,8 @@ int launch_accumulate(int dtype, uint32_t n_contrib, const ContribPtrs &g, float
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     if (dtype == PS_BF16)
         return launch_accum_t<uint16_t>(n_contrib, g, accum, overwrite, count, st);
+    if (dtype == PS_F16)
+        return launch_accum_t<f16_bits>(n_contrib, g, accum, overwrite, count, st);
     return launch_accum_t<float>(n_contrib, g, accum, overwrite, count, st);
 }
 
@@ -294,6 +298,9 @@ int launch_reduce_sumsq(int dtype, uint32_t n_contrib, const ContribPtrs &g, flo
     if (dtype == PS_BF16)
         return launch_reduce_t<uint16_t>(n_contrib, g, gs, reduced_out, count, partials,
                                          sumsq_out, accumulate, st);
+    if (dtype == PS_F16)
+        return launch_reduce_t<f16_bits>(n_contrib, g, gs, reduced_out, count, partials,
+                                         sumsq_out, accumulate, st);
     return launch_reduce_t<float>(n_contrib, g, gs, reduced_out, count, partials, sumsq_out,
                                   accumulate, st);
 }
@@ -371,6 +378,8 @@ int launch_diff_sumsq(int dtype, const void *a, const void *b, uint64_t count, d
     uint64_t *ws = reinterpret_cast<uint64_t *>(workspace);
     if (dtype == PS_BF16)
         return launch_diff_t<uint16_t>(a, b, count, out2, accumulate, ws, slots, st);
+    if (dtype == PS_F16)
+        return launch_diff_t<f16_bits>(a, b, count, out2, accumulate, ws, slots, st);
     return launch_diff_t<float>(a, b, count, out2, accumulate, ws, slots, st);
 }
 

@@ -37,7 +37,7 @@ ps_status_t need_device()
 }
 
 // beta^t for t up to 2^64-1 through the C library's pow in binary64.
-StepScalars derive_scalars(const ps_adamw_t &hp, uint32_t n_devices)
+StepScalars derive_scalars(const ps_adamw_t &hp, uint32_t n_devices, int32_t param_dtype)
 {
     const double bias1 = 1.0 - std::pow(hp.beta1, (double)hp.step);
     const double bias2 = 1.0 - std::pow(hp.beta2, (double)hp.step);
@@ -53,6 +53,7 @@ StepScalars derive_scalars(const ps_adamw_t &hp, uint32_t n_devices)
     s.isb2 = (float)(1.0 / std::sqrt(bias2));
     s.lw = (float)(hp.lr * hp.weight_decay);
     s.cc_device = hp.clip_coef_device;
+    s.out_f16 = param_dtype == PS_F16;
     return s;
 }
 
@@ -144,8 +145,8 @@ ps_status_t check_contribs(const void *const *ptrs, uint32_t n_contrib, int32_t 
         set_error("%s pointer array is NULL", what);
         return PS_EINVAL;
     }
-    if (dtype != PS_BF16 && dtype != PS_F32) {
-        set_error("%s dtype must be PS_BF16 or PS_F32", what);
+    if (dtype != PS_BF16 && dtype != PS_F32 && dtype != PS_F16) {
+        set_error("%s dtype must be PS_BF16, PS_F16 or PS_F32", what);
         return PS_EINVAL;
     }
     if (n_contrib == 0 || n_contrib > PS_MAX_CONTRIB) {
@@ -238,7 +239,22 @@ uint64_t clamp_count(uint64_t off, uint64_t count, uint64_t valid)
     return count < valid - off ? count : valid - off;
 }
 
-uint64_t elem_bytes(int32_t dtype) { return dtype == PS_BF16 ? 2 : 4; }
+uint64_t elem_bytes(int32_t dtype) { return dtype == PS_F32 ? 4 : 2; }
+
+// The parameters' 16-bit format, and that 16-bit gradients come in the same one.
+ps_status_t check_param_dtype(int32_t param_dtype, int32_t reserved, int32_t grad_dtype)
+{
+    if ((param_dtype != PS_BF16 && param_dtype != PS_F16) || reserved != 0) {
+        set_error("param_dtype must be PS_BF16 or PS_F16, reserved 0");
+        return PS_EINVAL;
+    }
+    if (grad_dtype != PS_F32 && grad_dtype != param_dtype) {
+        set_error("16-bit gradients (dtype %d) and parameters (dtype %d) must share one format",
+                  grad_dtype, param_dtype);
+        return PS_EUNSUPPORTED;
+    }
+    return PS_OK;
+}
 
 } // namespace
 
@@ -298,6 +314,7 @@ ps_status_t ps_step_update(const ps_spec_t *spec, const ps_adamw_t *hp, const ps
     const bool z1 = replicated_grad(spec);
     if ((st = check_contribs(grads->contrib, grads->n_contrib, grads->dtype, spec->n_devices,
                              "contribution", z1)) != PS_OK ||
+        (st = check_param_dtype(shard->param_dtype, shard->reserved, grads->dtype)) != PS_OK ||
         (st = check_range(elem_offset, elem_count, shard->len)) != PS_OK)
         return st;
     const uint64_t count = clamp_count(elem_offset, elem_count, shard->valid_len);
@@ -306,7 +323,7 @@ ps_status_t ps_step_update(const ps_spec_t *spec, const ps_adamw_t *hp, const ps
     if ((st = need_device()) != PS_OK)
         return st;
 
-    const StepScalars s = derive_scalars(*hp, spec->n_devices);
+    const StepScalars s = derive_scalars(*hp, spec->n_devices, shard->param_dtype);
     ContribPtrs g;
     std::memset(&g, 0, sizeof g);
     for (uint32_t r = 0; r < grads->n_contrib; ++r)
@@ -488,7 +505,8 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
         return PS_EUNSUPPORTED;
     }
     if ((st = check_contribs(plan->source, plan->n_contrib, plan->dtype, spec->n_devices,
-                             "bucket source")) != PS_OK)
+                             "bucket source")) != PS_OK ||
+        (st = check_param_dtype(shard->param_dtype, shard->reserved, plan->dtype)) != PS_OK)
         return st;
     if (plan->bucket_elems == 0 || plan->bucket_elems % 8 != 0) {
         set_error("bucket_elems must be a positive multiple of 8");
@@ -540,7 +558,7 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
 
     hipStream_t copy = reinterpret_cast<hipStream_t>(plan->copy_stream);
     hipStream_t comp = reinterpret_cast<hipStream_t>(plan->compute_stream);
-    const StepScalars s = derive_scalars(*hp, spec->n_devices);
+    const StepScalars s = derive_scalars(*hp, spec->n_devices, shard->param_dtype);
     const uint64_t eb = elem_bytes(plan->dtype);
     const uint64_t slot_stride = plan->bucket_elems * eb; // bytes between contributions in a slot
     const bool timed = plan->kernel_ms != nullptr;
@@ -678,8 +696,8 @@ ps_status_t ps_verify_diff_sumsq(const void *a, const void *b, int32_t dtype, ui
         set_error("a, b, out2 or workspace is NULL");
         return PS_EINVAL;
     }
-    if (dtype != PS_BF16 && dtype != PS_F32) {
-        set_error("dtype must be PS_BF16 or PS_F32");
+    if (dtype != PS_BF16 && dtype != PS_F32 && dtype != PS_F16) {
+        set_error("dtype must be PS_BF16, PS_F16 or PS_F32");
         return PS_EINVAL;
     }
     if (!aligned16(a) || !aligned16(b) || !aligned16(workspace) ||
@@ -748,8 +766,8 @@ ps_status_t ps_step_update_offloaded(const ps_spec_t *spec, const ps_adamw_t *hp
         set_error("plan has a NULL host buffer");
         return PS_EINVAL;
     }
-    if (plan->reserved != 0 || (plan->n_slots != 2 && plan->n_slots != 3)) {
-        set_error("n_slots must be 2 or 3, reserved 0");
+    if (plan->n_slots != 2 && plan->n_slots != 3) {
+        set_error("n_slots must be 2 or 3");
         return PS_EINVAL;
     }
     for (uint32_t k = 0; k < plan->n_slots; ++k) {
@@ -790,7 +808,8 @@ ps_status_t ps_step_update_offloaded(const ps_spec_t *spec, const ps_adamw_t *hp
         return PS_ERANGE;
     }
     if ((st = check_contribs(grads->contrib, grads->n_contrib, grads->dtype, spec->n_devices,
-                             "contribution")) != PS_OK)
+                             "contribution")) != PS_OK ||
+        (st = check_param_dtype(plan->param_dtype, 0, grads->dtype)) != PS_OK)
         return st;
     const uint64_t B = plan->bucket_elems;
     const uint64_t n_buckets = (plan->valid_len + B - 1) / B;
@@ -802,7 +821,7 @@ ps_status_t ps_step_update_offloaded(const ps_spec_t *spec, const ps_adamw_t *hp
     hipStream_t up = reinterpret_cast<hipStream_t>(plan->h2d_stream);
     hipStream_t comp = reinterpret_cast<hipStream_t>(plan->compute_stream);
     hipStream_t down = reinterpret_cast<hipStream_t>(plan->d2h_stream);
-    const StepScalars s = derive_scalars(*hp, spec->n_devices);
+    const StepScalars s = derive_scalars(*hp, spec->n_devices, plan->param_dtype);
     const uint64_t eb = elem_bytes(grads->dtype);
     const uint32_t S = plan->n_slots;
     hipEvent_t loaded[3] = {}, computed[3] = {}, drained[3] = {};

@@ -14,7 +14,7 @@ class Workload:
     n_devices: int           # N
     shard_index: int         # i
     strategy: str            # row of the paper's Table 2
-    grad_dtype: str          # "bf16" or "f32"
+    grad_dtype: str          # "bf16", "f16" or "f32"
     lr: float = 1e-4
     beta1: float = 0.9
     beta2: float = 0.999
@@ -32,6 +32,8 @@ class Workload:
     bucket_elems: int = 0           # >0: gradients arrive in buckets of this many elements
     max_grad_norm: float = 0.0      # >0: global-norm clipping
     micro_batches: int = 1          # >1: gradient accumulation over this many micro-batches
+    loss_scale: float = 1.0         # gradients are generated times this, grad_scale divides it out
+    param_dtype: str = "bf16"       # the 16-bit format of the parameter image: "bf16" or "f16"
     seed: int = 20260102
     extra: dict = field(default_factory=dict)
 
@@ -72,6 +74,12 @@ WORKLOADS = {
     # The other data-parallel rows of the paper's Table 2 on the 7B shard: ZeRO-1 (the
     # gradient arrives all-reduced, one replicated full-length buffer) and gradient
     # accumulation over four micro-batches before one ZeRO-2 update.
+    # The same shard in the paper's own FP16 (Table 1): binary16 gradients carrying a loss
+    # scale of 1024, binary16 parameter image.
+    "7b_zero2_f16": Workload("7b_zero2_f16", psi=6_738_415_616, n_devices=8, shard_index=0,
+                             strategy="zero2", grad_dtype="f16", param_dtype="f16", first_step=1000,
+                             warm_moments=True, grad_std=1e-4, outlier_frac=0.001,
+                             outlier_mult=100.0, loss_scale=1024.0),
     "7b_zero1": Workload("7b_zero1", psi=6_738_415_616, n_devices=8, shard_index=0,
                          strategy="zero1", grad_dtype="bf16", first_step=1000,
                          warm_moments=True, grad_std=8e-4),

@@ -2,8 +2,8 @@
 
 Buffers are filled in place, chunk by chunk, from a seeded ``torch.Generator``
 so that no temporary larger than a chunk is ever alive.  bf16 data is stored
-in ``torch.bfloat16`` tensors; the step library and the oracle only ever see
-the raw bytes.
+in ``torch.bfloat16`` tensors, binary16 in ``torch.float16``; the step library and the
+oracle only ever see the raw bytes.
 """
 import torch
 
@@ -75,7 +75,7 @@ def workload_state(w, n=None):
 
 def workload_gradients(w, step, n=None):
     n = w.shard_len if n is None else n
-    dt = torch.bfloat16 if w.grad_dtype == "bf16" else torch.float32
-    return [fill_gradient_(torch.empty(n, dtype=dt, device="cuda"), w.seed, step, r, w.grad_std,
-                           w.outlier_frac, w.outlier_mult, w.student_t_dof)
+    dt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[w.grad_dtype]
+    return [fill_gradient_(torch.empty(n, dtype=dt, device="cuda"), w.seed, step, r,
+                           w.grad_std * w.loss_scale, w.outlier_frac, w.outlier_mult, w.student_t_dof)
             for r in range(w.n_devices)]

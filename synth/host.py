@@ -52,5 +52,5 @@ def gradient(n, seed, step, replica, dtype="bf16", std=1e-3, outlier_frac=0.0,
 def workload_gradients(w, step, n=None):
     """All N contributions of workload ``w`` at ``step`` (full flat length unless n given)."""
     n = w.psi_padded if n is None else n
-    return [gradient(n, w.seed, step, r, w.grad_dtype, w.grad_std, w.outlier_frac,
+    return [gradient(n, w.seed, step, r, w.grad_dtype, w.grad_std * w.loss_scale, w.outlier_frac,
                      w.outlier_mult, w.student_t_dof) for r in range(w.n_devices)]

@@ -7,7 +7,7 @@ import torch
 
 import paper_2601_02311_amd as ps
 
-DT = {"bf16": ps.PS_BF16, "f32": ps.PS_F32}
+DT = {"bf16": ps.PS_BF16, "f32": ps.PS_F32, "f16": ps.PS_F16}
 
 
 def dev(a):
@@ -22,7 +22,7 @@ def host(t):
     t = t.detach()
     if t.dtype == torch.bfloat16:
         t = t.view(torch.int16)
-    a = t.cpu().numpy()
+    a = t.cpu().numpy()                      # float16 tensors come back as numpy float16
     return a.view(np.uint16) if a.dtype == np.int16 else a
 
 
@@ -40,12 +40,14 @@ def hp_of(w=None, t=1, **kw):
 
 
 def shard_of(master, m, v, out, length, valid=None):
+    """The parameter format follows the output tensor: float16 -> PS_F16, else bf16."""
+    fmt = ps.PS_F16 if out.dtype == torch.float16 else ps.PS_BF16
     return ps.ps_shard_t(master.data_ptr(), m.data_ptr(), v.data_ptr(), out.data_ptr(), length,
-                         length if valid is None else valid)
+                         length if valid is None else valid, fmt, 0)
 
 
 def grads_of(tensors, dtype, elem_offset=0):
-    esz = 2 if dtype == "bf16" else 4
+    esz = 4 if dtype == "f32" else 2
     return ps.make_grads([t.data_ptr() + elem_offset * esz for t in tensors], DT[dtype])
 
 
@@ -58,12 +60,13 @@ def ulp_diff(a, b):
 
 def assert_state_parity(got, want, what=""):
     """got/want: (theta, m, v, p) numpy arrays.  master/m/v within 2 binary32 ulp of the
-    oracle (NaNs must coincide); the bf16 image bit-exact wherever theta' agrees."""
+    oracle (NaNs must coincide); the 16-bit image bit-exact wherever theta' agrees."""
     for name, g, w in zip(("theta", "m", "v"), got[:3], want[:3]):
         gn, wn = np.isnan(g), np.isnan(w)
         assert np.array_equal(gn, wn), "%s %s: NaN pattern differs" % (what, name)
         d = ulp_diff(g[~gn], w[~wn])
         assert d.size == 0 or d.max() <= 2, "%s %s: max ulp %d" % (what, name, d.max())
     same = got[0].view(np.uint32) == want[0].view(np.uint32)
-    assert np.array_equal(got[3][same], want[3][same]), "%s bf16 image differs" % what
+    gp, wp = got[3].view(np.uint16), want[3].view(np.uint16)         # bf16 bits or binary16, as bits
+    assert np.array_equal(gp[same], wp[same]), "%s 16-bit image differs" % what
     return int((~same).sum())

@@ -52,38 +52,43 @@ def _hp(w, t, **kw):
 
 
 def _whole_shard_properties(master, m, v, out_slice, valid):
-    """bf16 image == RNE cast of the new master weight (library conversion), v' >= 0,
+    """16-bit image == RNE cast of the new master weight (library conversion), v' >= 0,
     everything finite -- over every element, on the device."""
     step = 1 << 28
     for lo in range(0, valid, step):
         hi = min(lo + step, valid)
-        assert torch.equal(master[lo:hi].to(torch.bfloat16).view(torch.int16),
+        assert torch.equal(master[lo:hi].to(out_slice.dtype).view(torch.int16),
                            out_slice[lo:hi].view(torch.int16))
         assert bool((v[lo:hi] >= 0).all())
         assert bool(torch.isfinite(master[lo:hi]).all()) and bool(torch.isfinite(m[lo:hi]).all())
 
 
-def test_7b_zero2_full_shard_sampled():
-    w = WORKLOADS["7b_zero2"]
+@pytest.mark.parametrize("name", ["7b_zero2", "7b_zero2_f16"])
+def test_7b_zero2_full_shard_sampled(name):
+    """bf16 gradients and parameters, and the same shard in binary16 with a loss scale."""
+    w = WORKLOADS[name]
     _need(45)
     n, N, t = w.shard_len, w.n_devices, w.first_step
-    _say("7b_zero2 full shard n=%d, one launch, sampled slices" % n)
+    f16 = w.param_dtype == "f16"
+    _say("%s full shard n=%d, one launch, sampled slices" % (name, n))
     spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi)
     cost = ps.ps_cost_eval(spec)
     master, m, v = dgen.workload_state(w)
     grads = dgen.workload_gradients(w, t)
-    out = torch.zeros(cost.psi_padded, dtype=torch.bfloat16, device="cuda")   # replicated Theta
+    out = torch.zeros(cost.psi_padded, dtype=torch.float16 if f16 else torch.bfloat16,
+                      device="cuda")                                            # replicated Theta
     sl = _slices(n)
     before = [([_take(x, lo, hi) for x in (master, m, v)], [_take(g, lo, hi) for g in grads])
               for lo, hi in sl]
-    hpd, hp = _hp(w, t)
+    gs = 1.0 / (N * w.loss_scale) if w.loss_scale != 1.0 else 0.0
+    hpd, hp = _hp(w, t, grad_scale=gs)
     ps.ps_step_update(spec, hp, shard_of(master, m, v, out, n), ps.make_grads(
-        [g.data_ptr() for g in grads], ps.PS_BF16), 0, n, stream_handle())
+        [g.data_ptr() for g in grads], ps.PS_F16 if f16 else ps.PS_BF16), 0, n, stream_handle())
     torch.cuda.synchronize()
-    s = orc.derive_scalars(t=t, n_devices=N, **hpd)
+    s = orc.derive_scalars(t=t, n_devices=N, grad_scale=gs, **hpd)
     off = cost.shard_offset
     for (lo, hi), (st, gr) in zip(sl, before):
-        want = [a.copy() for a in st] + [np.zeros(hi - lo, np.uint16)]
+        want = [a.copy() for a in st] + [np.zeros(hi - lo, np.float16 if f16 else np.uint16)]
         orc.step_f32(gr, s, *want)
         got = [_take(x, lo, hi) for x in (master, m, v)] + [_take(out, off + lo, off + hi)]
         assert assert_state_parity(got, want, "7b [%d,%d)" % (lo, hi)) == 0

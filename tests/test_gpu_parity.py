@@ -1097,3 +1097,201 @@ def test_bucketed_step_from_pinned_host_source(engine):
     ps.ps_step_update_bucketed(spec, hp, shard_of(th, m, v, p, n), plan)
     torch.cuda.synchronize()
     assert assert_state_parity([host(x) for x in (th, m, v, p)], want, "pinned source") == 0
+
+
+# ---- IEEE binary16 gradients and parameters (the FP16 of the paper's Table 1) ----
+
+LOSS_SCALE = 1024.0
+
+
+def _f16_case(n, N, seed, valid=None, std=1e-3):
+    """Scaled FP16 contributions (a loss scale of 1024 rides on grad_scale), FP32 state,
+    FP16 parameters; returns (grads, state, oracle scalars dict, hp)."""
+    grads = [gen.gradient(n, seed, 0, r, "f16", std=std * LOSS_SCALE, outlier_frac=0.01, outlier_mult=30.0)
+             for r in range(N)]
+    state = [gen.master(n, seed), *gen.moments(n, seed, True), np.full(n, np.float16(-77.0), np.float16)]
+    gs = 1.0 / (N * LOSS_SCALE)
+    hpd, hp = hp_of(None, 5, grad_scale=gs)
+    return grads, state, orc.derive_scalars(t=5, n_devices=N, grad_scale=gs, **hpd), hp
+
+
+@pytest.mark.parametrize("N", [2, 3, 8, 16])
+def test_f16_update_ragged(N):
+    n = 3 * TILE + 1234 + 3
+    valid = n - 5
+    _say("binary16 update n=%d valid=%d N=%d" % (n, valid, N))
+    spec = ps.ps_spec_preset("zero3", N, 0, n * N)
+    grads, state, s, hp = _f16_case(n, N, 201)
+    want = [a.copy() for a in state]
+    orc.step_f32(grads, s, *want, lo=0, hi=valid)
+    got = _run_gpu(spec, hp, state, grads, "f16", n, valid)
+    assert assert_state_parity(got, want, "f16") == 0
+    for g, a in zip(got, state):                                   # pads untouched, byte for byte
+        assert np.array_equal(g[valid:].view(np.uint8), a[valid:].view(np.uint8))
+    # a pre-reduced FP32 gradient with FP16 parameters (clip phase 2, accumulation)
+    red = orc.reduce_sum(grads)
+    want = [a.copy() for a in state]
+    orc.step_f32([red], s, *want, lo=0, hi=valid)
+    got = _run_gpu(spec, hp, state, [red], "f32", n, valid)
+    assert assert_state_parity(got, want, "f32 gradient, f16 parameters") == 0
+
+
+def test_f16_special_values():
+    """Overflow of the parameter image to infinity, subnormal images, infinite and NaN
+    gradients, the largest finite binary16 gradient summed N times."""
+    n, N = TILE + 64, 2
+    _say("binary16 special values n=%d" % n)
+    spec = ps.ps_spec_preset("zero3", N, 0, n * N)
+    grads, state, s, hp = _f16_case(n, N, 203)
+    g0, g1 = grads
+    g0[:6] = [np.inf, -np.inf, np.nan, 65504.0, 6e-8, -0.0]
+    g1[:6] = [1.0, 1.0, 1.0, 65504.0, 6e-8, -0.0]
+    g0[6:10] = np.inf
+    g1[6:10] = -np.inf                                             # inf - inf
+    th = state[0]
+    th[16:26] = [65519.9, 65530.0, -7e4, 3e38, 6.0e-8, 2.98e-8, 2.99e-8, -1e-9, 6.1e-5, 0.0]
+    for a in (g0, g1, state[1], state[2]):
+        a[16:26] = 0                                               # there only the decay acts
+    want = [a.copy() for a in state]
+    orc.step_f32(grads, s, *want)
+    got = _run_gpu(spec, hp, state, grads, "f16", n)
+    assert_state_parity(got, want, "f16 specials")
+    nan = np.isnan(want[0])
+    assert nan[2] and nan[6:10].all()
+    gp, wp = got[3].view(np.uint16), want[3].view(np.uint16)
+    assert ((gp[nan] & 0x7fff) == 0x7e00).all()                    # canonical quiet NaN
+    assert np.array_equal(gp[~nan], wp[~nan])
+    assert got[3][16] == np.float16(65504.0) and np.isinf(got[3][17:20]).all()     # 65520 and up: infinity
+    units = got[3][20:23].view(np.uint16)                    # subnormal images: units of 2^-24
+    assert list(units) == [1, 0, 1]                          # 6.0e-8 -> 1; just under / over half a unit
+    assert got[3][23].view(np.uint16) == 0x8000                                     # underflow keeps the sign
+
+
+def test_f16_cast_exhaustive_over_all_binary32_patterns():
+    """As for bf16: with lr = 0, zero moments and a zero gradient every finite master value
+    but -0 passes unchanged, so the binary16 image covers the cast of all 2^32 patterns;
+    compared bit for bit with the library's float32 -> float16 conversion."""
+    chunk = 1 << 28
+    _say("exhaustive binary16 cast: 2^32 master patterns in %d launches" % ((1 << 32) // chunk))
+    spec = ps.ps_spec_preset("zero3", 4, 0, chunk * 4)
+    _, hp = hp_of(None, 1, lr=0.0, weight_decay=0.0, grad_scale=1.0)
+    bits = torch.empty(chunk, dtype=torch.int32, device="cuda")
+    th = bits.view(torch.float32)
+    m = torch.zeros(chunk, dtype=torch.float32, device="cuda")
+    v = torch.zeros_like(m)
+    g = torch.zeros_like(m)
+    out = torch.empty(chunk, dtype=torch.float16, device="cuda")
+    ramp = torch.arange(chunk, dtype=torch.int64, device="cuda")
+    for lo in range(0, 1 << 32, chunk):
+        before = ((ramp + lo) & 0xffffffff)
+        bits.copy_(torch.where(before >= (1 << 31), before - (1 << 32), before).to(torch.int32))
+        before = bits.clone()
+        out.fill_(3.0)
+        ps.ps_step_update(spec, hp, shard_of(th, m, v, out, chunk), grads_of([g], "f32"), 0, chunk,
+                          stream_handle())
+        torch.cuda.synchronize()
+        finite = (before & 0x7fffffff) < 0x7f800000
+        keep = finite & (before != -(1 << 31))
+        assert torch.equal(bits[keep], before[keep]), hex(lo)
+        nan = torch.isnan(th)
+        lib = th.to(torch.float16).view(torch.int16)
+        o16 = out.view(torch.int16)
+        assert torch.equal(o16[~nan], lib[~nan]), hex(lo)
+        assert bool(((o16[nan] & 0x7fff) == 0x7e00).all()), hex(lo)
+
+
+def test_f16_reduce_accumulate_and_difference():
+    """The other entry points that read gradients, with binary16 contributions: reduce +
+    sum of squares, accumulation over micro-batches, and the relative-difference scan."""
+    N, n = 4, 9 * TILE + 777
+    valid = n - 11
+    _say("binary16 reduce / accumulate / difference n=%d N=%d" % (n, N))
+    spec = ps.ps_spec_preset("zero3", N, 0, n * N)
+    grads, _, s, _ = _f16_case(n, N, 207)
+    gs = 1.0 / (N * LOSS_SCALE)
+    mean, ss = orc.mean_sumsq(grads, gs, 0, valid)
+    red, ss_gpu = _reduce_gpu(spec, grads, "f16", n, valid, gs=gs)
+    assert np.array_equal(red[:valid].view(np.uint32), mean[:valid].view(np.uint32))
+    assert np.isnan(red[valid:]).all() and abs(ss_gpu - ss) <= 1e-12 * ss
+    acc_want = np.full(n, np.float32(3.0))
+    acc_dev = dev(acc_want.copy())
+    for j in range(3):
+        gj = [gen.gradient(n, 209, j, r, "f16", std=1.0) for r in range(N)]
+        orc.accumulate(gj, acc_want, overwrite=(j == 0), lo=0, hi=valid)
+        ps.ps_step_accumulate(spec, grads_of([dev(g) for g in gj], "f16"), acc_dev.data_ptr(), j == 0,
+                              0, n, valid, stream_handle())
+        torch.cuda.synchronize()
+    assert np.array_equal(host(acc_dev).view(np.uint32), acc_want.view(np.uint32))
+    a, b = grads[0], grads[1]
+    want_d, want_a = orc.diff_sumsq(a, b)
+    ws = torch.empty(ps.ps_verify_workspace_bytes(n * 2), dtype=torch.uint8, device="cuda")
+    out2 = torch.zeros(2, dtype=torch.float64, device="cuda")
+    da, db = dev(a), dev(b)
+    ps.ps_verify_diff_sumsq(da.data_ptr(), db.data_ptr(), ps.PS_F16, n, out2.data_ptr(), 0,
+                            ws.data_ptr(), ws.numel(), stream_handle())
+    torch.cuda.synchronize()
+    sd, sa = [float(x) for x in out2.tolist()]
+    assert abs(sd - want_d) <= 1e-12 * want_d and abs(sa - want_a) <= 1e-12 * want_a
+
+
+def test_f16_bucket_pipeline_and_offload():
+    """The two pipelines with binary16 gradients and parameters."""
+    N, bucket = 4, TILE
+    n = 4 * bucket + 520
+    valid = n - 7
+    _say("binary16 through the bucket pipeline and the offload path n=%d" % n)
+    spec = ps.ps_spec_preset("zero3", N, 3, n * N)
+    grads, state, s, hp = _f16_case(n, N, 211)
+    want = [a.copy() for a in state]
+    orc.step_f32(grads, s, *want, lo=0, hi=valid)
+    # bucket pipeline: the source holds every bucket
+    th, m, v, p = [dev(a) for a in state]
+    src = [dev(g) for g in grads]
+    staging = [torch.zeros(N * bucket * 2, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    copy, comp = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    plan = ps.ps_bucket_plan_t()
+    n_src = -(-n // 512) * 512
+    src = [torch.cat([x, torch.zeros(n_src - n, dtype=x.dtype, device="cuda")]) for x in src]
+    arr = (C.c_void_p * N)(*[x.data_ptr() for x in src])
+    plan.source = C.cast(arr, C.POINTER(C.c_void_p))
+    plan.n_contrib, plan.dtype, plan.bucket_elems, plan.source_elems = N, ps.PS_F16, bucket, n_src
+    plan.staging[0], plan.staging[1] = staging[0].data_ptr(), staging[1].data_ptr()
+    plan.copy_stream, plan.compute_stream = copy.cuda_stream, comp.cuda_stream
+    plan.copy_engine, plan.schedule = ps.PS_COPY_KERNEL, ps.PS_SCHED_AUTO
+    ps.ps_step_update_bucketed(spec, hp, shard_of(th, m, v, p, n, valid), plan)
+    torch.cuda.synchronize()
+    assert assert_state_parity([host(x) for x in (th, m, v, p)], want, "f16 bucketed") == 0
+    # offload: state and FP16 parameters in pinned host memory
+    spec_o = ps.ps_spec_preset("zero_offload", N, 3, n * N)
+    pinned = [torch.from_numpy(a.copy()).pin_memory() for a in state]
+    slots = [torch.zeros(14 * bucket, dtype=torch.uint8, device="cuda") for _ in range(3)]
+    s1, s2, s3 = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    op = ps.ps_offload_plan_t()
+    op.host_master, op.host_m, op.host_v, op.host_param_out = [t.data_ptr() for t in pinned]
+    op.len, op.valid_len, op.bucket_elems, op.n_slots, op.param_dtype = n, valid, bucket, 3, ps.PS_F16
+    for k, t in enumerate(slots):
+        op.slot[k] = t.data_ptr()
+    op.h2d_stream, op.compute_stream, op.d2h_stream = s1.cuda_stream, s2.cuda_stream, s3.cuda_stream
+    ps.ps_step_update_offloaded(spec_o, hp, op, grads_of([dev(g) for g in grads], "f16"))
+    torch.cuda.synchronize()
+    assert assert_state_parity([t.numpy() for t in pinned], want, "f16 offload") == 0
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_widening_of_all_65536_patterns(dtype):
+    """Every 16-bit pattern through the kernels' widening: one replicated contribution, scale
+    1, so the reduced output is the widened value itself (subnormals kept, infinities kept)."""
+    n = 65536
+    _say("widening of all %d %s patterns" % (n, dtype))
+    bits = np.arange(n, dtype=np.uint16)
+    g = bits.view(np.float16).copy() if dtype == "f16" else bits
+    want = g.astype(np.float32) if dtype == "f16" else (bits.astype(np.uint32) << 16).view(np.float32)
+    spec = ps.ps_spec_preset("dp", 4, 0, n)
+    red, _ = _reduce_gpu(spec, [g], dtype, n, n, gs=1.0)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(red), nan)
+    assert np.array_equal(red[~nan].view(np.uint32), want[~nan].view(np.uint32))
+    assert np.array_equal([orc.widen_f16(int(b)) if dtype == "f16" else orc.widen_bf16(int(b)) for b in bits[~nan][::97]],
+                          want[~nan][::97])

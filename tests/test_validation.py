@@ -73,7 +73,7 @@ def test_update_rejects_integrity_violations():
     assert _status(lambda: upd(spec, hp, shard, null, 0, 8)) == ps.PS_EINVAL
     odd = ps.make_grads([FAKE, FAKE + 2, FAKE, FAKE], ps.PS_BF16)
     assert _status(lambda: upd(spec, hp, shard, odd, 0, 8)) == ps.PS_EALIGN
-    badtype = ps.make_grads([FAKE] * 4, 2)
+    badtype = ps.make_grads([FAKE] * 4, 3)
     assert _status(lambda: upd(spec, hp, shard, badtype, 0, 8)) == ps.PS_EINVAL
     one_bf16 = ps.make_grads([FAKE], ps.PS_BF16)       # a single pre-reduced gradient is fp32 only
     assert _status(lambda: upd(spec, hp, shard, one_bf16, 0, 8)) == ps.PS_EINVAL
@@ -287,3 +287,23 @@ def test_device_clip_coefficient_arguments():
     assert _status(lambda: cc(FAKE + 4, 0, 1.0, FAKE)) == ps.PS_EALIGN
     assert _status(lambda: cc(FAKE, FAKE + 4, 1.0, FAKE)) == ps.PS_EALIGN
     assert _status(lambda: cc(FAKE, 0, 1.0, FAKE + 2)) == ps.PS_EALIGN
+
+
+def test_parameter_format_must_match_16_bit_gradients():
+    spec, hp, _, grads_bf16 = _valid()
+    upd = ps.ps_step_update
+    half = ps.ps_shard_t(FAKE, FAKE * 2, FAKE * 3, FAKE * 4, 1024, 1024, ps.PS_F16, 0)
+    assert _status(lambda: upd(spec, hp, half, grads_bf16, 0, 8)) == ps.PS_EUNSUPPORTED   # bf16 grads, FP16 params
+    g16 = ps.make_grads([FAKE * (5 + r) for r in range(4)], ps.PS_F16)
+    upd(spec, hp, half, g16, 0, 0)                                                        # FP16 both: valid, empty
+    bf = ps.ps_shard_t(FAKE, FAKE * 2, FAKE * 3, FAKE * 4, 1024, 1024)
+    assert _status(lambda: upd(spec, hp, bf, g16, 0, 8)) == ps.PS_EUNSUPPORTED            # FP16 grads, bf16 params
+    one32 = ps.make_grads([FAKE], ps.PS_F32)
+    upd(spec, hp, half, one32, 0, 0)                                                      # FP32 gradient: either format
+    upd(spec, hp, bf, one32, 0, 0)
+    bad = ps.ps_shard_t(FAKE, FAKE * 2, FAKE * 3, FAKE * 4, 1024, 1024, ps.PS_F32, 0)
+    assert _status(lambda: upd(spec, hp, bad, one32, 0, 8)) == ps.PS_EINVAL               # parameters are 16-bit
+    bad = ps.ps_shard_t(FAKE, FAKE * 2, FAKE * 3, FAKE * 4, 1024, 1024, ps.PS_F16, 7)
+    assert _status(lambda: upd(spec, hp, bad, one32, 0, 8)) == ps.PS_EINVAL               # reserved
+    g_bad = ps.make_grads([FAKE * (5 + r) for r in range(4)], 3)
+    assert _status(lambda: upd(spec, hp, bf, g_bad, 0, 8)) == ps.PS_EINVAL                # no such type
