@@ -1295,3 +1295,43 @@ def test_widening_of_all_65536_patterns(dtype):
     assert np.array_equal(red[~nan].view(np.uint32), want[~nan].view(np.uint32))
     assert np.array_equal([orc.widen_f16(int(b)) if dtype == "f16" else orc.widen_bf16(int(b)) for b in bits[~nan][::97]],
                           want[~nan][::97])
+
+
+def test_composed_tp_x_dp_step_equals_the_unsharded_update():
+    """Composition (Definition 5, Theorem 6): tensor parallelism of degree T inside, ZeRO-2
+    of degree D across.  Device d = (TP rank, DP rank) per ps_compose_index holds the
+    1/T share of its TP rank and, of that share, the ZeRO shard of its DP rank; its step
+    is the outer specification's step on the share (the convention of ps_compose_cost),
+    reducing the D contributions of its data-parallel group.  All T*D device results put
+    together are the unsharded update of the whole model with N = D."""
+    T, D = 2, 3
+    psi = T * D * (TILE + 264)
+    share, n = psi // T, psi // (T * D)
+    _say("TP(%d) x ZeRO-2(%d): psi=%d, share=%d, shard=%d" % (T, D, psi, share, n))
+    grads = [gen.gradient(psi, 301, 0, d, "bf16") for d in range(D)]         # one per DP replica
+    full = [gen.master(psi, 301), *gen.moments(psi, 301, True), np.zeros(psi, np.uint16)]
+    hpd, hp = hp_of(None, 3)
+    want = [a.copy() for a in full]
+    orc.step_f32(grads, orc.derive_scalars(t=3, n_devices=D, **hpd), *want)
+    got = [np.zeros_like(a) for a in full]
+    cost = None
+    for dev_id in range(T * D):
+        tp_group, tp_rank, dp_group, dp_rank = ps.ps_compose_index(T, D, dev_id)
+        assert dp_group == tp_rank and dp_rank == tp_group
+        spec = ps.ps_spec_preset("zero2", D, dp_rank, share)                 # outer spec on the share
+        c = ps.ps_cost_eval(spec)
+        cc = ps.ps_compose_cost(ps.ps_spec_preset("zero2", D, dp_rank, psi), T)
+        assert (c.shard_len, c.shard_offset, c.peak_total) == (cc.shard_len, cc.shard_offset, cc.peak_total)
+        lo = tp_rank * share + c.shard_offset                                # where this shard sits in the model
+        sl = slice(lo, lo + n)
+        th, m, v = [dev(np.ascontiguousarray(a[sl])) for a in full[:3]]
+        p_share = dev(np.zeros(share, np.uint16))                            # pi_Theta = R inside the DP group
+        gd = [dev(np.ascontiguousarray(g[sl])) for g in grads]
+        ps.ps_step_update(spec, hp, shard_of(th, m, v, p_share, n), grads_of(gd, "bf16"), 0, n,
+                          stream_handle())
+        torch.cuda.synchronize()
+        for k, t_ in enumerate((th, m, v)):
+            got[k][sl] = host(t_)
+        got[3][sl] = host(p_share)[c.shard_offset:c.shard_offset + n]
+    assert assert_state_parity(got, want, "TP x DP") == 0
+    assert np.array_equal(got[3], want[3])
