@@ -6,8 +6,8 @@
  * 16-bit parameters Theta are replicated (R) or sharded-with-gather (S*).
  * Device i reduces the N per-device gradient contributions for its shard in a
  * fixed order, applies mixed-precision Adam with decoupled weight decay to its
- * FP32 master/m/v shard, and writes the updated parameters as bf16 into the
- * buffer the following All-Gather reads.
+ * FP32 master/m/v shard, and writes the updated parameters in their 16-bit
+ * format (bf16 or IEEE binary16) into the buffer the following All-Gather reads.
  *
  * Conventions
  *   - Plain C types only.  Every pointer below is marked HOST or DEVICE.
