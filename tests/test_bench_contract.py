@@ -59,3 +59,23 @@ def test_json_line(workload):
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and c["sample"]
     assert d["value"] > c["value"]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("workload", ["13b_clip", "7b_zero2_f16", "7b_zero1", "7b_accum4", "7b_verify"])
+def test_json_line_of_the_other_workloads(workload):
+    """The other bench.py workloads still run and print one well-formed line (no CPU leg:
+    these shards are large and the oracle baseline is covered above)."""
+    import torch
+    if torch.cuda.mem_get_info()[0] < 120e9:
+        pytest.skip("needs a device with 120 GB free")
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", workload,
+                        "--steps", "2", "--warmup", "1", "--no-cpu-baseline"],
+                       stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=280)
+    assert p.returncode == 0, p.stderr[-2000:]
+    lines = [l for l in p.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert KEYS <= set(d) and d["config"]["workload"] == workload and d["value"] > 0
+    r = d["roofline"]
+    assert r["peak"] == 8000.0 and 0.5 < r["frac"] < 1.0     # an HBM-bound kernel on this part
