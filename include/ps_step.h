@@ -37,9 +37,12 @@
 extern "C" {
 #endif
 
-#define PS_ABI_VERSION 3u
+#define PS_ABI_VERSION 4u
 /* Largest number of gradient contributions one call can reduce. */
 #define PS_MAX_CONTRIB 16u
+
+/* Largest elem_count of one ps_step_reduce_sumsq_static call. */
+#define PS_STATIC_MAX_ELEMS (1ull << 30)
 
 /* Placement modes (Definition 1, Eq. 1-5). */
 enum { PS_R = 0, PS_S = 1, PS_SG = 2 /* S*: sharded with gather */, PS_M = 3, PS_O = 4 };
@@ -403,6 +406,26 @@ ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
                                  int32_t accumulate, void *workspace,
                                  uint64_t workspace_bytes, uint64_t elem_offset,
                                  uint64_t elem_count, uint64_t valid_len, void *stream);
+
+/* ps_step_reduce_sumsq for callers that cannot allocate device memory and so have
+ * no workspace to pass: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and error behaviour
+ * (bit for bit: same kernels, same reduction tree), minus the workspace: the
+ * partial sums live in an array of the library's own, a file-scope __device__
+ * array of 8 MiB + 8 KiB that every device the library runs on holds until the
+ * process ends.  The call allocates and frees nothing.  elem_count may be at most
+ * PS_STATIC_MAX_ELEMS (2^30) per call, else PS_ERANGE and nothing is enqueued; a
+ * longer range goes out as several calls in order, accumulate != 0 from the second
+ * on.  Nothing in the array has to start at zero (every partial sum is written
+ * before it is read), so it is never cleared.  All calls on one device share that
+ * device's array: calls whose work overlaps on one device (two streams, two
+ * threads) race on it; calls on one stream, or ordered by events, do not.  The first
+ * call on each device looks the array up with the runtime (no allocation either);
+ * make that call outside a stream capture. */
+ps_status_t ps_step_reduce_sumsq_static(const ps_spec_t *spec, const ps_grads_t *grads,
+                                        double grad_scale, float *reduced_out, double *sumsq_out,
+                                        int32_t accumulate, uint64_t elem_offset,
+                                        uint64_t elem_count, uint64_t valid_len, void *stream);
 
 /* ---- verification protocol (Section 7.1) ---- */
 

@@ -24,15 +24,17 @@ __all__ = [
     "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
     "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum",
     "ps_select_strategy", "ps_compose_index", "ps_compose_cost", "ps_step_update_offloaded",
-    "ps_step_clip_coef", "EXPORTED_SYMBOLS", "ABI_VERSION",
+    "ps_step_clip_coef", "ps_step_reduce_sumsq_static", "PS_STATIC_MAX_ELEMS",
+    "EXPORTED_SYMBOLS", "ABI_VERSION",
 ]
 
-ABI_VERSION = 3   # PS_ABI_VERSION of include/ps_step.h this binding mirrors
+ABI_VERSION = 4   # PS_ABI_VERSION of include/ps_step.h this binding mirrors
 PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
 PS_BF16, PS_F32, PS_F16 = 0, 1, 2
 PS_COPY_KERNEL, PS_COPY_MEMCPY = 0, 1
 PS_SCHED_AUTO, PS_SCHED_OVERLAP, PS_SCHED_ALTERNATE = 0, 1, 2
 PS_MAX_CONTRIB = 16
+PS_STATIC_MAX_ELEMS = 1 << 30
 (PS_OK, PS_EINVAL, PS_EUNSUPPORTED, PS_EALIGN, PS_ERANGE, PS_ENODEVICE, PS_EHIP) = range(7)
 
 EXPORTED_SYMBOLS = (
@@ -41,7 +43,7 @@ EXPORTED_SYMBOLS = (
     "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
     "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum",
     "ps_select_strategy", "ps_compose_index", "ps_compose_cost", "ps_step_update_offloaded",
-    "ps_step_clip_coef",
+    "ps_step_clip_coef", "ps_step_reduce_sumsq_static",
 )
 
 
@@ -169,6 +171,10 @@ def library():
                                            C.c_double, C.c_void_p, C.c_void_p, C.c_int32,
                                            C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint64,
                                            C.c_uint64, C.c_void_p]
+        L.ps_step_reduce_sumsq_static.restype = C.c_int
+        L.ps_step_reduce_sumsq_static.argtypes = [C.POINTER(ps_spec_t), C.POINTER(ps_grads_t),
+                                                  C.c_double, C.c_void_p, C.c_void_p, C.c_int32,
+                                                  C.c_uint64, C.c_uint64, C.c_uint64, C.c_void_p]
         L.ps_step_accumulate.restype = C.c_int
         L.ps_step_accumulate.argtypes = [C.POINTER(ps_spec_t), C.POINTER(ps_grads_t), C.c_void_p,
                                          C.c_int32, C.c_uint64, C.c_uint64, C.c_uint64,
@@ -302,6 +308,14 @@ def ps_step_reduce_sumsq(spec, grads, grad_scale, reduced_out, sumsq_out, accumu
                                           reduced_out or None, sumsq_out or None,
                                           int(accumulate), workspace or None, workspace_bytes,
                                           elem_offset, elem_count, valid_len, stream or None))
+
+
+def ps_step_reduce_sumsq_static(spec, grads, grad_scale, reduced_out, sumsq_out, accumulate,
+                                elem_offset, elem_count, valid_len, stream=0):
+    _check(library().ps_step_reduce_sumsq_static(_ref(spec), _ref(grads), grad_scale,
+                                                 reduced_out or None, sumsq_out or None,
+                                                 int(accumulate), elem_offset, elem_count,
+                                                 valid_len, stream or None))
 
 
 def ps_step_accumulate(spec, grads, accum, overwrite, elem_offset, elem_count, valid_len,

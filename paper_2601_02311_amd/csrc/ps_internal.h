@@ -48,6 +48,9 @@ int launch_clip_coef(const double *sumsq_local, const double *sumsq_others, doub
 int launch_reduce_sumsq(int dtype, uint32_t n_contrib, const ContribPtrs &g, float gs,
                         float *reduced_out, uint64_t count, double *partials,
                         double *sumsq_out, int accumulate, void *stream);
+// This device's copy of the library's static partial-sum array (looked up on the first
+// call per device) and its capacity in doubles; hipError_t as int.
+int static_reduce_scratch(double **out, uint64_t *doubles);
 int launch_accumulate(int dtype, uint32_t n_contrib, const ContribPtrs &g, float *accum,
                       int overwrite, uint64_t count, void *stream);
 // Verification scans.  `slots` 8-byte slots of workspace as verify_workspace_slots() says.

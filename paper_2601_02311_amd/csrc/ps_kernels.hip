@@ -3,6 +3,8 @@
 // reduction tree of the sum of squares is the same on every run.
 #include "ps_kernel_templates.h"
 
+#include <mutex>
+
 namespace ps {
 
 // Dynamic LDS requested by the streaming launches.  The kernels never touch it:
@@ -303,6 +305,42 @@ int launch_reduce_sumsq(int dtype, uint32_t n_contrib, const ContribPtrs &g, flo
                                          sumsq_out, accumulate, st);
     return launch_reduce_t<float>(n_contrib, g, gs, reduced_out, count, partials, sumsq_out,
                                   accumulate, st);
+}
+
+// ---- partial sums for callers that cannot allocate ----
+// The workspace of one reduce pass over PS_STATIC_MAX_ELEMS elements, held by every
+// device the library runs on until the process ends (8 MiB + 8 KiB).  Host code never
+// uses the array's name as an address: it asks the runtime once per device, with that
+// device current, and passes the pointer it got to the kernels like any workspace.
+constexpr uint64_t kScratchDoubles =
+    kFoldBlocks + PS_STATIC_MAX_ELEMS / ((uint64_t)kTileElems * kReduceTilesPerGroup) + 1;
+static __device__ __align__(256) double scratch[kScratchDoubles];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static double *scratch_ptr[kMaxDevices]; // per device: where its copy of `scratch` lives
+
+int static_reduce_scratch(double **out, uint64_t *doubles)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return (int)e;
+    if (dev < 0 || dev >= kMaxDevices)
+        return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        double *p = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch));
+        if (e != hipSuccess)
+            return (int)e;
+        if (!p)
+            return (int)hipErrorInvalidSymbol;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    *doubles = kScratchDoubles;
+    return 0;
 }
 
 int launch_clip_coef(const double *sumsq_local, const double *sumsq_others, double max_norm,

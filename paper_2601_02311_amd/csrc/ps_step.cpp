@@ -256,6 +256,90 @@ ps_status_t check_param_dtype(int32_t param_dtype, int32_t reserved, int32_t gra
     return PS_OK;
 }
 
+// Both reduce entry points: `workspace` is the caller's, or NULL for the library's
+// static per-device array (then workspace_bytes is ignored and nothing is allocated).
+ps_status_t reduce_sumsq_checked(const ps_spec_t *spec, const ps_grads_t *grads, double grad_scale,
+                                 float *reduced_out, double *sumsq_out, int32_t accumulate,
+                                 void *workspace, uint64_t workspace_bytes, uint64_t elem_offset,
+                                 uint64_t elem_count, uint64_t valid_len, void *stream)
+{
+    ps_status_t st;
+    if ((st = check_path(spec)) != PS_OK)
+        return st;
+    if (replicated_grad(spec) && grads && grads->n_contrib != 1) {
+        set_error("under pi_G = R the gradient is one all-reduced buffer");
+        return PS_EINVAL;
+    }
+    if (!grads || !sumsq_out) {
+        set_error("grads or sumsq_out is NULL");
+        return PS_EINVAL;
+    }
+    if (std::isnan(grad_scale)) {
+        set_error("grad_scale is NaN");
+        return PS_ERANGE;
+    }
+    if (workspace && workspace_bytes < ps_workspace_bytes(elem_count)) {
+        set_error("workspace of %llu bytes is smaller than ps_workspace_bytes(%llu) = %llu",
+                  (unsigned long long)workspace_bytes, (unsigned long long)elem_count,
+                  (unsigned long long)ps_workspace_bytes(elem_count));
+        return PS_ERANGE;
+    }
+    if ((workspace && !aligned16(workspace)) || (reinterpret_cast<uintptr_t>(sumsq_out) & 7u) ||
+        (reduced_out && !aligned16(reduced_out))) {
+        set_error("workspace, sumsq_out or reduced_out is misaligned");
+        return PS_EALIGN;
+    }
+    const bool z1 = replicated_grad(spec);
+    if ((st = check_contribs(grads->contrib, grads->n_contrib, grads->dtype, spec->n_devices,
+                             "contribution", z1)) != PS_OK)
+        return st;
+    uint64_t padded, off, len, valid;
+    if ((st = step_geometry(spec, &padded, &off, &len, &valid)) != PS_OK ||
+        (st = check_range(elem_offset, elem_count, len)) != PS_OK)
+        return st;
+    if (valid_len > len) {
+        set_error("valid_len exceeds the shard length");
+        return PS_ERANGE;
+    }
+    if (z1 && off % 8 != 0) {
+        set_error("shard offset %llu into the replicated gradient is not a multiple of 8",
+                  (unsigned long long)off);
+        return PS_EALIGN;
+    }
+    if ((st = need_device()) != PS_OK)
+        return st;
+    if (!workspace) {
+        double *own = nullptr;
+        uint64_t doubles = 0;
+        int se = static_reduce_scratch(&own, &doubles);
+        if (se != 0)
+            return hip_fail((hipError_t)se, "looking up the static partial-sum array");
+        if (doubles < reduce_workspace_doubles(elem_count)) {
+            set_error("static partial-sum array too small for %llu elements",
+                      (unsigned long long)elem_count);
+            return PS_ERANGE;
+        }
+        workspace = own;
+    }
+
+    const uint64_t count = clamp_count(elem_offset, elem_count, valid_len);
+    const float gs = (float)(grad_scale > 0.0 ? grad_scale : 1.0 / (double)spec->n_devices);
+    ContribPtrs g;
+    std::memset(&g, 0, sizeof g);
+    for (uint32_t r = 0; r < grads->n_contrib; ++r)
+        g.p[r] = grads->contrib[r];
+    if (z1)
+        g.p[0] = reinterpret_cast<const char *>(g.p[0]) +
+                 (off + elem_offset) * elem_bytes(grads->dtype);
+    int e = launch_reduce_sumsq(grads->dtype, grads->n_contrib, g, gs,
+                                reduced_out ? reduced_out + elem_offset : nullptr, count,
+                                reinterpret_cast<double *>(workspace), sumsq_out, accumulate,
+                                stream);
+    if (e != 0)
+        return hip_fail((hipError_t)e, "reduce kernel launch");
+    return PS_OK;
+}
+
 } // namespace
 
 extern "C" {
@@ -399,68 +483,29 @@ ps_status_t ps_step_reduce_sumsq(const ps_spec_t *spec, const ps_grads_t *grads,
                                  void *stream)
 {
     clear_error();
-    ps_status_t st;
-    if ((st = check_path(spec)) != PS_OK)
-        return st;
-    if (replicated_grad(spec) && grads && grads->n_contrib != 1) {
-        set_error("under pi_G = R the gradient is one all-reduced buffer");
+    if (!workspace) {
+        set_error("workspace is NULL");
         return PS_EINVAL;
     }
-    if (!grads || !sumsq_out || !workspace) {
-        set_error("grads, sumsq_out or workspace is NULL");
-        return PS_EINVAL;
-    }
-    if (std::isnan(grad_scale)) {
-        set_error("grad_scale is NaN");
-        return PS_ERANGE;
-    }
-    if (workspace_bytes < ps_workspace_bytes(elem_count)) {
-        set_error("workspace of %llu bytes is smaller than ps_workspace_bytes(%llu) = %llu",
-                  (unsigned long long)workspace_bytes, (unsigned long long)elem_count,
-                  (unsigned long long)ps_workspace_bytes(elem_count));
-        return PS_ERANGE;
-    }
-    if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(sumsq_out) & 7u) ||
-        (reduced_out && !aligned16(reduced_out))) {
-        set_error("workspace, sumsq_out or reduced_out is misaligned");
-        return PS_EALIGN;
-    }
-    const bool z1 = replicated_grad(spec);
-    if ((st = check_contribs(grads->contrib, grads->n_contrib, grads->dtype, spec->n_devices,
-                             "contribution", z1)) != PS_OK)
-        return st;
-    uint64_t padded, off, len, valid;
-    if ((st = step_geometry(spec, &padded, &off, &len, &valid)) != PS_OK ||
-        (st = check_range(elem_offset, elem_count, len)) != PS_OK)
-        return st;
-    if (valid_len > len) {
-        set_error("valid_len exceeds the shard length");
-        return PS_ERANGE;
-    }
-    if (z1 && off % 8 != 0) {
-        set_error("shard offset %llu into the replicated gradient is not a multiple of 8",
-                  (unsigned long long)off);
-        return PS_EALIGN;
-    }
-    if ((st = need_device()) != PS_OK)
-        return st;
-
-    const uint64_t count = clamp_count(elem_offset, elem_count, valid_len);
-    const float gs = (float)(grad_scale > 0.0 ? grad_scale : 1.0 / (double)spec->n_devices);
-    ContribPtrs g;
-    std::memset(&g, 0, sizeof g);
-    for (uint32_t r = 0; r < grads->n_contrib; ++r)
-        g.p[r] = grads->contrib[r];
-    if (z1)
-        g.p[0] = reinterpret_cast<const char *>(g.p[0]) +
-                 (off + elem_offset) * elem_bytes(grads->dtype);
-    int e = launch_reduce_sumsq(grads->dtype, grads->n_contrib, g, gs,
-                                reduced_out ? reduced_out + elem_offset : nullptr, count,
-                                reinterpret_cast<double *>(workspace), sumsq_out, accumulate,
+    return reduce_sumsq_checked(spec, grads, grad_scale, reduced_out, sumsq_out, accumulate,
+                                workspace, workspace_bytes, elem_offset, elem_count, valid_len,
                                 stream);
-    if (e != 0)
-        return hip_fail((hipError_t)e, "reduce kernel launch");
-    return PS_OK;
+}
+
+ps_status_t ps_step_reduce_sumsq_static(const ps_spec_t *spec, const ps_grads_t *grads,
+                                        double grad_scale, float *reduced_out, double *sumsq_out,
+                                        int32_t accumulate, uint64_t elem_offset,
+                                        uint64_t elem_count, uint64_t valid_len, void *stream)
+{
+    clear_error();
+    if (elem_count > PS_STATIC_MAX_ELEMS) {
+        set_error("elem_count %llu exceeds PS_STATIC_MAX_ELEMS = %llu: call once per range of at "
+                  "most that many elements, with accumulate set from the second on",
+                  (unsigned long long)elem_count, (unsigned long long)PS_STATIC_MAX_ELEMS);
+        return PS_ERANGE;
+    }
+    return reduce_sumsq_checked(spec, grads, grad_scale, reduced_out, sumsq_out, accumulate,
+                                nullptr, 0, elem_offset, elem_count, valid_len, stream);
 }
 
 ps_status_t ps_step_clip_coef(const double *sumsq_local, const double *sumsq_others,
