@@ -5,9 +5,12 @@
 
 A step is one pass of the whole hot path over one batch of synthetic gradient
 contributions for one device's shard.  The default workload is the 70B ZeRO-3
-shard (8.75e9 elements, N = 8): 33 buckets of 2^28 elements staged on a copy
-stream while the update kernel runs on the compute stream.  All inputs are
-resident in HBM before the timed region starts.  Prints ONE JSON line.
+shard (8.75e9 elements, N = 8) updated bucket by bucket, 33 buckets of 2^28
+elements.  All inputs are resident in HBM before the timed region starts: the
+eight contributions of every bucket (140 GB, every element distinct, nothing
+cache-assisted), which the bucket loop reads where they lie.  The staged
+two-stream pipeline for contributions that have to be moved first is timed by
+--copy-engine kernel|memcpy and by --extras.  Prints ONE JSON line.
 """
 import argparse
 import ctypes as C
@@ -49,9 +52,18 @@ def main():
     ap.add_argument("--workload", default="70b_zero3",
                     choices=["tiny", "gpt2s", "7b_zero2", "70b_zero3", "13b_clip", "7b_zero1",
                              "7b_accum4", "7b_verify", "7b_offload", "7b_zero2_f16"])
-    ap.add_argument("--pool-elems", type=int, default=1 << 21,
-                    help="elements per contribution of the resident, repeating bucket source")
-    ap.add_argument("--copy-engine", choices=["kernel", "memcpy"], default="kernel")
+    ap.add_argument("--pool-elems", type=int, default=0,
+                    help="elements per contribution of the resident bucket source; 0 (default): the "
+                         "whole shard length, every bucket distinct; shorter: a pool that repeats")
+    ap.add_argument("--copy-engine", choices=["none", "kernel", "memcpy"], default="none",
+                    help="none: the update reads each bucket of the resident source in place; kernel, "
+                         "memcpy: the two-stream pipeline that stages each bucket first")
+    ap.add_argument("--alloc", choices=["arena", "plain"], default="arena",
+                    help="bucketed workload with the whole source resident: arena = flat buffers whose "
+                         "physical memory is created bucket by bucket (ps_arena_create), so that a "
+                         "bucket's streams lie close together; plain = one allocation per buffer")
+    ap.add_argument("--waves-per-cu", type=int, default=0,
+                    help="override the update kernel's residency cap (measurement aid; 0 = library's choice)")
     ap.add_argument("--schedule", choices=["auto", "overlap", "alternate"], default="auto")
     ap.add_argument("--source-host", action="store_true",
                     help="keep the bucket source in pinned host memory (the step is then bound by "
@@ -99,14 +111,29 @@ def main():
     log("workload %s: shard of %d elements, N=%d, %s gradients" % (w.name, n, N, w.grad_dtype))
 
     t_setup = time.time()
-    master, m, v = dgen.workload_state(w)
+    free_at_start = torch.cuda.mem_get_info()[0]
+    bucketed = w.bucket_elems > 0
+    arena = None
     out_len = cost.psi_padded if spec.theta == ps.PS_R else n
-    out = torch.zeros(out_len, dtype=ptd, device="cuda")
+    if (bucketed and args.alloc == "arena" and not args.pool_elems and not args.source_host
+            and out_len == n):
+        # contributions 0..N-1, master, m, v, parameters: flat, physically interleaved by bucket
+        try:
+            arena = ps.ps_arena_create(n, args.bucket_elems or w.bucket_elems, [esz] * N + [4, 4, 4, 2])
+        except ps.PsError as err:
+            log("arena not created (%s): plain allocations instead" % err.detail)
+    if arena is not None:
+        a_buf = [ps.ps_arena_buffer(arena, k) for k in range(N + 4)]
+        master, m, v = dgen.workload_state(w, into=[dgen.as_tensor(a_buf[N + j], n, torch.float32)
+                                                    for j in range(3)])
+        out = dgen.as_tensor(a_buf[N + 3], n, ptd).zero_()
+    else:
+        master, m, v = dgen.workload_state(w)
+        out = torch.zeros(out_len, dtype=ptd, device="cuda")
     shard = ps.ps_shard_t(master.data_ptr(), m.data_ptr(), v.data_ptr(), out.data_ptr(), n,
                           cost.valid_len, pdt, 0)
     compute = torch.cuda.Stream()
     copy = torch.cuda.Stream()
-    bucketed = w.bucket_elems > 0
     step_no = [w.first_step]
 
     def hp(clip_coef=0.0, grad_scale=0.0):
@@ -115,35 +142,61 @@ def main():
         return ps.ps_adamw_t(w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, step_no[0],
                              grad_scale, clip_coef)
 
-    kernel_ms = []          # per-launch durations of the dominant kernel in the timed region
+    kernel_ms = []          # per-launch durations of the dominant kernel
+    if args.waves_per_cu:
+        ps.ps_probe_set_update_residency(args.waves_per_cu)
     if bucketed:
         B = args.bucket_elems or w.bucket_elems
         n_b = -(-n // B)
-        pool = [dgen.fill_gradient_(torch.empty(args.pool_elems, dtype=tdt, device="cuda"),
+        staged = args.copy_engine != "none"
+        # The source: every bucket of every contribution resident and distinct (the whole shard
+        # length), unless a shorter pool is asked for or the device cannot hold it.
+        pool_elems = args.pool_elems or n
+        need = N * pool_elems * esz + (2 * N * B * esz if staged or args.extras else 0) + (2 << 30)
+        free_now = torch.cuda.mem_get_info()[0]
+        if not args.pool_elems and need > free_now and arena is None:
+            pool_elems = 2 * B
+            log("source of %d elements per contribution does not fit (%.0f GB free): using a "
+                "pool of two buckets that repeats" % (n, free_now / 1e9))
+        pool_elems = -(-pool_elems // 512) * 512
+        pool = [dgen.fill_gradient_(dgen.as_tensor(a_buf[r], n, tdt) if arena is not None else
+                                    torch.empty(pool_elems, dtype=tdt, device="cuda"),
                                     w.seed, w.first_step, r, w.grad_std, w.outlier_frac,
                                     w.outlier_mult, w.student_t_dof) for r in range(N)]
         if args.source_host:
             pool = [p.cpu().pin_memory() for p in pool]
-        staging = [torch.empty(N * B, dtype=tdt, device="cuda") for _ in range(2)]
+        staging = ([torch.empty(N * B, dtype=tdt, device="cuda") for _ in range(2)]
+                   if staged or args.extras else None)
         src = (C.c_void_p * N)(*[p.data_ptr() for p in pool])
         ms = (C.c_float * n_b)()
         plan = ps.ps_bucket_plan_t()
         plan.source = C.cast(src, C.POINTER(C.c_void_p))
         plan.n_contrib, plan.dtype = N, dt
-        plan.bucket_elems, plan.source_elems = B, args.pool_elems
-        plan.copy_engine = ps.PS_COPY_KERNEL if args.copy_engine == "kernel" else ps.PS_COPY_MEMCPY
+        plan.bucket_elems, plan.source_elems = B, pool_elems
+        plan.copy_engine = {"none": ps.PS_COPY_NONE, "kernel": ps.PS_COPY_KERNEL,
+                            "memcpy": ps.PS_COPY_MEMCPY}[args.copy_engine]
         plan.schedule = {"auto": ps.PS_SCHED_AUTO, "overlap": ps.PS_SCHED_OVERLAP,
                          "alternate": ps.PS_SCHED_ALTERNATE}[args.schedule]
-        plan.staging[0], plan.staging[1] = staging[0].data_ptr(), staging[1].data_ptr()
+        if staging:
+            plan.staging[0], plan.staging[1] = staging[0].data_ptr(), staging[1].data_ptr()
         plan.copy_stream, plan.compute_stream = copy.cuda_stream, compute.cuda_stream
-        plan.kernel_ms, plan.kernel_ms_len = ms, n_b
         launches_per_step = n_b
 
         def step(record):
+            # the timed region runs the asynchronous loop: no per-launch events, no host wait
+            plan.kernel_ms, plan.kernel_ms_len = None, 0
             ps.ps_step_update_bucketed(spec, hp(), shard, plan)
-            if record:
-                kernel_ms.extend(ms[b] for b in range(n_b))   # every launch, the short last bucket too
             step_no[0] += 1
+
+        def timed_pass(steps):
+            """Per-launch durations of the update kernel (HIP events recorded by the library on
+            the compute stream around each bucket's launch), in a pass of its own."""
+            plan.kernel_ms, plan.kernel_ms_len = ms, n_b
+            for _ in range(steps):
+                ps.ps_step_update_bucketed(spec, hp(), shard, plan)
+                kernel_ms.extend(ms[b] for b in range(n_b))   # every launch, the short last bucket too
+                step_no[0] += 1
+            plan.kernel_ms, plan.kernel_ms_len = None, 0
         elems_per_launch = cost.valid_len / n_b               # average over the launches of a step
     else:
         zero1, k_mb = w.strategy == "zero1", w.micro_batches
@@ -201,7 +254,7 @@ def main():
             step_no[0] += 1
     torch.cuda.synchronize()
     log("setup %.1f s, %.1f GB allocated" % (time.time() - t_setup,
-                                             torch.cuda.memory_allocated() / 1e9))
+                                             (free_at_start - torch.cuda.mem_get_info()[0]) / 1e9))
 
     for _ in range(args.warmup):
         step(False)
@@ -212,7 +265,9 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    if not bucketed:
+    if bucketed:
+        timed_pass(args.steps)
+    else:
         kernel_ms.extend(a.elapsed_time(b) for a, b in ev)
     elems_per_step = cost.valid_len
     value = elems_per_step / (ms_per_step * 1e-3)
@@ -222,37 +277,33 @@ def main():
     log("%.3f ms/step, %.3e elements/s; dominant kernel %.3f ms avg -> %.0f GB/s" %
         (ms_per_step, value, avg_ms, achieved))
 
-    # The same kernel alone on the device (no staging copy in flight) and a plain copy
-    # of equal footprint, as yardsticks; neither is the headline value.
+    # Other ways through the same bucket loop on the same source, as context; none of them is
+    # the headline value: the pipeline that stages each bucket first (copy kernel taking turns
+    # with the update, or side by side; DMA copies), and the loop that reads in place.
     extras = {}
     if bucketed and args.extras:
-        gs = ps.make_grads([staging[0].data_ptr() + r * B * esz for r in range(N)], dt)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 8
-        with torch.cuda.stream(compute):
-            ps.ps_step_update(spec, hp(), shard, gs, 0, B, compute.cuda_stream)
-            e0.record(compute)
-            for k in range(reps):
-                ps.ps_step_update(spec, hp(), shard, gs, (k % 8) * B, B, compute.cuda_stream)
-            e1.record(compute)
-        torch.cuda.synchronize()
-        iso_ms = e0.elapsed_time(e1) / reps
-        extras["kernel_alone"] = {"ms": iso_ms, "GBps": bpe * B / (iso_ms * 1e-3) / 1e9,
-                                  "note": "update kernel on one bucket, nothing else on the device"}
-        # the other schedule of the same pipeline, for comparison
-        other = ps.PS_SCHED_OVERLAP if plan.schedule != ps.PS_SCHED_OVERLAP else ps.PS_SCHED_ALTERNATE
-        keep, plan.schedule = plan.schedule, other
-        step(False)
-        torch.cuda.synchronize()
-        o0 = time.perf_counter()
-        for _ in range(3):
+        variants = [("in_place", ps.PS_COPY_NONE, ps.PS_SCHED_AUTO),
+                    ("staged_copy_kernel_alternate", ps.PS_COPY_KERNEL, ps.PS_SCHED_ALTERNATE),
+                    ("staged_copy_kernel_overlap", ps.PS_COPY_KERNEL, ps.PS_SCHED_OVERLAP)]
+        if pool_elems % B == 0:
+            variants.append(("staged_memcpy_overlap", ps.PS_COPY_MEMCPY, ps.PS_SCHED_OVERLAP))
+        keep = (plan.copy_engine, plan.schedule)
+        for name, eng, sch in variants:
+            plan.copy_engine, plan.schedule = eng, sch
             step(False)
-        torch.cuda.synchronize()
-        o_ms = (time.perf_counter() - o0) * 1e3 / 3
-        plan.schedule = keep
-        extras["other_schedule"] = {"schedule": "overlap" if other == ps.PS_SCHED_OVERLAP else "alternate",
-                                    "ms_per_step": o_ms,
-                                    "kernel_ms_avg": sum(ms[b] for b in range(n_b - 1)) / (n_b - 1)}
+            torch.cuda.synchronize()
+            o0 = time.perf_counter()
+            for _ in range(3):
+                step(False)
+            torch.cuda.synchronize()
+            o_ms = (time.perf_counter() - o0) * 1e3 / 3
+            before = len(kernel_ms)
+            timed_pass(1)
+            k_ms = kernel_ms[before:]
+            del kernel_ms[before:]
+            extras[name] = {"ms_per_step": o_ms, "step_GBps": bpe * elems_per_step / (o_ms * 1e-3) / 1e9,
+                            "update_kernel_ms_avg": sum(k_ms) / len(k_ms)}
+        plan.copy_engine, plan.schedule = keep
     # One plain copy of known size: the yardstick that hardware byte counters are scaled by.
     nbytes = min(master.numel() * 4, 1 << 32)
     reps = 5 if args.extras else 1
@@ -275,11 +326,20 @@ def main():
         "config": {"workload": w.name, "psi": w.psi, "n_devices": N, "shard_index": w.shard_index,
                    "shard_elems": n, "grad_dtype": w.grad_dtype, "param_dtype": w.param_dtype, "strategy": w.strategy,
                    "bucket_elems": (B if bucketed else 0), "launches_per_step": launches_per_step,
-                   "bucket_source": ("resident pool of %d elements per contribution, repeating; "
-                                     "copy engine %s, schedule %s" %
-                                     (args.pool_elems, args.copy_engine, args.schedule)) +
-                                    (" (source in pinned HOST memory)" if args.source_host else "")
+                   "bucket_source": ((("every bucket of every contribution resident in HBM and distinct "
+                                       "(%d elements per contribution, %.1f GB in all)"
+                                       % (pool_elems, N * pool_elems * esz / 1e9)) if pool_elems >= n else
+                                      ("resident pool of %d elements per contribution (%.2f GB in all), "
+                                       "repeating" % (pool_elems, N * pool_elems * esz / 1e9))) +
+                                     ("; read in place by the update kernel, one launch per bucket"
+                                      if args.copy_engine == "none" else
+                                      "; staged per bucket into two slots: copy engine %s, schedule %s"
+                                      % (args.copy_engine, args.schedule)) +
+                                     (" (source in pinned HOST memory)" if args.source_host else ""))
                                     if bucketed else None,
+                   "allocation": (("arena: flat buffers, physical memory created bucket by bucket"
+                                   if arena is not None else "one plain allocation per buffer")
+                                  if bucketed else None),
                    "clip_coefficient": (("host (one sync per step)" if args.clip_on_host
                                          else "device (no host round trip)") if clip else None),
                    "bytes_per_elem": bpe, "step_GBps": bpe * elems_per_step / (ms_per_step * 1e-3) / 1e9,
@@ -288,15 +348,25 @@ def main():
                    "memory_bus_bits": info.memory_bus_bits, "hbm_total_GB": info.total_bytes / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBS,
+                     # the same bytes over the wall time of whole steps (the target metric);
+                     # `achieved` and `frac` above are the dominant kernel's own launches
+                     "step_achieved": bpe * elems_per_step / (ms_per_step * 1e-3) / 1e9,
+                     "step_frac": bpe * elems_per_step / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
                      "traffic": measured_traffic(w, elems_per_launch),
                      "kernel": ("reduce_sumsq_tiles+update_tiles" if clip else
                                 "accumulate_tiles x%d + update_tiles" % w.micro_batches
                                 if w.micro_batches > 1 else "update_tiles"),
                      "elems_per_launch": elems_per_launch, "avg_launch_ms": avg_ms,
                      "median_launch_ms": sorted(kernel_ms)[len(kernel_ms) // 2],
-                     "best_launch_ms": min(kernel_ms), "launches_timed": len(kernel_ms)},
+                     "best_launch_ms": min(kernel_ms), "launches_timed": len(kernel_ms),
+                     "launch_timing": ("a pass of %d steps after the timed region, HIP events around "
+                                       "each launch on the compute stream" % args.steps) if bucketed
+                                      else "HIP events around each step's launches in the timed region"},
         "extras": extras,
     }
+    if arena is not None:       # every view of its buffers is dead from here on
+        torch.cuda.synchronize()
+        ps.ps_arena_destroy(arena)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, bpe, args.cpu_baseline_seconds)
     print(json.dumps(result), flush=True)
@@ -423,10 +493,10 @@ def verify_bench(args):
 
 def measured_traffic(w, elems_per_launch):
     """HBM bytes per launch of the dominant kernel from the committed hardware-counter summary
-    (profiles/update_tiles__70b_zero3__hbm_traffic.txt).  None when there is no summary for this workload
-    or when the kernel sources have changed since the counters were taken."""
+    (profiles/update_tiles__<workload>__hbm_traffic.txt).  None when there is no summary for this
+    workload or when the kernel sources have changed since the counters were taken."""
     import hashlib
-    path = os.path.join(ROOT, "profiles", "update_tiles__70b_zero3__hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", "update_tiles__%s__hbm_traffic.txt" % w.name)
     if not os.path.exists(path):
         return None
     kv = {}
@@ -451,7 +521,7 @@ def cpu_baseline(w, bpe, seconds=15.0):
     from synth import host as gen
 
     cores = min(16, os.cpu_count() or 1)
-    sample = min(w.shard_len, 1 << 25)
+    sample = min(w.shard_len, 1 << 26)
     grads = [gen.gradient(sample, w.seed, w.first_step, r, w.grad_dtype, w.grad_std * w.loss_scale,
                           w.outlier_frac, w.outlier_mult, w.student_t_dof)
              for r in range(w.n_devices)]

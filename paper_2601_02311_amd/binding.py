@@ -15,7 +15,7 @@ import torch  # noqa: F401
 from . import build as _build
 
 __all__ = [
-    "PS_R", "PS_S", "PS_SG", "PS_M", "PS_O", "PS_BF16", "PS_F32", "PS_F16", "PS_MAX_CONTRIB", "PS_COPY_KERNEL", "PS_COPY_MEMCPY", "PS_SCHED_AUTO", "PS_SCHED_OVERLAP", "PS_SCHED_ALTERNATE",
+    "PS_R", "PS_S", "PS_SG", "PS_M", "PS_O", "PS_BF16", "PS_F32", "PS_F16", "PS_MAX_CONTRIB", "PS_COPY_KERNEL", "PS_COPY_MEMCPY", "PS_COPY_NONE", "PS_SCHED_AUTO", "PS_SCHED_OVERLAP", "PS_SCHED_ALTERNATE",
     "PS_OK", "PS_EINVAL", "PS_EUNSUPPORTED", "PS_EALIGN", "PS_ERANGE", "PS_ENODEVICE", "PS_EHIP",
     "PsError", "ps_spec_t", "ps_cost_t", "ps_adamw_t", "ps_shard_t", "ps_grads_t",
     "ps_bucket_plan_t", "ps_offload_plan_t", "ps_device_info_t", "library", "library_path",
@@ -25,13 +25,14 @@ __all__ = [
     "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum",
     "ps_select_strategy", "ps_compose_index", "ps_compose_cost", "ps_step_update_offloaded",
     "ps_step_clip_coef", "ps_step_reduce_sumsq_static", "PS_STATIC_MAX_ELEMS",
+    "ps_probe_set_update_residency", "ps_arena_create", "ps_arena_buffer", "ps_arena_destroy",
     "EXPORTED_SYMBOLS", "ABI_VERSION",
 ]
 
 ABI_VERSION = 4   # PS_ABI_VERSION of include/ps_step.h this binding mirrors
 PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
 PS_BF16, PS_F32, PS_F16 = 0, 1, 2
-PS_COPY_KERNEL, PS_COPY_MEMCPY = 0, 1
+PS_COPY_KERNEL, PS_COPY_MEMCPY, PS_COPY_NONE = 0, 1, 2
 PS_SCHED_AUTO, PS_SCHED_OVERLAP, PS_SCHED_ALTERNATE = 0, 1, 2
 PS_MAX_CONTRIB = 16
 PS_STATIC_MAX_ELEMS = 1 << 30
@@ -43,7 +44,8 @@ EXPORTED_SYMBOLS = (
     "ps_step_reduce_sumsq", "ps_step_accumulate", "ps_probe_copy", "ps_clip_coef",
     "ps_verify_workspace_bytes", "ps_verify_diff_sumsq", "ps_verify_checksum",
     "ps_select_strategy", "ps_compose_index", "ps_compose_cost", "ps_step_update_offloaded",
-    "ps_step_clip_coef", "ps_step_reduce_sumsq_static",
+    "ps_step_clip_coef", "ps_step_reduce_sumsq_static", "ps_probe_set_update_residency",
+    "ps_arena_create", "ps_arena_buffer", "ps_arena_destroy",
 )
 
 
@@ -188,6 +190,15 @@ def library():
         L.ps_verify_checksum.restype = C.c_int
         L.ps_verify_checksum.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_int32,
                                          C.c_void_p, C.c_uint64, C.c_void_p]
+        L.ps_arena_create.restype = C.c_int
+        L.ps_arena_create.argtypes = [C.c_uint64, C.c_uint64, C.POINTER(C.c_uint32), C.c_uint32,
+                                      C.POINTER(C.c_void_p)]
+        L.ps_arena_buffer.restype = C.c_void_p
+        L.ps_arena_buffer.argtypes = [C.c_void_p, C.c_uint32]
+        L.ps_arena_destroy.restype = C.c_int
+        L.ps_arena_destroy.argtypes = [C.c_void_p]
+        L.ps_probe_set_update_residency.restype = C.c_int
+        L.ps_probe_set_update_residency.argtypes = [C.c_uint32]
         L.ps_probe_copy.restype = C.c_int
         L.ps_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
         if L.ps_abi_version() != ABI_VERSION:
@@ -340,6 +351,27 @@ def ps_verify_checksum(buf, nbytes, first_word_index, out, accumulate, workspace
     _check(library().ps_verify_checksum(buf or None, nbytes, first_word_index, out or None,
                                         int(accumulate), workspace or None, workspace_bytes,
                                         stream or None))
+
+
+def ps_arena_create(length, chunk_elems, elem_bytes):
+    """Returns the arena handle (an integer); buffers via ps_arena_buffer(handle, k)."""
+    n = len(elem_bytes)
+    arr = (C.c_uint32 * n)(*elem_bytes) if n else None
+    out = C.c_void_p()
+    _check(library().ps_arena_create(length, chunk_elems, arr, n, C.byref(out)))
+    return out.value
+
+
+def ps_arena_buffer(arena, k):
+    return library().ps_arena_buffer(arena, k) or 0
+
+
+def ps_arena_destroy(arena):
+    _check(library().ps_arena_destroy(arena))
+
+
+def ps_probe_set_update_residency(waves_per_cu):
+    _check(library().ps_probe_set_update_residency(waves_per_cu))
 
 
 def ps_probe_copy(dst, src, nbytes, stream=0):

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libps_step.so")
-SOURCES = ["ps_cost.cpp", "ps_step.cpp", "ps_kernels.hip"]
+SOURCES = ["ps_cost.cpp", "ps_step.cpp", "ps_arena.cpp", "ps_kernels.hip"]
 HEADERS = ["ps_internal.h", "ps_kernel_templates.h"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -59,6 +59,7 @@ int launch_diff_sumsq(int dtype, const void *a, const void *b, uint64_t count, d
                       int accumulate, void *workspace, uint64_t slots, void *stream);
 int launch_checksum(const void *buf, uint64_t n_words, uint64_t first_index, uint64_t *out,
                     int accumulate, void *workspace, void *stream);
+void set_update_residency(uint32_t waves_per_cu);
 int launch_copy(void *dst, const void *src, uint64_t bytes, void *stream);
 // Stage one bucket: for each contribution r copy n_vec 16-byte vectors to
 // dst + r * slot_stride_bytes from src.p[r], starting at vector first_vec of the

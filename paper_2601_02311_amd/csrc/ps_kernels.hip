@@ -3,6 +3,7 @@
 // reduction tree of the sum of squares is the same on every run.
 #include "ps_kernel_templates.h"
 
+#include <atomic>
 #include <mutex>
 
 namespace ps {
@@ -22,8 +23,17 @@ constexpr uint32_t lds_for_waves(uint32_t waves_per_cu)
     return (163840u / waves_per_cu) & ~255u;
 }
 
+// Measurement aid: a residency cap for the update kernel that replaces the choice below
+// (0 = none; 3..32 waves per CU; above 32 = no cap at all).
+static std::atomic<uint32_t> update_residency_override{0};
+
+void set_update_residency(uint32_t waves_per_cu) { update_residency_override.store(waves_per_cu); }
+
 static uint32_t update_lds(uint32_t n_contrib, int dtype)
 {
+    const uint32_t forced = update_residency_override.load();
+    if (forced)
+        return forced > 32 ? 0u : lds_for_waves(forced < 3 ? 3 : forced);
     if (n_contrib == 1)
         return lds_for_waves(dtype == PS_BF16 ? 12 : 10);
     const uint32_t in_flight = n_contrib * (dtype == PS_BF16 ? 512u : 1024u) + 3072u;

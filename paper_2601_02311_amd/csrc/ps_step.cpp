@@ -565,10 +565,12 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
         set_error("source_elems must be a multiple of 512");
         return PS_EALIGN;
     }
-    if (plan->copy_engine != PS_COPY_KERNEL && plan->copy_engine != PS_COPY_MEMCPY) {
-        set_error("copy_engine must be PS_COPY_KERNEL or PS_COPY_MEMCPY");
+    if (plan->copy_engine != PS_COPY_KERNEL && plan->copy_engine != PS_COPY_MEMCPY &&
+        plan->copy_engine != PS_COPY_NONE) {
+        set_error("copy_engine must be PS_COPY_KERNEL, PS_COPY_MEMCPY or PS_COPY_NONE");
         return PS_EINVAL;
     }
+    const bool in_place = plan->copy_engine == PS_COPY_NONE;
     if (plan->schedule != PS_SCHED_AUTO && plan->schedule != PS_SCHED_OVERLAP &&
         plan->schedule != PS_SCHED_ALTERNATE) {
         set_error("schedule must be PS_SCHED_AUTO, PS_SCHED_OVERLAP or PS_SCHED_ALTERNATE");
@@ -578,17 +580,19 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
         set_error("PS_COPY_MEMCPY needs source_elems to be a multiple of bucket_elems");
         return PS_EUNSUPPORTED;
     }
-    if (!plan->staging[0] || !plan->staging[1] || plan->staging[0] == plan->staging[1]) {
-        set_error("two distinct staging buffers are required");
-        return PS_EINVAL;
-    }
-    if (!aligned16(plan->staging[0]) || !aligned16(plan->staging[1])) {
-        set_error("staging buffer not 16-byte aligned");
-        return PS_EALIGN;
-    }
-    if (plan->copy_stream == plan->compute_stream) {
-        set_error("copy_stream and compute_stream must differ");
-        return PS_EINVAL;
+    if (!in_place) {
+        if (!plan->staging[0] || !plan->staging[1] || plan->staging[0] == plan->staging[1]) {
+            set_error("two distinct staging buffers are required");
+            return PS_EINVAL;
+        }
+        if (!aligned16(plan->staging[0]) || !aligned16(plan->staging[1])) {
+            set_error("staging buffer not 16-byte aligned");
+            return PS_EALIGN;
+        }
+        if (plan->copy_stream == plan->compute_stream) {
+            set_error("copy_stream and compute_stream must differ");
+            return PS_EINVAL;
+        }
     }
     const uint64_t n_buckets = (shard->len + plan->bucket_elems - 1) / plan->bucket_elems;
     if (plan->kernel_ms && plan->kernel_ms_len < n_buckets) {
@@ -625,7 +629,7 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
             what = #call;                                                                         \
         }                                                                                         \
     } while (0)
-    for (int k = 0; k < 2; ++k) {
+    for (int k = 0; k < 2 && !in_place; ++k) {
         PS_TRY(hipEventCreateWithFlags(&staged[k], hipEventDisableTiming));
         PS_TRY(hipEventCreateWithFlags(&freed[k], hipEventDisableTiming));
     }
@@ -669,8 +673,38 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
         PS_TRY(hipEventRecord(staged[k], copy));
     };
 
-    stage(0);
-    for (uint64_t b = 0; b < n_buckets && e == hipSuccess; ++b) {
+    // A source in this device's memory is read where it lies: one kernel per bucket on the
+    // compute stream (one per contiguous piece where a repeating source wraps inside a
+    // bucket), no staging slot, no second stream, no events.
+    for (uint64_t b = 0; in_place && b < n_buckets && e == hipSuccess; ++b) {
+        const uint64_t lo = b * plan->bucket_elems;
+        const uint64_t cnt = clamp_count(lo, plan->bucket_elems, shard->valid_len);
+        if (timed)
+            PS_TRY(hipEventRecord(t0[b], comp));
+        for (uint64_t cur = lo; cur < lo + cnt && e == hipSuccess;) {
+            const uint64_t pos = cur % plan->source_elems;
+            const uint64_t room = plan->source_elems - pos;
+            const uint64_t take = lo + cnt - cur < room ? lo + cnt - cur : room;
+            ContribPtrs g;
+            std::memset(&g, 0, sizeof g);
+            for (uint32_t r = 0; r < plan->n_contrib; ++r)
+                g.p[r] = reinterpret_cast<const char *>(plan->source[r]) + pos * eb;
+            uint16_t *out = reinterpret_cast<uint16_t *>(shard->gather_out) + out_off + cur;
+            int le = launch_update(plan->dtype, plan->n_contrib, g, shard->master + cur,
+                                   shard->m + cur, shard->v + cur, out, take, s, comp);
+            if (le != 0) {
+                e = (hipError_t)le;
+                what = "update kernel launch";
+            }
+            cur += take;
+        }
+        if (timed)
+            PS_TRY(hipEventRecord(t1[b], comp));
+    }
+
+    if (!in_place)
+        stage(0);
+    for (uint64_t b = 0; !in_place && b < n_buckets && e == hipSuccess; ++b) {
         const int k = (int)(b & 1);
         if (b + 1 < n_buckets && !alternate)
             stage(b + 1);
@@ -699,11 +733,13 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
             stage(b + 1);
     }
     // Later work on the copy stream must not overtake the last kernels.
-    PS_TRY(hipStreamWaitEvent(copy, freed[(n_buckets - 1) & 1], 0));
+    if (!in_place)
+        PS_TRY(hipStreamWaitEvent(copy, freed[(n_buckets - 1) & 1], 0));
 
     if (timed) {
         PS_TRY(hipStreamSynchronize(comp));
-        PS_TRY(hipStreamSynchronize(copy));
+        if (!in_place)
+            PS_TRY(hipStreamSynchronize(copy));
         for (uint64_t b = 0; b < n_buckets; ++b)
             PS_TRY(hipEventElapsedTime(&plan->kernel_ms[b], t0[b], t1[b]));
     }
@@ -935,6 +971,17 @@ ps_status_t ps_step_update_offloaded(const ps_spec_t *spec, const ps_adamw_t *hp
     }
     if (e != hipSuccess)
         return hip_fail(e, what);
+    return PS_OK;
+}
+
+ps_status_t ps_probe_set_update_residency(uint32_t waves_per_cu)
+{
+    clear_error();
+    if (waves_per_cu != 0 && waves_per_cu < 3) {
+        set_error("waves_per_cu must be 0 (library's choice), 3..32, or above 32 (no cap)");
+        return PS_ERANGE;
+    }
+    set_update_residency(waves_per_cu);
     return PS_OK;
 }
 

@@ -9,6 +9,25 @@ import torch
 
 CHUNK = 1 << 27
 
+_TYPESTR = {torch.float32: "<f4", torch.int16: "<i2", torch.uint8: "|u1", torch.float16: "<f2",
+            torch.float64: "<f8", torch.int64: "<i8"}
+
+
+class _Foreign:
+    """Device memory that torch did not allocate, described the way array libraries expect."""
+
+    def __init__(self, ptr, numel, typestr):
+        self.__cuda_array_interface__ = {"shape": (numel,), "typestr": typestr,
+                                         "data": (int(ptr), False), "version": 2, "strides": None}
+
+
+def as_tensor(ptr, numel, dtype):
+    """A torch view (no copy) of `numel` elements of device memory at `ptr` that someone else
+    owns and keeps alive (an arena of the step library).  bfloat16 travels as int16."""
+    carrier = torch.int16 if dtype == torch.bfloat16 else dtype
+    t = torch.as_tensor(_Foreign(ptr, numel, _TYPESTR[carrier]), device="cuda")
+    return t.view(dtype)
+
 
 def _gen(seed, *stream):
     g = torch.Generator(device="cuda")
@@ -58,19 +77,39 @@ def fill_gradient_(t, seed, step, replica, std=1e-3, outlier_frac=0.0, outlier_m
     return t
 
 
-def workload_state(w, n=None):
-    """(master, m, v) fp32 device tensors of the workload's shard length."""
+def workload_state(w, n=None, into=None):
+    """(master, m, v) fp32 device tensors of the workload's shard length; `into`: three
+    tensors to fill instead of new ones."""
     n = w.shard_len if n is None else n
-    master = fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), w.theta_std, w.seed, 1)
+    master, m, v = into if into is not None else [torch.empty(n, dtype=torch.float32, device="cuda")
+                                                  for _ in range(3)]
+    fill_normal_(master, w.theta_std, w.seed, 1)
     if w.warm_moments:
-        m = fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), 1e-3, w.seed, 2,
-                         absolute=True)
-        v = fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), 1e-3, w.seed, 3,
-                         square=True)
+        fill_normal_(m, 1e-3, w.seed, 2, absolute=True)
+        fill_normal_(v, 1e-3, w.seed, 3, square=True)
     else:
-        m = torch.zeros(n, dtype=torch.float32, device="cuda")
-        v = torch.zeros(n, dtype=torch.float32, device="cuda")
+        m.zero_()
+        v.zero_()
     return master, m, v
+
+
+def state_chunks(w, n=None):
+    """The same values workload_state() writes, regenerated chunk by chunk: yields
+    (lo, hi, master, m, v) with temporaries of at most CHUNK elements.  The generators are
+    advanced exactly as fill_normal_ advances them, so the streams are identical."""
+    n = w.shard_len if n is None else n
+    gens = [_gen(w.seed, k) for k in (1, 2, 3)]
+    for lo in range(0, n, CHUNK):
+        hi = min(lo + CHUNK, n)
+        th = torch.empty(hi - lo, dtype=torch.float32, device="cuda").normal_(0.0, w.theta_std, generator=gens[0])
+        if w.warm_moments:
+            m = torch.empty(hi - lo, dtype=torch.float32, device="cuda").normal_(0.0, 1e-3, generator=gens[1]).abs_()
+            v = torch.empty(hi - lo, dtype=torch.float32, device="cuda").normal_(0.0, 1e-3, generator=gens[2])
+            v.mul_(v)
+        else:
+            m = torch.zeros(hi - lo, dtype=torch.float32, device="cuda")
+            v = torch.zeros(hi - lo, dtype=torch.float32, device="cuda")
+        yield lo, hi, th, m, v
 
 
 def workload_gradients(w, step, n=None):

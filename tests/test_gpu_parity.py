@@ -549,7 +549,8 @@ def _periodic(src_np, n):
 @pytest.mark.parametrize("engine,schedule", [(ps.PS_COPY_KERNEL, ps.PS_SCHED_AUTO),
                                              (ps.PS_COPY_KERNEL, ps.PS_SCHED_OVERLAP),
                                              (ps.PS_COPY_MEMCPY, ps.PS_SCHED_AUTO),
-                                             (ps.PS_COPY_MEMCPY, ps.PS_SCHED_ALTERNATE)])
+                                             (ps.PS_COPY_MEMCPY, ps.PS_SCHED_ALTERNATE),
+                                             (ps.PS_COPY_NONE, ps.PS_SCHED_AUTO)])
 @pytest.mark.parametrize("timed", [False, True])
 def test_bucketed_step_matches_oracle(timed, engine, schedule):
     bucket, N = 2 * TILE + 512, 8          # 4608: a multiple of 512 so that both engines apply
@@ -575,7 +576,10 @@ def test_bucketed_step_matches_oracle(timed, engine, schedule):
 @pytest.mark.parametrize("dtype,engine,pool", [("f32", ps.PS_COPY_MEMCPY, 2 * TILE),    # pool of 2 buckets
                                                ("f32", ps.PS_COPY_KERNEL, 2 * TILE),
                                                ("bf16", ps.PS_COPY_KERNEL, 1536),        # shorter than a bucket,
-                                               ("f32", ps.PS_COPY_KERNEL, 512)])         # buckets straddle the wrap
+                                               ("f32", ps.PS_COPY_KERNEL, 512),          # buckets straddle the wrap
+                                               ("f32", ps.PS_COPY_NONE, 2 * TILE),       # read in place: whole
+                                               ("bf16", ps.PS_COPY_NONE, 1536),          # buckets, pieces of a
+                                               ("bf16", ps.PS_COPY_NONE, 512)])          # bucket, many pieces
 def test_bucketed_step_with_a_repeating_source_pool(dtype, engine, pool):
     """A source shorter than the shard repeats: element e reads source[e % source_elems]
     (how the benchmark feeds 33 buckets from a small resident pool)."""
@@ -589,6 +593,48 @@ def test_bucketed_step_with_a_repeating_source_pool(dtype, engine, pool):
     orc.step_f32(_periodic(src, n), orc.derive_scalars(t=1, n_devices=N, **hpd), *want)
     got, _ = _bucketed(spec, hp, state, src, dtype, n, n, bucket, engine)
     assert assert_state_parity(got, want, "pool") == 0
+
+
+def test_step_on_arena_buffers_matches_oracle():
+    """Flat buffers whose physical memory is created chunk by chunk (ps_arena_create): the
+    bucket loop reads the contributions in place from them.  Chunks of 2^20 elements, a ragged
+    last chunk, canaries past the valid range."""
+    from synth import device as dgen
+    chunk, N = 1 << 20, 4
+    n = 2 * chunk + 12345 * 8
+    valid = n - 5
+    _say("arena: n=%d in chunks of %d, N=%d bf16, in-place bucket loop" % (n, chunk, N))
+    spec = ps.ps_spec_preset("zero3", N, 1, n * N)
+    arena = ps.ps_arena_create(n, chunk, [2] * N + [4, 4, 4, 2])
+    try:
+        ptrs = [ps.ps_arena_buffer(arena, k) for k in range(N + 4)]
+        assert all(p and p % (2 << 20) == 0 for p in ptrs) and ps.ps_arena_buffer(arena, N + 4) == 0
+        src_np = [gen.gradient(n, 47, 0, r, "bf16", 1e-3) for r in range(N)]
+        state = [gen.master(n, 47), *gen.moments(n, 47, True), np.full(n, 0x5A5A, np.uint16)]
+        views = [dgen.as_tensor(ptrs[r], n, torch.bfloat16) for r in range(N)]
+        views += [dgen.as_tensor(ptrs[N + j], n, torch.float32) for j in range(3)]
+        views.append(dgen.as_tensor(ptrs[N + 3], n, torch.bfloat16))
+        for t_, a in zip(views, src_np + state):
+            t_.copy_(dev(a).view(t_.dtype))
+        hpd, hp = hp_of(None, 7)
+        plan = ps.ps_bucket_plan_t()
+        arr = (C.c_void_p * N)(*ptrs[:N])
+        plan.source = C.cast(arr, C.POINTER(C.c_void_p))
+        plan.n_contrib, plan.dtype, plan.bucket_elems, plan.source_elems = N, ps.PS_BF16, chunk, -(-n // 512) * 512
+        plan.compute_stream, plan.copy_engine = stream_handle(), ps.PS_COPY_NONE
+        sh = ps.ps_shard_t(ptrs[N], ptrs[N + 1], ptrs[N + 2], ptrs[N + 3], n, valid, ps.PS_BF16, 0)
+        ps.ps_step_update_bucketed(spec, hp, sh, plan)
+        torch.cuda.synchronize()
+        want = [a.copy() for a in state]
+        orc.step_f32(src_np, orc.derive_scalars(t=7, n_devices=N, **hpd), *want, lo=0, hi=valid)
+        got = [host(t_) for t_ in views[N:]]
+        assert assert_state_parity(got, want, "arena") == 0
+        for g, a in zip(got, state):
+            assert np.array_equal(g[valid:].view(np.uint8), a[valid:].view(np.uint8))
+        del views, t_
+    finally:
+        torch.cuda.synchronize()
+        ps.ps_arena_destroy(arena)
 
 
 # ---- the other data-parallel rows: ZeRO-1 and gradient accumulation ----

@@ -189,7 +189,9 @@ def test_bucketed_rejects_bad_arguments():
     assert _status(lambda: run(spec, hp, shard, plan(bucket_elems=100))) == ps.PS_EALIGN
     assert _status(lambda: run(spec, hp, shard, plan(source_elems=0))) == ps.PS_ERANGE
     assert _status(lambda: run(spec, hp, shard, plan(source_elems=1000))) == ps.PS_EALIGN
-    assert _status(lambda: run(spec, hp, shard, plan(copy_engine=2))) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, shard, plan(copy_engine=3))) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, shard, plan(copy_engine=ps.PS_COPY_NONE,
+                                                       source_elems=1000))) == ps.PS_EALIGN
     assert _status(lambda: run(spec, hp, shard, plan(schedule=3))) == ps.PS_EINVAL
     assert _status(lambda: run(spec, hp, shard, plan(copy_engine=ps.PS_COPY_MEMCPY, bucket_elems=384,
                                                        source_elems=1024))) == ps.PS_EUNSUPPORTED
@@ -199,6 +201,24 @@ def test_bucketed_rejects_bad_arguments():
     assert _status(lambda: run(spec, hp, shard, plan(n_contrib=3))) == ps.PS_EINVAL
     ms = (C.c_float * 2)()
     assert _status(lambda: run(spec, hp, shard, plan(kernel_ms=ms, kernel_ms_len=2))) == ps.PS_ERANGE
+
+
+def test_arena_rejects_bad_arguments():
+    L = ps.library()
+    out = C.c_void_p(1)
+    eb = (C.c_uint32 * 3)(2, 4, 4)
+    bad = (C.c_uint32 * 3)(2, 0, 4)
+    run = lambda *a: L.ps_arena_create(*a)
+    assert run(1 << 20, 1 << 20, None, 3, C.byref(out)) == ps.PS_EINVAL
+    assert run(1 << 20, 1 << 20, eb, 3, None) == ps.PS_EINVAL
+    assert run(1 << 20, 1 << 20, eb, 0, C.byref(out)) == ps.PS_ERANGE
+    assert run(0, 1 << 20, eb, 3, C.byref(out)) == ps.PS_ERANGE
+    assert run(1 << 20, 0, eb, 3, C.byref(out)) == ps.PS_ERANGE
+    assert run(1 << 20, 1 << 20, bad, 3, C.byref(out)) == ps.PS_ERANGE
+    assert run(1 << 20, (1 << 20) + 8, eb, 3, C.byref(out)) == ps.PS_EALIGN       # pieces not whole 2 MiB pages
+    assert out.value is None                                                       # cleared on every refusal
+    assert "2 MiB" in ps.ps_last_error()
+    assert L.ps_arena_buffer(None, 0) is None and L.ps_arena_destroy(None) == ps.PS_OK
 
 
 def test_offloaded_rejects_bad_arguments():
@@ -270,6 +290,19 @@ def test_valid_calls_report_no_device():
     assert _status(lambda: ps.ps_probe_copy(FAKE, FAKE * 2, 4096)) == ps.PS_ENODEVICE
     assert _status(lambda: ps.ps_step_reduce_sumsq(
         spec, grads, 0.0, FAKE, FAKE, 0, FAKE, ps.ps_workspace_bytes(8), 0, 8, 1024)) == ps.PS_ENODEVICE
+    assert _status(lambda: ps.ps_step_reduce_sumsq_static(
+        spec, grads, 0.0, FAKE, FAKE, 0, 0, 8, 1024)) == ps.PS_ENODEVICE
+    # the bucket loop that reads in place needs no staging slots and no second stream, so
+    # neither is checked: the otherwise valid call gets as far as looking for a device
+    src = (C.c_void_p * 4)(*[FAKE] * 4)
+    p = ps.ps_bucket_plan_t()
+    p.source = C.cast(src, C.POINTER(C.c_void_p))
+    p.n_contrib, p.dtype, p.bucket_elems, p.source_elems = 4, ps.PS_BF16, 256, 1024
+    p.compute_stream, p.copy_engine = 0x200, ps.PS_COPY_NONE
+    assert _status(lambda: ps.ps_step_update_bucketed(spec, hp, shard, p)) == ps.PS_ENODEVICE
+    out = C.c_void_p()
+    assert ps.library().ps_arena_create(1 << 20, 1 << 20, (C.c_uint32 * 2)(2, 4), 2,
+                                        C.byref(out)) == ps.PS_ENODEVICE
 
 
 def test_device_clip_coefficient_arguments():
