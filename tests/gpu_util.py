@@ -70,3 +70,54 @@ def assert_state_parity(got, want, what=""):
     gp, wp = got[3].view(np.uint16), want[3].view(np.uint16)         # bf16 bits or binary16, as bits
     assert np.array_equal(gp[same], wp[same]), "%s 16-bit image differs" % what
     return int((~same).sum())
+
+
+class HostChunks:
+    """Pinned host buffers, one per named array, reused from chunk to chunk."""
+
+    def __init__(self, **specs):
+        self.buf = {}
+        for name, (numel, dtype) in specs.items():
+            carrier = torch.int16 if dtype == torch.bfloat16 else dtype
+            self.buf[name] = torch.empty(numel, dtype=carrier, pin_memory=True)
+
+    def fetch(self, name, t):
+        """Copy the device tensor t (at most the buffer's length) to the host; returns a numpy
+        view of the pinned buffer with the original byte meaning (2-byte bit patterns as
+        uint16, float16 as float16)."""
+        k = t.numel()
+        t = t.detach()
+        if t.dtype == torch.bfloat16:
+            t = t.view(torch.int16)
+        dst = self.buf[name][:k]
+        dst.copy_(t)                     # synchronous for pinned destinations on this stream
+        torch.cuda.current_stream().synchronize()
+        a = dst.numpy()
+        return a.view(np.uint16) if a.dtype == np.int16 else a
+
+
+def oracle_mismatches(step_f32, scalars, grads, pre, post, count, threads=16):
+    """Runs the oracle's step over [0, count) of one chunk on `threads` host threads that
+    share nothing (contiguous ranges; the update is elementwise) and counts, per array, the
+    elements whose bits differ from what the device produced.  grads: contributions (host);
+    pre: [theta, m, v] before the step, overwritten with the oracle's result; post: [theta,
+    m, v, p] from the device.  Returns [bad_theta, bad_m, bad_v, bad_p]."""
+    import threading
+    p_want = np.zeros(pre[0].shape[0], post[3].dtype)
+    bounds = [count * k // threads for k in range(threads + 1)]
+    bad = [[0, 0, 0, 0] for _ in range(threads)]
+
+    def work(k):
+        lo, hi = bounds[k], bounds[k + 1]
+        if hi <= lo:
+            return
+        step_f32(grads, scalars, pre[0], pre[1], pre[2], p_want, lo, hi)
+        for j in range(3):
+            bad[k][j] = int(np.count_nonzero(pre[j][lo:hi].view(np.uint32) != post[j][lo:hi].view(np.uint32)))
+        bad[k][3] = int(np.count_nonzero(p_want[lo:hi].view(np.uint16) != post[3][lo:hi].view(np.uint16)))
+    ts = [threading.Thread(target=work, args=(k,)) for k in range(threads)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    return [sum(b[j] for b in bad) for j in range(4)]

@@ -1,11 +1,15 @@
-"""Full-size GPU parity in the launch configurations bench.py times: the 7B ZeRO-2
-shard (one launch), the 70B ZeRO-3 shard (33 buckets through the two-stream
-pipeline), the ragged 13B shard with clipping (two phases), and the ZeRO-1,
-accumulation, verification and offload rows on the 7B shard.  Inputs are
-generated on the device; sampled slices are copied to the host *before* the step
-and the oracle is run on exactly those slices.  Whole-shard properties that hold
-at any size are checked on the device with library primitives."""
+"""Full-size GPU parity in the launch configurations bench.py times.  The 7B ZeRO-2
+shard (one launch), the 70B ZeRO-3 shard (33 buckets read in place from arena
+buffers) and the ragged 13B shard with clipping (two phases) are compared with the
+oracle on EVERY element: inputs are generated on the device from seeded generators,
+the state before the step is regenerated chunk by chunk afterwards, and chunks of
+2^27 elements travel to the host where the oracle runs on all cores.  The staged
+two-stream pipeline is checked on whole buckets at full size, the ZeRO-1,
+accumulation and offload rows on sampled slices, the verification scans on whole
+buffers.  Whole-shard properties that hold at any size are checked on the device
+with library primitives."""
 import ctypes as C
+import time
 
 import numpy as np
 import pytest
@@ -16,7 +20,8 @@ from oracle import step as orc
 from synth import WORKLOADS
 from synth import device as dgen
 
-from gpu_util import assert_state_parity, host, shard_of, stream_handle
+from gpu_util import (HostChunks, assert_state_parity, host, oracle_mismatches, shard_of,
+                      stream_handle)
 
 pytestmark = pytest.mark.gpu
 
@@ -63,23 +68,75 @@ def _whole_shard_properties(master, m, v, out_slice, valid):
         assert bool(torch.isfinite(master[lo:hi]).all()) and bool(torch.isfinite(m[lo:hi]).all())
 
 
+CHUNK = dgen.CHUNK            # elements per host round trip of the every-element checks
+
+
+def _progress(capsys, msg):
+    """A line that reaches the terminal while the test runs (long tests must not look hung)."""
+    with capsys.disabled():
+        print("[full-size] " + msg, flush=True)
+
+
+def _pinned(n_contrib, grad_torch_dtype, param_torch_dtype, extra=()):
+    spec = {"g%d" % r: (CHUNK, grad_torch_dtype) for r in range(n_contrib)}
+    for k in ("th0", "m0", "v0", "th1", "m1", "v1"):
+        spec[k] = (CHUNK, torch.float32)
+    spec["p1"] = (CHUNK, param_torch_dtype)
+    for name, dt in extra:
+        spec[name] = (CHUNK, dt)
+    return HostChunks(**spec)
+
+
+def _check_every_element(capsys, what, w, s, pin, grads_of_chunk, master, m, v, out_slice, valid,
+                         saved_head=None):
+    """Every element of [0, valid) against the oracle: the state before the step is regenerated
+    chunk by chunk from the seeded generator (same values the buffers were filled with), the
+    contributions and the state after the step come from the device; the oracle runs on all
+    host threads.  Asserts zero differing elements in master, m, v and the 16-bit image."""
+    bad = [0, 0, 0, 0]
+    done = 0
+    t0 = time.time()
+    for lo, hi, th0, m0, v0 in dgen.state_chunks(w):
+        if lo >= valid:
+            break
+        k = min(hi, valid) - lo
+        pre = [pin.fetch("th0", th0), pin.fetch("m0", m0), pin.fetch("v0", v0)]
+        if lo == 0 and saved_head is not None:      # the regenerated stream is the one the buffers held
+            for a, b in zip(pre, saved_head):
+                assert np.array_equal(a[:b.shape[0]].view(np.uint32), b.view(np.uint32))
+        grads = grads_of_chunk(lo, hi)
+        post = [pin.fetch("th1", master[lo:hi]), pin.fetch("m1", m[lo:hi]), pin.fetch("v1", v[lo:hi]),
+                pin.fetch("p1", out_slice[lo:hi])]
+        if hi > valid:                               # pad: untouched, byte for byte
+            for a, b in zip(post[:3], pre):
+                assert np.array_equal(a[k:].view(np.uint32), b[k:].view(np.uint32)), what + ": pad touched"
+        for j, x in enumerate(oracle_mismatches(orc.step_f32, s, grads, pre, post, k)):
+            bad[j] += x
+        done += k
+        if (lo // CHUNK) % 8 == 7 or hi >= valid:
+            _progress(capsys, "%s: %d of %d elements checked against the oracle, %.0f s, mismatches %s"
+                      % (what, done, valid, time.time() - t0, bad))
+        assert bad == [0, 0, 0, 0], "%s: elements differing from the oracle in [%d,%d): %s" % (what, lo, hi, bad)
+    assert done == valid
+    return bad
+
+
 @pytest.mark.parametrize("name", ["7b_zero2", "7b_zero2_f16"])
-def test_7b_zero2_full_shard_sampled(name):
-    """bf16 gradients and parameters, and the same shard in binary16 with a loss scale."""
+def test_7b_zero2_full_shard_every_element(name, capsys):
+    """bf16 gradients and parameters, and the same shard in binary16 with a loss scale: one
+    launch over the whole shard, every element compared with the oracle."""
     w = WORKLOADS[name]
     _need(45)
     n, N, t = w.shard_len, w.n_devices, w.first_step
     f16 = w.param_dtype == "f16"
-    _say("%s full shard n=%d, one launch, sampled slices" % (name, n))
+    tdt = torch.float16 if f16 else torch.bfloat16
+    _say("%s full shard n=%d, one launch, every element" % (name, n))
     spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi)
     cost = ps.ps_cost_eval(spec)
     master, m, v = dgen.workload_state(w)
+    head = [_take(x, 0, 4096) for x in (master, m, v)]
     grads = dgen.workload_gradients(w, t)
-    out = torch.zeros(cost.psi_padded, dtype=torch.float16 if f16 else torch.bfloat16,
-                      device="cuda")                                            # replicated Theta
-    sl = _slices(n)
-    before = [([_take(x, lo, hi) for x in (master, m, v)], [_take(g, lo, hi) for g in grads])
-              for lo, hi in sl]
+    out = torch.zeros(cost.psi_padded, dtype=tdt, device="cuda")               # replicated Theta
     gs = 1.0 / (N * w.loss_scale) if w.loss_scale != 1.0 else 0.0
     hpd, hp = _hp(w, t, grad_scale=gs)
     ps.ps_step_update(spec, hp, shard_of(master, m, v, out, n), ps.make_grads(
@@ -87,24 +144,68 @@ def test_7b_zero2_full_shard_sampled(name):
     torch.cuda.synchronize()
     s = orc.derive_scalars(t=t, n_devices=N, grad_scale=gs, **hpd)
     off = cost.shard_offset
-    for (lo, hi), (st, gr) in zip(sl, before):
-        want = [a.copy() for a in st] + [np.zeros(hi - lo, np.float16 if f16 else np.uint16)]
-        orc.step_f32(gr, s, *want)
-        got = [_take(x, lo, hi) for x in (master, m, v)] + [_take(out, off + lo, off + hi)]
-        assert assert_state_parity(got, want, "7b [%d,%d)" % (lo, hi)) == 0
-    _whole_shard_properties(master, m, v, out[off:off + n], n)
-    assert not bool(out[off + n:off + n + SLICE].view(torch.int16).any())   # next shard's slice untouched
-    del master, m, v, grads, out
+    pin = _pinned(N, tdt, tdt)
+    _check_every_element(capsys, name, w, s, pin,
+                         lambda lo, hi: [pin.fetch("g%d" % r, grads[r][lo:hi]) for r in range(N)],
+                         master, m, v, out[off:off + n], n, saved_head=head)
+    assert not bool(out[off + n:].view(torch.int16).any())                     # the other shards' slices untouched
+    del master, m, v, grads, out, pin
     torch.cuda.empty_cache()
 
 
-def test_70b_zero3_bucketed_full_shard_sampled():
+def test_70b_zero3_in_place_every_element(capsys):
+    """The configuration bench.py times: the whole 70B shard, its 140 GB of contributions
+    resident and distinct in flat arena buffers, 33 buckets read in place; every one of the
+    8.75e9 elements compared with the oracle."""
     w = WORKLOADS["70b_zero3"]
-    _need(140)
+    _need(280)
     n, N, t, B = w.shard_len, w.n_devices, w.first_step, w.bucket_elems
-    pool_elems = 1 << 21
     n_b = -(-n // B)
-    _say("70b_zero3 full shard n=%d, %d buckets of %d, pool %d, sampled slices" % (n, n_b, B, pool_elems))
+    _say("70b_zero3 full shard n=%d, %d buckets of %d read in place from arena buffers, every element" % (n, n_b, B))
+    spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi)
+    arena = ps.ps_arena_create(n, B, [2] * N + [4, 4, 4, 2])
+    try:
+        buf = [ps.ps_arena_buffer(arena, k) for k in range(N + 4)]
+        master, m, v = dgen.workload_state(w, into=[dgen.as_tensor(buf[N + j], n, torch.float32) for j in range(3)])
+        out = dgen.as_tensor(buf[N + 3], n, torch.bfloat16).zero_()
+        grads = [dgen.fill_gradient_(dgen.as_tensor(buf[r], n, torch.bfloat16), w.seed, t, r, w.grad_std)
+                 for r in range(N)]
+        head = [_take(x, 0, 4096) for x in (master, m, v)]
+        comp = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        plan = ps.ps_bucket_plan_t()
+        arr = (C.c_void_p * N)(*buf[:N])
+        plan.source = C.cast(arr, C.POINTER(C.c_void_p))
+        plan.n_contrib, plan.dtype, plan.bucket_elems = N, ps.PS_BF16, B
+        plan.source_elems = -(-n // 512) * 512          # as long as the shard: never wraps
+        plan.compute_stream, plan.copy_engine = comp.cuda_stream, ps.PS_COPY_NONE
+        hpd, hp = _hp(w, t)
+        ps.ps_step_update_bucketed(spec, hp, shard_of(master, m, v, out, n), plan)
+        torch.cuda.synchronize()
+        s = orc.derive_scalars(t=t, n_devices=N, **hpd)
+        pin = _pinned(N, torch.bfloat16, torch.bfloat16)
+        _check_every_element(capsys, "70b in place", w, s, pin,
+                             lambda lo, hi: [pin.fetch("g%d" % r, grads[r][lo:hi]) for r in range(N)],
+                             master, m, v, out, n, saved_head=head)
+        del master, m, v, out, grads, pin
+    finally:
+        torch.cuda.synchronize()
+        ps.ps_arena_destroy(arena)
+    torch.cuda.empty_cache()
+
+
+def test_70b_zero3_staged_pipeline_whole_buckets(capsys):
+    """The two-stream pipeline that stages each bucket first, at full size, from a pool whose
+    length does not divide the bucket size (every bucket starts somewhere else in the pool and
+    wraps inside it).  Whole buckets 0, 15 (the other staging slot), 16 and the short last one
+    are compared element by element with the oracle; the rest of the shard by properties."""
+    w = WORKLOADS["70b_zero3"]
+    _need(150)
+    n, N, t, B = w.shard_len, w.n_devices, w.first_step, w.bucket_elems
+    pool_elems = 5 * (1 << 25) + 3 * 512
+    n_b = -(-n // B)
+    check = (0, 15, 16, n_b - 1)
+    _say("70b_zero3 staged: n=%d, %d buckets of %d, pool %d, whole buckets %s" % (n, n_b, B, pool_elems, check))
     spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi)
     master, m, v = dgen.workload_state(w)
     out = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
@@ -113,10 +214,6 @@ def test_70b_zero3_bucketed_full_shard_sampled():
     pool_np = [host(p) for p in pool]
     staging = [torch.empty(N * B, dtype=torch.bfloat16, device="cuda") for _ in range(2)]
     copy, comp = torch.cuda.Stream(), torch.cuda.Stream()
-    # buckets 0, 16 and the short last one, plus ranges that straddle bucket edges
-    sl = _slices(n, extra=[(16 * B - 4096, 16 * B + 4096), ((n_b - 1) * B - 4096, (n_b - 1) * B + 4096),
-                           (16 * B + 12345 * 8, 16 * B + 12345 * 8 + SLICE)])
-    before = [[_take(x, lo, hi) for x in (master, m, v)] for lo, hi in sl]
     torch.cuda.synchronize()
     plan = ps.ps_bucket_plan_t()
     arr = (C.c_void_p * N)(*[p.data_ptr() for p in pool])
@@ -129,19 +226,42 @@ def test_70b_zero3_bucketed_full_shard_sampled():
     ps.ps_step_update_bucketed(spec, hp, shard_of(master, m, v, out, n), plan)
     torch.cuda.synchronize()
     s = orc.derive_scalars(t=t, n_devices=N, **hpd)
-    for (lo, hi), st in zip(sl, before):
-        idx = np.arange(lo, hi) % pool_elems             # element e reads source[e % source_elems]
-        gr = [np.ascontiguousarray(p[idx]) for p in pool_np]
-        want = [a.copy() for a in st] + [np.zeros(hi - lo, np.uint16)]
-        orc.step_f32(gr, s, *want)
-        got = [_take(x, lo, hi) for x in (master, m, v, out)]
-        assert assert_state_parity(got, want, "70b [%d,%d)" % (lo, hi)) == 0
+    pin = _pinned(0, torch.bfloat16, torch.bfloat16)
+
+    def wrapped(lo, hi):
+        """Contributions of elements [lo, hi): element e reads source[e % source_elems]."""
+        outs = []
+        for p_ in pool_np:
+            parts, cur = [], lo
+            while cur < hi:
+                pos = cur % pool_elems
+                take = min(hi - cur, pool_elems - pos)
+                parts.append(p_[pos:pos + take])
+                cur += take
+            outs.append(np.ascontiguousarray(np.concatenate(parts)))
+        return outs
+    bad, t0 = [0, 0, 0, 0], time.time()
+    for lo, hi, th0, m0, v0 in dgen.state_chunks(w):
+        if lo // B not in check and (hi - 1) // B not in check:
+            continue                                   # the generators still advanced past this chunk
+        pre = [pin.fetch("th0", th0), pin.fetch("m0", m0), pin.fetch("v0", v0)]
+        post = [pin.fetch("th1", master[lo:hi]), pin.fetch("m1", m[lo:hi]), pin.fetch("v1", v[lo:hi]),
+                pin.fetch("p1", out[lo:hi])]
+        for j, x in enumerate(oracle_mismatches(orc.step_f32, s, wrapped(lo, hi), pre, post, hi - lo)):
+            bad[j] += x
+        _progress(capsys, "70b staged: [%d,%d) (bucket %d) checked, %.0f s, mismatches %s"
+                  % (lo, hi, lo // B, time.time() - t0, bad))
+        assert bad == [0, 0, 0, 0]
     _whole_shard_properties(master, m, v, out, n)
-    del master, m, v, out, pool, staging
+    del master, m, v, out, pool, staging, pin
     torch.cuda.empty_cache()
 
 
-def test_13b_clip_ragged_full_shard_sampled():
+def test_13b_clip_ragged_full_shard_every_element(capsys):
+    """Ragged 13B shard, six fp32 contributions, global-norm clipping in two phases.  The mean
+    gradient of every valid element and the sum of its squares come from the oracle
+    (sequential binary64), the coefficient both sides use is formed from THAT sum, and every
+    element of the updated state is compared with the oracle; the pad stays untouched."""
     w = WORKLOADS["13b_clip"]
     _need(100)
     N, t = w.n_devices, w.first_step
@@ -150,57 +270,50 @@ def test_13b_clip_ragged_full_shard_sampled():
     cost = ps.ps_cost_eval(spec)
     n, valid = cost.shard_len, cost.valid_len
     assert n == w.shard_len and valid == n - 1001
-    _say("13b_clip ragged full shard n=%d valid=%d N=%d fp32, two phases" % (n, valid, N))
+    _say("13b_clip ragged full shard n=%d valid=%d N=%d fp32, two phases, every element" % (n, valid, N))
     master, m, v = dgen.workload_state(w)
+    head = [_take(x, 0, 4096) for x in (master, m, v)]
     grads = dgen.workload_gradients(w, t)
     out = torch.full((n,), -1.0, dtype=torch.bfloat16, device="cuda")
     red = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
     ssd = torch.zeros(1, dtype=torch.float64, device="cuda")
     ws = torch.empty(ps.ps_workspace_bytes(n), dtype=torch.uint8, device="cuda")
-    sl = _slices(valid, extra=[(n - SLICE, n)])          # the last range includes the pad
-    before = [([_take(x, lo, hi) for x in (master, m, v, out)], [_take(g, lo, hi) for g in grads])
-              for lo, hi in sl]
     g = ps.make_grads([x.data_ptr() for x in grads], ps.PS_F32)
     ps.ps_step_reduce_sumsq(spec, g, 0.0, red.data_ptr(), ssd.data_ptr(), 0, ws.data_ptr(),
                             ws.numel(), 0, n, valid, stream_handle())
     ss_gpu = float(ssd.item())
-    # the same sum with library primitives in binary64 on the device (a definition, not the HIP path)
-    gs = np.float32(1.0 / N)
-    ss_ref = 0.0
-    step = 1 << 27
-    for lo in range(0, valid, step):
-        hi = min(lo + step, valid)
-        acc = grads[0][lo:hi].clone()
-        for r in range(1, N):
-            acc += grads[r][lo:hi]
-        acc *= float(gs)
-        assert torch.equal(acc, red[lo:hi])                                  # bit-exact mean, every element
-        ss_ref += float(acc.double().square_().sum().item())
-    assert abs(ss_gpu - ss_ref) <= 1e-9 * ss_ref
-    assert bool(torch.isnan(red[valid:]).all())                               # pad never written
     again = torch.zeros(1, dtype=torch.float64, device="cuda")
     ps.ps_step_reduce_sumsq(spec, g, 0.0, 0, again.data_ptr(), 0, ws.data_ptr(), ws.numel(), 0, n,
                             valid, stream_handle())
     assert float(again.item()) == ss_gpu                                      # run-to-run identical
-    # the oracle's coefficient from the independent sum; both sides use this one value
-    coef = orc.clip_coef(ss_ref, 5 * ss_ref, w.max_grad_norm)
-    assert ps.ps_clip_coef(ss_ref, 5 * ss_ref, w.max_grad_norm) == coef
+    # phase 1 against the oracle: the mean bit for bit on every element, the sum within the
+    # sequential sum's own rounding bound (valid * 2^-53 relative, all terms >= 0)
+    pin = _pinned(N, torch.float32, torch.bfloat16, extra=[("red", torch.float32)])
+    gs = np.float32(1.0 / N)
+    ss_oracle, t0 = 0.0, time.time()
+    for lo in range(0, valid, CHUNK):
+        hi = min(lo + CHUNK, valid)
+        gr = [pin.fetch("g%d" % r, grads[r][lo:hi]) for r in range(N)]
+        gm, ss_c = orc.mean_sumsq(gr, gs, 0, hi - lo)
+        ss_oracle += ss_c
+        assert np.array_equal(gm.view(np.uint32), pin.fetch("red", red[lo:hi]).view(np.uint32))
+        if (lo // CHUNK) % 8 == 7 or hi == valid:
+            _progress(capsys, "13b phase 1: mean of %d of %d elements equals the oracle's, %.0f s"
+                      % (hi, valid, time.time() - t0))
+    assert abs(ss_gpu - ss_oracle) <= valid * 2.0 ** -53 * ss_oracle
+    assert bool(torch.isnan(red[valid:]).all())                               # pad never written
+    coef = orc.clip_coef(ss_oracle, 5 * ss_oracle, w.max_grad_norm)           # five iid peer shards
+    assert ps.ps_clip_coef(ss_oracle, 5 * ss_oracle, w.max_grad_norm) == coef
     hpd, hp = _hp(w, t, grad_scale=1.0, clip_coef=coef)
     ps.ps_step_update(spec, hp, shard_of(master, m, v, out, n, valid),
                       ps.make_grads([red.data_ptr()], ps.PS_F32), 0, n, stream_handle())
     torch.cuda.synchronize()
-    s = orc.derive_scalars(t=t, n_devices=N, clip_coef=coef, **hpd)
-    for (lo, hi), (st, gr) in zip(sl, before):
-        want = [a.copy() for a in st]
-        orc.step_f32(gr, s, *want, lo=0, hi=min(hi, valid) - lo)              # oracle stops at valid
-        got = [_take(x, lo, hi) for x in (master, m, v, out)]
-        assert assert_state_parity(got, want, "13b [%d,%d)" % (lo, hi)) == 0
-        assert np.array_equal(got[3], want[3])
-        if hi > valid:                                                        # pad bytes untouched
-            for a, b in zip(got, st):
-                assert np.array_equal(a[valid - lo:].view(np.uint8), b[valid - lo:].view(np.uint8))
-    _whole_shard_properties(master, m, v, out, valid)
-    del master, m, v, out, red, grads, ws
+    s = orc.derive_scalars(t=t, n_devices=N, clip_coef=coef, **hpd)           # the unsharded definition:
+    _check_every_element(capsys, "13b phase 2", w, s, pin,                    # six contributions, mean 1/N
+                         lambda lo, hi: [pin.fetch("g%d" % r, grads[r][lo:hi]) for r in range(N)],
+                         master, m, v, out, valid, saved_head=head)
+    assert bool((out[valid:].view(torch.int16) == out.new_full((1,), -1.0).view(torch.int16)).all())
+    del master, m, v, out, red, grads, ws, pin
     torch.cuda.empty_cache()
 
 
