@@ -72,6 +72,9 @@ def main():
     ap.add_argument("--clip-on-host", action="store_true",
                     help="clipped workload: read the sum of squares back and form the coefficient "
                          "on the host (one device->host sync per step) instead of on the device")
+    ap.add_argument("--offload-layout", choices=["packed", "flat"], default="packed",
+                    help="7b_offload: host state as one image packed bucket by bucket (one copy per "
+                         "direction per bucket) or as four flat arrays (three copies up, four down)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-baseline-seconds", type=float, default=15.0,
                     help="about how much CPU work the oracle baseline may take")
@@ -385,14 +388,28 @@ def offload_bench(args):
     info = ps.ps_device_info()
     n, N, B = w.shard_len, w.n_devices, (args.bucket_elems or w.bucket_elems)
     spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi)
-    master, m, v = [t.cpu().pin_memory() for t in dgen.workload_state(w)]
-    out = torch.zeros(n, dtype=torch.bfloat16).pin_memory()
+    plan = ps.ps_offload_plan_t()
+    n_b = -(-n // B)
+    state = dgen.workload_state(w)
+    if args.offload_layout == "packed":
+        # one pinned image, bucket by bucket master | m | v | parameters: one copy per direction
+        image = torch.empty(n_b * 14 * B, dtype=torch.uint8).pin_memory()
+        for b in range(n_b):
+            lo, hi = b * B, min((b + 1) * B, n)
+            for j, t in enumerate(state):
+                image[b * 14 * B + 4 * B * j:b * 14 * B + 4 * B * j + 4 * (hi - lo)].copy_(
+                    t[lo:hi].view(torch.uint8))
+        plan.host_layout, plan.host_packed = ps.PS_HOST_PACKED, image.data_ptr()
+    else:
+        master, m, v = [t.cpu().pin_memory() for t in state]
+        out = torch.zeros(n, dtype=torch.bfloat16).pin_memory()
+        plan.host_master, plan.host_m, plan.host_v, plan.host_param_out = (master.data_ptr(), m.data_ptr(),
+                                                                           v.data_ptr(), out.data_ptr())
+    del state
+    torch.cuda.empty_cache()
     grads = dgen.workload_gradients(w, w.first_step)
     slots = [torch.empty(14 * B, dtype=torch.uint8, device="cuda") for _ in range(3)]
     s1, s2, s3 = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
-    plan = ps.ps_offload_plan_t()
-    plan.host_master, plan.host_m, plan.host_v, plan.host_param_out = (master.data_ptr(), m.data_ptr(),
-                                                                       v.data_ptr(), out.data_ptr())
     plan.len, plan.valid_len, plan.bucket_elems, plan.n_slots = n, n, B, 3
     for k, t in enumerate(slots):
         plan.slot[k] = t.data_ptr()
@@ -402,29 +419,60 @@ def offload_bench(args):
 
     def step():
         hp = ps.ps_adamw_t(w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, t_no[0], 0.0, 0.0)
-        ps.ps_step_update_offloaded(spec, hp, plan, g)
-        torch.cuda.synchronize()       # the next step reads what this one wrote back
+        ps.ps_step_update_offloaded(spec, hp, plan, g)     # consecutive steps are ordered on the streams
         t_no[0] += 1
     for _ in range(args.warmup):
         step()
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
+    torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     up, down = 12 * n, 14 * n
     log("%.3f ms/step: %.1f GB/s up, %.1f GB/s down over the host link" %
         (ms_per_step, up / ms_per_step / 1e6, down / ms_per_step / 1e6))
+
+    # Yardstick, like the copy kernel for HBM: the same bytes over the same link as plain
+    # pinned copies, 12 B bytes up and 14 B bytes down per bucket, both directions at once.
+    src_up = torch.empty(12 * B, dtype=torch.uint8).pin_memory()
+    dst_down = torch.empty(14 * B, dtype=torch.uint8).pin_memory()
+    dev_up = torch.empty(12 * B, dtype=torch.uint8, device="cuda")
+    dev_down = torch.empty(14 * B, dtype=torch.uint8, device="cuda")
+
+    def probe(do_up, do_down):
+        torch.cuda.synchronize()
+        p0 = time.perf_counter()
+        for _ in range(n_b):
+            if do_up:
+                with torch.cuda.stream(s1):
+                    dev_up.copy_(src_up, non_blocking=True)
+            if do_down:
+                with torch.cuda.stream(s3):
+                    dst_down.copy_(dev_down, non_blocking=True)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - p0) * 1e3
+    probe(True, True)
+    both_ms, up_ms, down_ms = probe(True, True), probe(True, False), probe(False, True)
+    link = {"both_directions_ms": both_ms,
+            "up_GBps_both": 12 * B * n_b / both_ms / 1e6, "down_GBps_both": 14 * B * n_b / both_ms / 1e6,
+            "up_GBps_alone": 12 * B * n_b / up_ms / 1e6, "down_GBps_alone": 14 * B * n_b / down_ms / 1e6,
+            "note": "plain pinned copies of the step's bytes, one per direction per bucket"}
+    log("link probe: %s" % json.dumps(link))
     print(json.dumps({
         "metric": "offloaded shard reduce+AdamW+cast: host-link GB/s, elements/s",
         "value": n / (ms_per_step * 1e-3), "unit": "elements/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "shard_elems": n, "n_devices": N, "bucket_elems": B,
-                   "slots": 3, "device": info.name.decode()},
+                   "slots": 3, "host_layout": args.offload_layout, "device": info.name.decode()},
         "roofline": {"bound": "host link (PCIe, full duplex)", "achieved": down / ms_per_step / 1e6,
                      "peak": 64.0, "unit": "GB/s", "frac": down / ms_per_step / 1e6 / 64.0,
+                     "frac_of_link_probe": both_ms * n / (n_b * B) / ms_per_step,
                      "traffic": None, "note": "the busier direction: 14 bytes per element device to host; "
-                     "peak is PCIe 5.0 x16 per direction"}}), flush=True)
+                     "peak is PCIe 5.0 x16 per direction; frac_of_link_probe = time plain pinned copies "
+                     "of the same bytes take / time of the step"},
+        "extras": {"link_probe": link}}), flush=True)
 
 
 def verify_bench(args):

@@ -201,11 +201,14 @@ typedef struct ps_bucket_plan_t {
     uint64_t kernel_ms_len;     /* capacity of kernel_ms                                */
 } ps_bucket_plan_t;
 
+/* Where ps_step_update_offloaded finds the state on the host. */
+enum { PS_HOST_FLAT = 0, PS_HOST_PACKED = 1 };
+
 /* Offloaded optimizer state (Table 2, ZeRO-Offload: Theta and Omega in mode O,
  * G sharded): master, m, v and the 16-bit parameters of this shard live in pinned
  * HOST memory and stream through the device in buckets. */
 typedef struct ps_offload_plan_t {
-    float *host_master;     /* pinned HOST, len floats, updated in place                 */
+    float *host_master;     /* pinned HOST, len floats, updated in place (PS_HOST_FLAT)  */
     float *host_m;          /* pinned HOST, len floats                                   */
     float *host_v;          /* pinned HOST, len floats                                   */
     void *host_param_out;   /* pinned HOST, len 16-bit elements of type param_dtype:
@@ -221,6 +224,16 @@ typedef struct ps_offload_plan_t {
     void *h2d_stream;       /* hipStream_t; the three streams must differ                */
     void *compute_stream;
     void *d2h_stream;
+    int32_t host_layout;    /* PS_HOST_FLAT (0, a zeroed field): the four host_* arrays above.
+                               PS_HOST_PACKED: host_packed below, the four host_* are unused */
+    int32_t reserved;       /* must be 0                                                 */
+    void *host_packed;      /* pinned HOST, ceil(len / bucket_elems) * 14 * bucket_elems
+                               bytes, 16-byte aligned: bucket b occupies the 14 *
+                               bucket_elems bytes from byte b * 14 * bucket_elems on, laid
+                               out like a DEVICE slot: master | m | v (FP32, bucket_elems
+                               each) | 16-bit parameters (bucket_elems).  A whole bucket
+                               then moves as ONE copy per direction (12 bucket_elems bytes
+                               up, 14 bucket_elems bytes down) instead of three and four */
 } ps_offload_plan_t;
 
 typedef struct ps_device_info_t {
@@ -254,14 +267,15 @@ ps_status_t ps_spec_preset(const char *name, uint32_t n_devices, uint32_t shard_
  * PS_ERANGE if a division by N is not exact or a result overflows 64 bits. */
 ps_status_t ps_cost_eval(const ps_spec_t *spec, ps_cost_t *cost);
 
-/* Global-norm clip coefficient, in binary64: min(1, max_norm / (sqrt(sumsq_local
+/* Global-norm clip coefficient (gradient clipping is not in the paper; the named
+ * 13B workload asks for it), in binary64: min(1, max_norm / (sqrt(sumsq_local
  * + sumsq_others) + 1e-6)), the sums being those of the squared mean gradient
  * over this device's shard and over all other devices' shards.  A non-finite
  * or negative sum, or max_norm <= 0, gives NaN (the caller should skip the
  * step).  Pass the result as ps_adamw_t.clip_coef. */
 double ps_clip_coef(double sumsq_local, double sumsq_others, double max_norm);
 
-/* The same coefficient formed on the device, for callers that keep the two
+/* The same coefficient (again not in the paper) formed on the device, for callers that keep the two
  * phases of a clipped step on the stream: *coef_out (DEVICE float) =
  * ps_clip_coef(*sumsq_local, sumsq_others ? *sumsq_others : 0, max_norm) rounded
  * to binary32, NaN where ps_clip_coef gives NaN.  sumsq_local and sumsq_others
@@ -386,9 +400,13 @@ ps_status_t ps_step_accumulate(const ps_spec_t *spec, const ps_grads_t *grads, f
  * this shard's slice of contribution r in DEVICE memory (n_contrib ==
  * n_devices, or 1 with PS_F32).  Per bucket: three host-to-device copies on
  * h2d_stream, the update kernel on compute_stream, four device-to-host copies on
- * d2h_stream, ordered by events; nothing waits on the host.  The caller
- * synchronises d2h_stream before reading the host buffers.  The path is bound by
- * the host link (12 bytes in, 14 bytes out per element), not by HBM. */
+ * d2h_stream, ordered by events; nothing waits on the host.  Before it returns the
+ * call makes h2d_stream wait for its own last downloads, so a following call with
+ * the same streams may be enqueued right away: its uploads (which reuse the slots
+ * and read the host ranges this call writes) start only when this step's results
+ * have landed.  The caller synchronises d2h_stream before reading the host buffers
+ * itself.  The path is bound by the host link (12 bytes in, 14 bytes out per
+ * element), not by HBM. */
 ps_status_t ps_step_update_offloaded(const ps_spec_t *spec, const ps_adamw_t *hp,
                                      const ps_offload_plan_t *plan, const ps_grads_t *grads);
 

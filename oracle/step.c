@@ -170,13 +170,12 @@ void oracle_derive_scalars(double lr, double beta1, double beta2, double eps,
 
 /* Contribution r's element e, widened to binary32.  All contributions carry
  * one data type (Theorem 4: identical data types); dtype 0 = bf16, 1 = binary32,
- * 2 = binary16 (in the functions below the parameter keeps its first name,
- * is_f32, from when there were two). */
-static float contribution(const void *const *g, int is_f32, uint32_t r, uint64_t e)
+ * 2 = binary16. */
+static float contribution(const void *const *g, int dtype, uint32_t r, uint64_t e)
 {
-    if (is_f32 == 1)
+    if (dtype == 1)
         return ((const float *)g[r])[e];
-    if (is_f32 == 2)
+    if (dtype == 2)
         return widen_f16(((const uint16_t *)g[r])[e]);
     return widen_bf16(((const uint16_t *)g[r])[e]);
 }
@@ -184,13 +183,13 @@ static float contribution(const void *const *g, int is_f32, uint32_t r, uint64_t
 /* The reduce-scatter result before the mean (Section 2.3 "Reduce-Scatter";
  * Theorem 2 part 2): acc[e] = ((g_0[e] + g_1[e]) + g_2[e]) + ... in binary32,
  * device index ascending. */
-void oracle_reduce_sum(const void *const *g, uint32_t n_contrib, int is_f32,
+void oracle_reduce_sum(const void *const *g, uint32_t n_contrib, int dtype,
                        float *acc_out, uint64_t lo, uint64_t hi)
 {
     for (uint64_t e = lo; e < hi; ++e) {
-        float acc = contribution(g, is_f32, 0, e);
+        float acc = contribution(g, dtype, 0, e);
         for (uint32_t r = 1; r < n_contrib; ++r)
-            acc = acc + contribution(g, is_f32, r, e);
+            acc = acc + contribution(g, dtype, r, e);
         acc_out[e] = acc;
     }
 }
@@ -199,13 +198,13 @@ void oracle_reduce_sum(const void *const *g, uint32_t n_contrib, int is_f32,
  * before one synchronisation).  Each call adds one micro-batch: its N
  * contributions are summed in the fixed order, then that sum is added to the
  * running binary32 total; the first micro-batch (overwrite != 0) stores its sum. */
-void oracle_accumulate(const void *const *g, uint32_t n_contrib, int is_f32,
+void oracle_accumulate(const void *const *g, uint32_t n_contrib, int dtype,
                        float *accum, int overwrite, uint64_t lo, uint64_t hi)
 {
     for (uint64_t e = lo; e < hi; ++e) {
-        float acc = contribution(g, is_f32, 0, e);
+        float acc = contribution(g, dtype, 0, e);
         for (uint32_t r = 1; r < n_contrib; ++r)
-            acc = acc + contribution(g, is_f32, r, e);
+            acc = acc + contribution(g, dtype, r, e);
         accum[e] = overwrite ? acc : accum[e] + acc;
     }
 }
@@ -213,14 +212,14 @@ void oracle_accumulate(const void *const *g, uint32_t n_contrib, int is_f32,
 /* Mean gradient g = acc * gs and the sum of its squares, the latter summed
  * sequentially in binary64 (each product of two widened binary32 values is
  * exact in binary64).  g_out may be NULL.  Returns the sum over [lo, hi). */
-double oracle_mean_sumsq(const void *const *g, uint32_t n_contrib, int is_f32,
+double oracle_mean_sumsq(const void *const *g, uint32_t n_contrib, int dtype,
                          float gs, float *g_out, uint64_t lo, uint64_t hi)
 {
     double ss = 0.0;
     for (uint64_t e = lo; e < hi; ++e) {
-        float acc = contribution(g, is_f32, 0, e);
+        float acc = contribution(g, dtype, 0, e);
         for (uint32_t r = 1; r < n_contrib; ++r)
-            acc = acc + contribution(g, is_f32, r, e);
+            acc = acc + contribution(g, dtype, r, e);
         float gm = acc * gs;
         if (g_out)
             g_out[e] = gm;
@@ -243,14 +242,14 @@ double oracle_clip_coef(double sumsq_local, double sumsq_others, double max_norm
 /* One step on elements [lo, hi) of the full-length arrays.  theta, m, v are
  * updated in place; p receives the 16-bit image of the new theta: bf16, or
  * binary16 when p_f16 != 0. */
-void oracle_step_f32(const void *const *g, uint32_t n_contrib, int is_f32,
+void oracle_step_f32(const void *const *g, uint32_t n_contrib, int dtype,
                      const oracle_scalars *s, float *theta, float *m, float *v,
                      uint16_t *p, int p_f16, uint64_t lo, uint64_t hi)
 {
     for (uint64_t e = lo; e < hi; ++e) {
-        float acc = contribution(g, is_f32, 0, e);
+        float acc = contribution(g, dtype, 0, e);
         for (uint32_t r = 1; r < n_contrib; ++r)
-            acc = acc + contribution(g, is_f32, r, e);
+            acc = acc + contribution(g, dtype, r, e);
         float gm = acc * s->gs;
         gm = gm * s->cc;
         float m1 = fmaf(s->b1, m[e], s->omb1 * gm);
@@ -271,7 +270,7 @@ void oracle_step_f32(const void *const *g, uint32_t n_contrib, int is_f32,
 /* Same formulas with every scalar and operation in binary64 and the binary32
  * inputs widened; nothing is rounded to binary32.  Outputs go to separate
  * double arrays. */
-void oracle_step_f64(const void *const *g, uint32_t n_contrib, int is_f32,
+void oracle_step_f64(const void *const *g, uint32_t n_contrib, int dtype,
                      double lr, double beta1, double beta2, double eps,
                      double weight_decay, uint64_t t, double grad_scale,
                      double clip_coef, const float *theta, const float *m,
@@ -285,7 +284,7 @@ void oracle_step_f64(const void *const *g, uint32_t n_contrib, int is_f32,
     for (uint64_t e = lo; e < hi; ++e) {
         double acc = 0.0;
         for (uint32_t r = 0; r < n_contrib; ++r)
-            acc += (double)contribution(g, is_f32, r, e);
+            acc += (double)contribution(g, dtype, r, e);
         double gm = acc * gs * cc;
         double m1 = beta1 * (double)m[e] + (1.0 - beta1) * gm;
         double v1 = beta2 * (double)v[e] + (1.0 - beta2) * gm * gm;
@@ -306,14 +305,14 @@ void oracle_step_f64(const void *const *g, uint32_t n_contrib, int is_f32,
 /* Sums for the relative gradient difference ||a - b|| / ||a||: out[0] = sum of
  * (a-b)^2, out[1] = sum of a^2, both sequential in binary64 (the difference of
  * two widened 16- or 32-bit values is exact in binary64). */
-void oracle_diff_sumsq(const void *a, const void *b, int is_f32, uint64_t lo,
+void oracle_diff_sumsq(const void *a, const void *b, int dtype, uint64_t lo,
                        uint64_t hi, double *out)
 {
     const void *pa[1] = {a}, *pb[1] = {b};
     double sd = 0.0, sa = 0.0;
     for (uint64_t e = lo; e < hi; ++e) {
-        double x = (double)contribution(pa, is_f32, 0, e);
-        double y = (double)contribution(pb, is_f32, 0, e);
+        double x = (double)contribution(pa, dtype, 0, e);
+        double y = (double)contribution(pb, dtype, 0, e);
         double d = x - y;
         sd += d * d;
         sa += x * x;

@@ -140,26 +140,26 @@ def f16_rne_bits(u32):
 
 
 def reduce_sum(grads, lo=0, hi=None):
-    ptrs, n_c, is_f32, n = _contrib_ptrs(grads)
+    ptrs, n_c, dtype, n = _contrib_ptrs(grads)
     hi = n if hi is None else hi
     acc = np.zeros(n, dtype=np.float32)
-    lib().oracle_reduce_sum(ptrs, n_c, is_f32, acc.ctypes.data, lo, hi)
+    lib().oracle_reduce_sum(ptrs, n_c, dtype, acc.ctypes.data, lo, hi)
     return acc
 
 
 def accumulate(grads, accum, overwrite, lo=0, hi=None):
     """accum[lo:hi] (+)= fixed-order sum of one micro-batch's contributions, in place."""
-    ptrs, n_c, is_f32, n = _contrib_ptrs(grads)
+    ptrs, n_c, dtype, n = _contrib_ptrs(grads)
     hi = n if hi is None else hi
     _check(accum, np.float32, n)
-    lib().oracle_accumulate(ptrs, n_c, is_f32, accum.ctypes.data, int(bool(overwrite)), lo, hi)
+    lib().oracle_accumulate(ptrs, n_c, dtype, accum.ctypes.data, int(bool(overwrite)), lo, hi)
 
 
 def mean_sumsq(grads, gs, lo=0, hi=None, want_mean=True):
-    ptrs, n_c, is_f32, n = _contrib_ptrs(grads)
+    ptrs, n_c, dtype, n = _contrib_ptrs(grads)
     hi = n if hi is None else hi
     gm = np.zeros(n, dtype=np.float32) if want_mean else None
-    ss = lib().oracle_mean_sumsq(ptrs, n_c, is_f32, float(np.float32(gs)),
+    ss = lib().oracle_mean_sumsq(ptrs, n_c, dtype, float(np.float32(gs)),
                                  gm.ctypes.data if want_mean else None, lo, hi)
     return gm, ss
 
@@ -171,7 +171,7 @@ def clip_coef(sumsq_local, sumsq_others, max_norm):
 def step_f32(grads, scalars, theta, m, v, p, lo=0, hi=None):
     """In-place binary32 step on [lo, hi) of the full-length arrays.  p is uint16 (receives
     bf16 bit patterns) or float16 (receives the binary16 image)."""
-    ptrs, n_c, is_f32, n = _contrib_ptrs(grads)
+    ptrs, n_c, dtype, n = _contrib_ptrs(grads)
     hi = n if hi is None else hi
     for a in (theta, m, v):
         _check(a, np.float32, n)
@@ -179,19 +179,19 @@ def step_f32(grads, scalars, theta, m, v, p, lo=0, hi=None):
     _check(p, np.float16 if p_f16 else np.uint16, n)
     if not (0 <= lo <= hi <= n):
         raise ValueError("bad range")
-    lib().oracle_step_f32(ptrs, n_c, is_f32, C.byref(scalars), theta.ctypes.data,
+    lib().oracle_step_f32(ptrs, n_c, dtype, C.byref(scalars), theta.ctypes.data,
                           m.ctypes.data, v.ctypes.data, p.ctypes.data, int(p_f16), lo, hi)
 
 
 def step_f64(grads, lr, beta1, beta2, eps, weight_decay, t, theta, m, v,
              grad_scale=0.0, clip_coef=0.0, lo=0, hi=None):
     """Binary64 pass; returns (theta', m', v') as float64 arrays (zeros outside [lo,hi))."""
-    ptrs, n_c, is_f32, n = _contrib_ptrs(grads)
+    ptrs, n_c, dtype, n = _contrib_ptrs(grads)
     hi = n if hi is None else hi
     for a in (theta, m, v):
         _check(a, np.float32, n)
     to, mo, vo = (np.zeros(n, dtype=np.float64) for _ in range(3))
-    lib().oracle_step_f64(ptrs, n_c, is_f32, lr, beta1, beta2, eps, weight_decay, int(t),
+    lib().oracle_step_f64(ptrs, n_c, dtype, lr, beta1, beta2, eps, weight_decay, int(t),
                           float(grad_scale), float(clip_coef), theta.ctypes.data,
                           m.ctypes.data, v.ctypes.data, to.ctypes.data, mo.ctypes.data,
                           vo.ctypes.data, lo, hi)
@@ -200,10 +200,10 @@ def step_f64(grads, lr, beta1, beta2, eps, weight_decay, t, theta, m, v,
 
 def diff_sumsq(a, b, lo=0, hi=None):
     """(sum (a-b)^2, sum a^2) over [lo, hi), sequential binary64."""
-    ptrs, _, is_f32, n = _contrib_ptrs([a, b])
+    ptrs, _, dtype, n = _contrib_ptrs([a, b])
     hi = n if hi is None else hi
     out = (C.c_double * 2)()
-    lib().oracle_diff_sumsq(a.ctypes.data, b.ctypes.data, is_f32, lo, hi, out)
+    lib().oracle_diff_sumsq(a.ctypes.data, b.ctypes.data, dtype, lo, hi, out)
     return out[0], out[1]
 
 

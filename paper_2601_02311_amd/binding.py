@@ -15,7 +15,7 @@ import torch  # noqa: F401
 from . import build as _build
 
 __all__ = [
-    "PS_R", "PS_S", "PS_SG", "PS_M", "PS_O", "PS_BF16", "PS_F32", "PS_F16", "PS_MAX_CONTRIB", "PS_COPY_KERNEL", "PS_COPY_MEMCPY", "PS_COPY_NONE", "PS_SCHED_AUTO", "PS_SCHED_OVERLAP", "PS_SCHED_ALTERNATE",
+    "PS_R", "PS_S", "PS_SG", "PS_M", "PS_O", "PS_BF16", "PS_F32", "PS_F16", "PS_MAX_CONTRIB", "PS_COPY_KERNEL", "PS_COPY_MEMCPY", "PS_COPY_NONE", "PS_SCHED_AUTO", "PS_SCHED_OVERLAP", "PS_SCHED_ALTERNATE", "PS_HOST_FLAT", "PS_HOST_PACKED",
     "PS_OK", "PS_EINVAL", "PS_EUNSUPPORTED", "PS_EALIGN", "PS_ERANGE", "PS_ENODEVICE", "PS_EHIP",
     "PsError", "ps_spec_t", "ps_cost_t", "ps_adamw_t", "ps_shard_t", "ps_grads_t",
     "ps_bucket_plan_t", "ps_offload_plan_t", "ps_device_info_t", "library", "library_path",
@@ -34,6 +34,7 @@ PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
 PS_BF16, PS_F32, PS_F16 = 0, 1, 2
 PS_COPY_KERNEL, PS_COPY_MEMCPY, PS_COPY_NONE = 0, 1, 2
 PS_SCHED_AUTO, PS_SCHED_OVERLAP, PS_SCHED_ALTERNATE = 0, 1, 2
+PS_HOST_FLAT, PS_HOST_PACKED = 0, 1
 PS_MAX_CONTRIB = 16
 PS_STATIC_MAX_ELEMS = 1 << 30
 (PS_OK, PS_EINVAL, PS_EUNSUPPORTED, PS_EALIGN, PS_ERANGE, PS_ENODEVICE, PS_EHIP) = range(7)
@@ -106,7 +107,8 @@ class ps_offload_plan_t(C.Structure):
                 ("host_param_out", C.c_void_p), ("len", C.c_uint64), ("valid_len", C.c_uint64),
                 ("bucket_elems", C.c_uint64), ("n_slots", C.c_uint32), ("param_dtype", C.c_int32),
                 ("slot", C.c_void_p * 3), ("h2d_stream", C.c_void_p),
-                ("compute_stream", C.c_void_p), ("d2h_stream", C.c_void_p)]
+                ("compute_stream", C.c_void_p), ("d2h_stream", C.c_void_p),
+                ("host_layout", C.c_int32), ("reserved", C.c_int32), ("host_packed", C.c_void_p)]
 
 
 class ps_device_info_t(C.Structure):
@@ -125,10 +127,15 @@ def library_path():
 
 
 def library():
-    """The loaded shared library.  Built first only if no build exists."""
+    """The loaded shared library.  A library that is missing, or that was built from other
+    sources than the ones on disk (content hash recorded at build time), is rebuilt first;
+    where that is impossible the import fails: a stale binary is never loaded silently."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_build.LIB):
+        if _build.stale():
+            if not os.path.exists(_build.HIPCC):
+                raise ImportError("%s is missing or was built from other sources, and there is "
+                                  "no %s to rebuild it" % (_build.LIB, _build.HIPCC))
             _build.build()
         L = C.CDLL(_build.LIB)
         L.ps_abi_version.restype = C.c_uint32

@@ -27,13 +27,28 @@ FLAGS = [
 ]
 
 
-def stale() -> bool:
-    if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
+BUILD_ID = os.path.join(HERE, "libps_step.build_id")   # what the library was built from
+
+
+def source_id() -> str:
+    """Hash of everything the library is compiled from (sources, headers, flags)."""
+    import hashlib
+    h = hashlib.sha256(" ".join(FLAGS[:-4]).encode())
     deps = [os.path.join(CSRC, f) for f in SOURCES + HEADERS]
     deps.append(os.path.join(ROOT, "include", "ps_step.h"))
-    return any(os.path.getmtime(d) > t for d in deps)
+    for d in deps:
+        with open(d, "rb") as f:
+            h.update(os.path.basename(d).encode() + b"\0" + f.read())
+    return h.hexdigest()
+
+
+def stale() -> bool:
+    """True when there is no library, or when it was built from other sources than the
+    ones on disk now (compared by content, not by time stamp)."""
+    if not os.path.exists(LIB) or not os.path.exists(BUILD_ID):
+        return True
+    with open(BUILD_ID) as f:
+        return f.read().strip() != source_id()
 
 
 def build(verbose: bool = False) -> str:
@@ -41,8 +56,12 @@ def build(verbose: bool = False) -> str:
     cmd = [HIPCC, *FLAGS, "-x", "hip", *[os.path.join(CSRC, s) for s in SOURCES], "-o", tmp]
     if verbose:
         print(" ".join(cmd), file=sys.stderr)
+    sid = source_id()
     subprocess.run(cmd, check=True)
     os.replace(tmp, LIB)
+    with open(BUILD_ID + ".tmp.%d" % os.getpid(), "w") as f:
+        f.write(sid + "\n")
+    os.replace(BUILD_ID + ".tmp.%d" % os.getpid(), BUILD_ID)
     return LIB
 
 

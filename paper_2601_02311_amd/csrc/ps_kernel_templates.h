@@ -527,9 +527,8 @@ struct ScanArgs {
     const void *b;
     void *partials0; // per-workgroup partial sums (first quantity)
     void *partials1; // second quantity, where there is one
-    uint64_t n_tiles; // tail kernels: leftover units; group kernels take their extent from the grid
+    uint64_t n_tiles; // finishing kernels: leftover units; group kernels take their extent from the grid
     uint64_t first_index;
-    uint32_t partial_slot;
 };
 
 // The scans only read, and a read-only stream is fastest on this part with large
@@ -584,24 +583,64 @@ __global__ __launch_bounds__(kScanThreads) void diff_sumsq_tiles(const ScanArgs 
     }
 }
 
-// Tail: what is left (less than one group), one element per lane, one pair of
-// partials per workgroup of kThreads lanes from slot partial_slot on.
+// Last stage of the difference scan, one workgroup: adds the n_partials pairs the groups
+// left (lane-strided, fixed order), then the elements past the last whole group (fewer
+// than one group's worth; s.a and s.b point at the first of them), runs the block tree
+// once and stores the two totals, or adds them to what out2 holds.
 template <typename G>
-__global__ __launch_bounds__(kThreads) void diff_sumsq_tail(const ScanArgs s)
+__global__ __launch_bounds__(kScanThreads) void diff_sumsq_finish(const ScanArgs s, uint64_t n_partials,
+                                                                  double *out2, int accumulate)
 {
     double both[2] = {0.0, 0.0};
-    const uint64_t e = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (e < s.n_tiles) {
+    const double *p0 = reinterpret_cast<const double *>(s.partials0);
+    const double *p1 = reinterpret_cast<const double *>(s.partials1);
+    // four lane-strided rows at a time, all eight loads in flight; the order is fixed
+    uint64_t i = threadIdx.x;
+    for (; i + 3 * kScanThreads < n_partials; i += 4 * kScanThreads) {
+        const double a0 = p0[i], a1 = p0[i + kScanThreads], a2 = p0[i + 2 * kScanThreads],
+                     a3 = p0[i + 3 * kScanThreads];
+        const double b0 = p1[i], b1 = p1[i + kScanThreads], b2 = p1[i + 2 * kScanThreads],
+                     b3 = p1[i + 3 * kScanThreads];
+        both[0] += (a0 + a1) + (a2 + a3);
+        both[1] += (b0 + b1) + (b2 + b3);
+    }
+    for (; i < n_partials; i += kScanThreads) {
+        both[0] += p0[i];
+        both[1] += p1[i];
+    }
+    for (uint64_t e = threadIdx.x; e < s.n_tiles; e += kScanThreads) {
         const double x = (double)load_contrib1<G>(s.a, e), y = (double)load_contrib1<G>(s.b, e);
         const double d = x - y;
-        both[0] = d * d;
-        both[1] = x * x;
+        both[0] += d * d;
+        both[1] += x * x;
     }
-    block_sum_once<double, kThreads, 2>(both);
+    block_sum_once<double, kScanThreads, 2>(both);
     if (threadIdx.x == 0) {
-        reinterpret_cast<double *>(s.partials0)[s.partial_slot + blockIdx.x] = both[0];
-        reinterpret_cast<double *>(s.partials1)[s.partial_slot + blockIdx.x] = both[1];
+        out2[0] = accumulate ? out2[0] + both[0] : both[0];
+        out2[1] = accumulate ? out2[1] + both[1] : both[1];
     }
+}
+
+// Intermediate stage for very long buffers: workgroup (b, q) adds the contiguous slice
+// [b*per, min((b+1)*per, n)) of quantity q's partials into its second-level slot b.
+struct FoldArgs {
+    const void *in[2];
+    void *out[2];
+};
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void fold_partials_q(const FoldArgs f, uint64_t n, uint64_t per)
+{
+    const T *in = reinterpret_cast<const T *>(f.in[blockIdx.y]);
+    T *out = reinterpret_cast<T *>(f.out[blockIdx.y]);
+    const uint64_t lo = (uint64_t)blockIdx.x * per;
+    const uint64_t hi = lo + per < n ? lo + per : n;
+    T ss = 0;
+    for (uint64_t i = lo + threadIdx.x; i < hi; i += kThreads)
+        ss += in[i];
+    const T t = block_sum(ss);
+    if (threadIdx.x == 0)
+        out[blockIdx.x] = t;
 }
 
 // One word's contribution to the checksum: the splitmix64 output function of
@@ -648,16 +687,24 @@ __global__ __launch_bounds__(kScanThreads) void checksum_tiles(const ScanArgs s)
         reinterpret_cast<uint64_t *>(s.partials0)[blockIdx.x] = one[0];
 }
 
-// Tail: one word per lane, one partial per workgroup from slot partial_slot on.
-__global__ __launch_bounds__(kThreads) void checksum_tail(const ScanArgs s)
+// Last stage of the checksum, one workgroup: the groups' partials, then the words past the
+// last whole group (s.a points at the first of them, s.first_index is its index), all
+// modulo 2^64, stored or added to *out.
+__global__ __launch_bounds__(kScanThreads) void checksum_finish(const ScanArgs s, uint64_t n_partials,
+                                                                uint64_t *out, int accumulate)
 {
     uint64_t one[1] = {0};
-    const uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i < s.n_tiles)
-        one[0] = checksum_term(reinterpret_cast<const uint64_t *>(s.a)[i], s.first_index + i);
-    block_sum_once<uint64_t, kThreads, 1>(one);
+    const uint64_t *p0 = reinterpret_cast<const uint64_t *>(s.partials0);
+    uint64_t i = threadIdx.x;
+    for (; i + 3 * kScanThreads < n_partials; i += 4 * kScanThreads)
+        one[0] += (p0[i] + p0[i + kScanThreads]) + (p0[i + 2 * kScanThreads] + p0[i + 3 * kScanThreads]);
+    for (; i < n_partials; i += kScanThreads)
+        one[0] += p0[i];
+    for (i = threadIdx.x; i < s.n_tiles; i += kScanThreads)
+        one[0] += checksum_term(reinterpret_cast<const uint64_t *>(s.a)[i], s.first_index + i);
+    block_sum_once<uint64_t, kScanThreads, 1>(one);
     if (threadIdx.x == 0)
-        reinterpret_cast<uint64_t *>(s.partials0)[s.partial_slot + blockIdx.x] = one[0];
+        *out = accumulate ? *out + one[0] : one[0];
 }
 
 // Plain copy with the update kernel's access shape: one wave per 1 KiB, 16 B

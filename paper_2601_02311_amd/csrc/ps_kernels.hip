@@ -361,15 +361,43 @@ int launch_clip_coef(const double *sumsq_local, const double *sumsq_others, doub
     return (int)hipGetLastError();
 }
 
-// Workspace of the verification scans, in 8-byte slots, for a buffer of `bytes`
-// bytes: two partial arrays (one partial per 32 KiB at most, plus the tail's: one
-// per kThreads of the fewer than 16384 elements or 8192 words left), each with
-// its own second level.
+// Workspace of the verification scans, in 8-byte slots, for a buffer of `bytes` bytes:
+// two partial arrays (one partial per 32 KiB at most), each with its own second level.
 uint64_t verify_workspace_slots(uint64_t bytes)
 {
     const uint64_t group_bytes = (uint64_t)kScanThreads * kDiffVecs * 16;
-    const uint64_t tail_partials = group_bytes / 2 / kThreads; // narrowest element: 2 bytes
-    return 2 * (kFoldBlocks + bytes / group_bytes + tail_partials + 2);
+    return 2 * (kFoldBlocks + bytes / group_bytes + 2);
+}
+
+// The single finishing workgroup adds up to kFinishDirect partials by itself (a few
+// microseconds).  More than that go through one folding launch first: slices of at least
+// kFoldSlice partials, at most kFoldBlocks of them, each added by its own workgroup (both
+// quantities of the difference scan in the same launch).  The slicing depends only on the
+// number of partials, so the tree is the same on every run.
+constexpr uint64_t kFinishDirect = 4096;
+constexpr uint64_t kFoldSlice = 2048;
+
+template <typename T>
+static int fold_for_finish(ScanArgs &s, void *l2a, void *l2b, uint64_t &n_partials, int quantities,
+                           hipStream_t st)
+{
+    if (n_partials <= kFinishDirect)
+        return 0;
+    uint64_t per = (n_partials + kFoldBlocks - 1) / kFoldBlocks;
+    if (per < kFoldSlice)
+        per = kFoldSlice;
+    const uint32_t blocks = (uint32_t)((n_partials + per - 1) / per);
+    FoldArgs f;
+    f.in[0] = s.partials0;
+    f.in[1] = s.partials1;
+    f.out[0] = l2a;
+    f.out[1] = l2b;
+    hipLaunchKernelGGL((fold_partials_q<T>), dim3(blocks, quantities), dim3(kThreads), 0, st, f,
+                       n_partials, per);
+    s.partials0 = l2a;
+    s.partials1 = l2b;
+    n_partials = blocks;
+    return (int)hipGetLastError();
 }
 
 template <typename G>
@@ -377,7 +405,7 @@ static int launch_diff_t(const void *a, const void *b, uint64_t count, double *o
                          int accumulate, uint64_t *workspace, uint64_t slots, hipStream_t st)
 {
     constexpr uint64_t kGroupElems = (uint64_t)kScanThreads * kDiffVecs * (16 / sizeof(G));
-    const uint64_t groups = count / kGroupElems; // whole groups; the tail takes the rest
+    const uint64_t groups = count / kGroupElems; // whole groups; the finishing workgroup takes the rest
     const uint64_t body = groups * kGroupElems;
     if (groups > kMaxGrid)
         return (int)hipErrorInvalidConfiguration;
@@ -390,33 +418,24 @@ static int launch_diff_t(const void *a, const void *b, uint64_t count, double *o
     s.partials0 = l1a;
     s.partials1 = l1b;
     s.first_index = 0;
-    s.partial_slot = 0;
-    uint64_t n_partials = 0;
+    s.n_tiles = groups;
+    uint64_t n_partials = groups;
     if (groups) {
-        s.n_tiles = groups;
         hipLaunchKernelGGL((diff_sumsq_tiles<G>), dim3((uint32_t)groups), dim3(kScanThreads), 0,
                            st, s);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return (int)e;
-        n_partials = groups;
     }
-    if (count > body) {
-        s.a = advance<G>(a, body);
-        s.b = advance<G>(b, body);
-        s.n_tiles = count - body;
-        s.partial_slot = (uint32_t)n_partials;
-        const uint32_t blocks = (uint32_t)((count - body + kThreads - 1) / kThreads);
-        hipLaunchKernelGGL((diff_sumsq_tail<G>), dim3(blocks), dim3(kThreads), 0, st, s);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess)
-            return (int)e;
-        n_partials += blocks;
-    }
-    int e = fold_to_one(l1a, l2a, n_partials, out2, accumulate, st);
-    if (e != 0)
-        return e;
-    return fold_to_one(l1b, l2b, n_partials, out2 + 1, accumulate, st);
+    int fe = fold_for_finish<double>(s, l2a, l2b, n_partials, 2, st);
+    if (fe != 0)
+        return fe;
+    s.a = advance<G>(a, body);
+    s.b = advance<G>(b, body);
+    s.n_tiles = count - body;
+    hipLaunchKernelGGL((diff_sumsq_finish<G>), dim3(1), dim3(kScanThreads), 0, st, s, n_partials,
+                       out2, accumulate);
+    return (int)hipGetLastError();
 }
 
 int launch_diff_sumsq(int dtype, const void *a, const void *b, uint64_t count, double *out2,
@@ -436,7 +455,7 @@ int launch_checksum(const void *buf, uint64_t n_words, uint64_t first_index, uin
 {
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     constexpr uint64_t kGroupWords = (uint64_t)kScanThreads * kChecksumVecs * 2;
-    const uint64_t groups = n_words / kGroupWords; // whole groups; the tail takes the rest
+    const uint64_t groups = n_words / kGroupWords; // whole groups; the finishing workgroup takes the rest
     const uint64_t body = groups * kGroupWords;
     if (groups > kMaxGrid)
         return (int)hipErrorInvalidConfiguration;
@@ -447,29 +466,23 @@ int launch_checksum(const void *buf, uint64_t n_words, uint64_t first_index, uin
     s.partials0 = l1;
     s.partials1 = nullptr;
     s.first_index = first_index;
-    s.partial_slot = 0;
-    uint64_t n_partials = 0;
+    s.n_tiles = groups;
+    uint64_t n_partials = groups;
     if (groups) {
-        s.n_tiles = groups;
         hipLaunchKernelGGL(checksum_tiles, dim3((uint32_t)groups), dim3(kScanThreads), 0, st, s);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return (int)e;
-        n_partials = groups;
     }
-    if (n_words > body) {
-        s.a = reinterpret_cast<const uint64_t *>(buf) + body;
-        s.first_index = first_index + body;
-        s.n_tiles = n_words - body;
-        s.partial_slot = (uint32_t)n_partials;
-        const uint32_t blocks = (uint32_t)((n_words - body + kThreads - 1) / kThreads);
-        hipLaunchKernelGGL(checksum_tail, dim3(blocks), dim3(kThreads), 0, st, s);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess)
-            return (int)e;
-        n_partials += blocks;
-    }
-    return fold_to_one(l1, l2, n_partials, out, accumulate, st);
+    int fe = fold_for_finish<uint64_t>(s, l2, nullptr, n_partials, 1, st);
+    if (fe != 0)
+        return fe;
+    s.a = reinterpret_cast<const uint64_t *>(buf) + body;
+    s.first_index = first_index + body;
+    s.n_tiles = n_words - body;
+    hipLaunchKernelGGL(checksum_finish, dim3(1), dim3(kScanThreads), 0, st, s, n_partials, out,
+                       accumulate);
+    return (int)hipGetLastError();
 }
 
 int launch_copy(void *dst, const void *src, uint64_t bytes, void *stream)

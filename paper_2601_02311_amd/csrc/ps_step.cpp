@@ -843,7 +843,14 @@ ps_status_t ps_step_update_offloaded(const ps_spec_t *spec, const ps_adamw_t *hp
         set_error("plan or grads is NULL");
         return PS_EINVAL;
     }
-    if (!plan->host_master || !plan->host_m || !plan->host_v || !plan->host_param_out) {
+    if ((plan->host_layout != PS_HOST_FLAT && plan->host_layout != PS_HOST_PACKED) ||
+        plan->reserved != 0) {
+        set_error("host_layout must be PS_HOST_FLAT or PS_HOST_PACKED, reserved 0");
+        return PS_EINVAL;
+    }
+    const bool packed = plan->host_layout == PS_HOST_PACKED;
+    if (packed ? !plan->host_packed
+               : (!plan->host_master || !plan->host_m || !plan->host_v || !plan->host_param_out)) {
         set_error("plan has a NULL host buffer");
         return PS_EINVAL;
     }
@@ -870,8 +877,9 @@ ps_status_t ps_step_update_offloaded(const ps_spec_t *spec, const ps_adamw_t *hp
         set_error("bucket_elems must be a positive multiple of 8");
         return PS_EALIGN;
     }
-    if (!aligned16(plan->host_master) || !aligned16(plan->host_m) || !aligned16(plan->host_v) ||
-        !aligned16(plan->host_param_out)) {
+    if (packed ? !aligned16(plan->host_packed)
+               : (!aligned16(plan->host_master) || !aligned16(plan->host_m) ||
+                  !aligned16(plan->host_v) || !aligned16(plan->host_param_out))) {
         set_error("host buffer not 16-byte aligned");
         return PS_EALIGN;
     }
@@ -932,9 +940,21 @@ ps_status_t ps_step_update_offloaded(const ps_spec_t *spec, const ps_adamw_t *hp
         // upload: the slot is free once bucket b - S has been written back
         if (b >= S)
             PS_TRY(hipStreamWaitEvent(up, drained[k], 0));
-        PS_TRY(hipMemcpyAsync(d_master, plan->host_master + lo, cnt * 4, hipMemcpyHostToDevice, up));
-        PS_TRY(hipMemcpyAsync(d_m, plan->host_m + lo, cnt * 4, hipMemcpyHostToDevice, up));
-        PS_TRY(hipMemcpyAsync(d_v, plan->host_v + lo, cnt * 4, hipMemcpyHostToDevice, up));
+        // where this bucket's four arrays lie on the host
+        char *h_pack = packed ? reinterpret_cast<char *>(plan->host_packed) + b * 14 * B : nullptr;
+        float *h_master = packed ? reinterpret_cast<float *>(h_pack) : plan->host_master + lo;
+        float *h_m = packed ? reinterpret_cast<float *>(h_pack + 4 * B) : plan->host_m + lo;
+        float *h_v = packed ? reinterpret_cast<float *>(h_pack + 8 * B) : plan->host_v + lo;
+        uint16_t *h_out = packed ? reinterpret_cast<uint16_t *>(h_pack + 12 * B)
+                                 : reinterpret_cast<uint16_t *>(plan->host_param_out) + lo;
+        const bool one_copy = packed && cnt == B; // host and slot layouts coincide
+        if (one_copy) {
+            PS_TRY(hipMemcpyAsync(slot, h_pack, 12 * B, hipMemcpyHostToDevice, up));
+        } else {
+            PS_TRY(hipMemcpyAsync(d_master, h_master, cnt * 4, hipMemcpyHostToDevice, up));
+            PS_TRY(hipMemcpyAsync(d_m, h_m, cnt * 4, hipMemcpyHostToDevice, up));
+            PS_TRY(hipMemcpyAsync(d_v, h_v, cnt * 4, hipMemcpyHostToDevice, up));
+        }
         PS_TRY(hipEventRecord(loaded[k], up));
         // update in the slot
         PS_TRY(hipStreamWaitEvent(comp, loaded[k], 0));
@@ -953,13 +973,20 @@ ps_status_t ps_step_update_offloaded(const ps_spec_t *spec, const ps_adamw_t *hp
         PS_TRY(hipEventRecord(computed[k], comp));
         // download
         PS_TRY(hipStreamWaitEvent(down, computed[k], 0));
-        PS_TRY(hipMemcpyAsync(plan->host_master + lo, d_master, cnt * 4, hipMemcpyDeviceToHost, down));
-        PS_TRY(hipMemcpyAsync(plan->host_m + lo, d_m, cnt * 4, hipMemcpyDeviceToHost, down));
-        PS_TRY(hipMemcpyAsync(plan->host_v + lo, d_v, cnt * 4, hipMemcpyDeviceToHost, down));
-        PS_TRY(hipMemcpyAsync(reinterpret_cast<uint16_t *>(plan->host_param_out) + lo, d_out, cnt * 2,
-                              hipMemcpyDeviceToHost, down));
+        if (one_copy) {
+            PS_TRY(hipMemcpyAsync(h_pack, slot, 14 * B, hipMemcpyDeviceToHost, down));
+        } else {
+            PS_TRY(hipMemcpyAsync(h_master, d_master, cnt * 4, hipMemcpyDeviceToHost, down));
+            PS_TRY(hipMemcpyAsync(h_m, d_m, cnt * 4, hipMemcpyDeviceToHost, down));
+            PS_TRY(hipMemcpyAsync(h_v, d_v, cnt * 4, hipMemcpyDeviceToHost, down));
+            PS_TRY(hipMemcpyAsync(h_out, d_out, cnt * 2, hipMemcpyDeviceToHost, down));
+        }
         PS_TRY(hipEventRecord(drained[k], down));
     }
+    // The next call on these streams uploads into the same slots and reads the same host
+    // ranges: its first upload must not start before this call's last downloads are done.
+    for (uint32_t k = 0; k < S && k < n_buckets; ++k)
+        PS_TRY(hipStreamWaitEvent(up, drained[k], 0));
 #undef PS_TRY
     for (uint32_t k = 0; k < S; ++k) {
         if (loaded[k])

@@ -228,3 +228,16 @@ def test_corollary1_on_the_library():
         assert 2 * total(z2) == total(z1)
         assert total(z3) - total(z2) == 2 * (N - 1) * 2 * P
         assert z3.peak_total * N == 16 * P and z2.peak_total * N == 2 * P * N + 14 * P
+
+
+def test_a_library_built_from_other_sources_counts_as_stale(tmp_path, monkeypatch):
+    """The binding rebuilds (or refuses to load) a library whose recorded source hash differs
+    from the sources on disk, whatever the time stamps say."""
+    from paper_2601_02311_amd import build
+    assert not build.stale()                              # the library in the tree matches its sources
+    monkeypatch.setattr(build, "BUILD_ID", str(tmp_path / "id"))
+    assert build.stale()                                  # no record of what it was built from
+    (tmp_path / "id").write_text("0" * 64 + "\n")
+    assert build.stale()                                  # built from something else
+    (tmp_path / "id").write_text(build.source_id() + "\n")
+    assert not build.stale()

@@ -776,37 +776,110 @@ def test_gradient_accumulation_then_update(dtype, N):
 
 # ---- offloaded optimizer state (ZeRO-Offload row) ----
 
-@pytest.mark.parametrize("n_slots,dtype,N", [(3, "bf16", 4), (2, "bf16", 4), (3, "f32", 6)])
-def test_offloaded_state_streams_through_the_device(n_slots, dtype, N):
+def _pack_host(state, bucket):
+    """Host image in the packed layout: per bucket master | m | v | parameters, each array's
+    piece bucket elements long (the last bucket only partly meaningful, the rest canaries)."""
+    n = state[0].shape[0]
+    n_b = -(-n // bucket)
+    buf = np.full(n_b * 14 * bucket, 0xEE, np.uint8)
+    for b in range(n_b):
+        lo, hi = b * bucket, min((b + 1) * bucket, n)
+        base = b * 14 * bucket
+        for j, off in enumerate((0, 4 * bucket, 8 * bucket)):
+            buf[base + off:base + off + 4 * (hi - lo)] = state[j][lo:hi].view(np.uint8)
+        buf[base + 12 * bucket:base + 12 * bucket + 2 * (hi - lo)] = state[3][lo:hi].view(np.uint8)
+    return buf
+
+
+def _unpack_host(buf, n, bucket):
+    out = [np.empty(n, np.float32) for _ in range(3)] + [np.empty(n, np.uint16)]
+    for b in range(-(-n // bucket)):
+        lo, hi = b * bucket, min((b + 1) * bucket, n)
+        base = b * 14 * bucket
+        for j, off in enumerate((0, 4 * bucket, 8 * bucket)):
+            out[j][lo:hi] = buf[base + off:base + off + 4 * (hi - lo)].view(np.float32)
+        out[3][lo:hi] = buf[base + 12 * bucket:base + 12 * bucket + 2 * (hi - lo)].view(np.uint16)
+    return out
+
+
+@pytest.mark.parametrize("n_slots,dtype,N,packed", [(3, "bf16", 4, False), (2, "bf16", 4, False),
+                                                    (3, "f32", 6, False), (3, "bf16", 4, True),
+                                                    (2, "f32", 6, True)])
+def test_offloaded_state_streams_through_the_device(n_slots, dtype, N, packed):
     n = 5 * TILE + 100
     valid = n - 3
     bucket = TILE + 8
-    _say("offload n=%d bucket=%d slots=%d N=%d %s" % (n, bucket, n_slots, N, dtype))
+    _say("offload n=%d bucket=%d slots=%d N=%d %s packed=%s" % (n, bucket, n_slots, N, dtype, packed))
     spec = ps.ps_spec_preset("zero_offload", N, 2, n * N)
     grads = [gen.gradient(n, 111, 0, r, dtype) for r in range(N)]
     state = [gen.master(n, 111), *gen.moments(n, 111, True), np.full(n, 0x5555, np.uint16)]
     hpd, hp = hp_of(None, 12)
     want = [a.copy() for a in state]
     orc.step_f32(grads, orc.derive_scalars(t=12, n_devices=N, **hpd), *want, lo=0, hi=valid)
-    pinned = [torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).pin_memory()
-              for a in state]
     gd = [dev(g) for g in grads]
     slots = [torch.zeros(14 * bucket, dtype=torch.uint8, device="cuda") for _ in range(n_slots)]
     s1, s2, s3 = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     torch.cuda.synchronize()
     plan = ps.ps_offload_plan_t()
-    plan.host_master, plan.host_m, plan.host_v, plan.host_param_out = [t.data_ptr() for t in pinned]
+    if packed:
+        image = _pack_host(state, bucket)
+        pinned = torch.from_numpy(image.copy()).pin_memory()
+        plan.host_layout, plan.host_packed = ps.PS_HOST_PACKED, pinned.data_ptr()
+    else:
+        pinned = [torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).pin_memory()
+                  for a in state]
+        plan.host_master, plan.host_m, plan.host_v, plan.host_param_out = [t.data_ptr() for t in pinned]
     plan.len, plan.valid_len, plan.bucket_elems, plan.n_slots = n, valid, bucket, n_slots
     for k, t in enumerate(slots):
         plan.slot[k] = t.data_ptr()
     plan.h2d_stream, plan.compute_stream, plan.d2h_stream = s1.cuda_stream, s2.cuda_stream, s3.cuda_stream
     ps.ps_step_update_offloaded(spec, hp, plan, grads_of(gd, dtype))
     torch.cuda.synchronize()
-    got = [t.numpy().copy() for t in pinned]
-    got[3] = got[3].view(np.uint16)
+    if packed:
+        got = _unpack_host(pinned.numpy(), n, bucket)
+        # bytes of the image that belong to no element (the short last bucket's tail) keep their canary
+        unused = _pack_host([np.zeros(n, np.float32)] * 3 + [np.zeros(n, np.uint16)], bucket) == 0xEE
+        assert unused.any() and (pinned.numpy()[unused] == 0xEE).all()
+    else:
+        got = [t.numpy().copy() for t in pinned]
+        got[3] = got[3].view(np.uint16)
     assert assert_state_parity(got, want, "offload") == 0
     for g, a in zip(got, state):                                   # pad untouched on the host
         assert np.array_equal(g[valid:].view(np.uint8), a[valid:].view(np.uint8))
+
+
+def test_offloaded_steps_back_to_back_with_one_final_sync():
+    """Three offloaded steps enqueued one after the other on the same streams and slots,
+    the host waiting only once at the end: every step's uploads must see the previous
+    step's downloads (state consistency across steps, Theorem 4)."""
+    n, N, bucket, n_slots = 9 * TILE + 44, 4, 2 * TILE, 2
+    _say("offload back to back: n=%d bucket=%d slots=%d, 3 steps, one sync" % (n, bucket, n_slots))
+    spec = ps.ps_spec_preset("zero_offload", N, 0, n * N)
+    state = [gen.master(n, 113), *gen.moments(n, 113, True), np.zeros(n, np.uint16)]
+    want = [a.copy() for a in state]
+    pinned = [torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a.copy()).pin_memory()
+              for a in state]
+    slots = [torch.zeros(14 * bucket, dtype=torch.uint8, device="cuda") for _ in range(n_slots)]
+    s1, s2, s3 = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    plan = ps.ps_offload_plan_t()
+    plan.host_master, plan.host_m, plan.host_v, plan.host_param_out = [t.data_ptr() for t in pinned]
+    plan.len, plan.valid_len, plan.bucket_elems, plan.n_slots = n, n, bucket, n_slots
+    for k, t in enumerate(slots):
+        plan.slot[k] = t.data_ptr()
+    plan.h2d_stream, plan.compute_stream, plan.d2h_stream = s1.cuda_stream, s2.cuda_stream, s3.cuda_stream
+    all_g = [[gen.gradient(n, 113, t, r, "bf16") for r in range(N)] for t in (1, 2, 3)]
+    all_gd = [[dev(g) for g in gs] for gs in all_g]
+    torch.cuda.synchronize()
+    for t, gd in zip((1, 2, 3), all_gd):
+        _, hp = hp_of(None, t)
+        ps.ps_step_update_offloaded(spec, hp, plan, grads_of(gd, "bf16"))      # no wait in between
+    torch.cuda.synchronize()
+    for t, gs in zip((1, 2, 3), all_g):
+        hpd, _ = hp_of(None, t)
+        orc.step_f32(gs, orc.derive_scalars(t=t, n_devices=N, **hpd), *want)
+    got = [t.numpy().copy() for t in pinned]
+    got[3] = got[3].view(np.uint16)
+    assert assert_state_parity(got, want, "offload x3") == 0
 
 
 # ---- verification protocol kernels ----
