@@ -51,7 +51,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="70b_zero3",
                     choices=["tiny", "gpt2s", "7b_zero2", "70b_zero3", "13b_clip", "7b_zero1",
-                             "7b_accum4", "7b_verify", "7b_offload", "7b_zero2_f16"])
+                             "7b_accum4", "7b_verify", "7b_offload", "7b_zero2_f16", "placement_map"])
     ap.add_argument("--pool-elems", type=int, default=0,
                     help="elements per contribution of the resident bucket source; 0 (default): the "
                          "whole shard length, every bucket distinct; shorter: a pool that repeats")
@@ -62,6 +62,8 @@ def main():
                     help="bucketed workload with the whole source resident: arena = flat buffers whose "
                          "physical memory is created bucket by bucket (ps_arena_create), so that a "
                          "bucket's streams lie close together; plain = one allocation per buffer")
+    ap.add_argument("--arena-chunk-elems", type=int, default=0,
+                    help="elements per physical chunk of the arena (0 = the bucket size)")
     ap.add_argument("--waves-per-cu", type=int, default=0,
                     help="override the update kernel's residency cap (measurement aid; 0 = library's choice)")
     ap.add_argument("--schedule", choices=["auto", "overlap", "alternate"], default="auto")
@@ -93,6 +95,8 @@ def main():
     from synth import WORKLOADS
     from synth import device as dgen
 
+    if args.workload == "placement_map":
+        return placement_map(args)
     if args.workload == "7b_verify":
         return verify_bench(args)
     if args.workload == "7b_offload":
@@ -122,7 +126,8 @@ def main():
             and out_len == n):
         # contributions 0..N-1, master, m, v, parameters: flat, physically interleaved by bucket
         try:
-            arena = ps.ps_arena_create(n, args.bucket_elems or w.bucket_elems, [esz] * N + [4, 4, 4, 2])
+            arena = ps.ps_arena_create(n, args.arena_chunk_elems or args.bucket_elems or w.bucket_elems,
+                                       [esz] * N + [4, 4, 4, 2])
         except ps.PsError as err:
             log("arena not created (%s): plain allocations instead" % err.detail)
     if arena is not None:
@@ -373,6 +378,65 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, bpe, args.cpu_baseline_seconds)
     print(json.dumps(result), flush=True)
+
+
+def placement_map(args):
+    """Measurement aid behind ps_arena_create: the update kernel on one 2^28-element bucket
+    of the 70B workload whose eight contributions (a cluster of 4 GiB) and whose state and
+    parameters (a cluster of 3.5 GiB) are placed at chosen offsets of ONE 248 GiB allocation.
+    Prints the time per launch for every pair of offsets on a 16 GiB grid: which parts of the
+    address space go together, and what it costs when they do not."""
+    import torch
+
+    import paper_2601_02311_amd as ps
+    from synth import WORKLOADS
+
+    w = WORKLOADS["70b_zero3"]
+    torch.cuda.set_device(0)
+    info = ps.ps_device_info()
+    GiB, B, N = 1 << 30, w.bucket_elems, w.n_devices
+    total = 248 * GiB
+    big = torch.zeros(total, dtype=torch.uint8, device="cuda")
+    base = big.data_ptr()
+    spec = ps.ps_spec_preset(w.strategy, N, 0, B * N)          # one bucket stands for the shard
+    hp = ps.ps_adamw_t(w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, w.first_step, 0.0, 0.0)
+    st = torch.cuda.current_stream().cuda_stream
+    xs = list(range(0, 248 - 3, 16))
+    ys = list(range(4, 248 - 3, 16))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    rows = []
+    for x in xs:
+        row = []
+        for y in ys:
+            g = ps.make_grads([base + x * GiB + r * (GiB // 2) for r in range(N)], ps.PS_BF16)
+            sh = ps.ps_shard_t(base + y * GiB, base + (y + 1) * GiB, base + (y + 2) * GiB,
+                               base + (y + 3) * GiB, B, B, ps.PS_BF16, 0)
+            ps.ps_step_update(spec, hp, sh, g, 0, B, st)
+            e0.record()
+            for _ in range(args.steps):
+                ps.ps_step_update(spec, hp, sh, g, 0, B, st)
+            e1.record()
+            torch.cuda.synchronize()
+            row.append(e0.elapsed_time(e1) / args.steps)
+        rows.append(row)
+        log("contributions at %3d GiB: " % x + " ".join("%.3f" % t for t in row))
+    flat = sorted(t for r in rows for t in r)
+    fast = [t for t in flat if t < (flat[0] + flat[-1]) / 2]
+    slow = [t for t in flat if t >= (flat[0] + flat[-1]) / 2]
+    print(json.dumps({
+        "metric": "update kernel, ms per 2^28-element bucket, by placement of its operands",
+        "value": sum(fast) / len(fast), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": 1,
+        "ms_per_step": sum(flat) / len(flat), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "placement_map", "device": info.name.decode(),
+                   "allocation_GiB": 248, "contribution_offsets_GiB": xs, "state_offsets_GiB": ys,
+                   "ms": rows, "fast_pairs": len(fast), "fast_ms_avg": sum(fast) / len(fast),
+                   "slow_pairs": len(slow), "slow_ms_avg": sum(slow) / max(1, len(slow))},
+        "roofline": {"bound": "hbm", "achieved": 42 * B / (sum(fast) / len(fast)) / 1e6,
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": 42 * B / (sum(fast) / len(fast)) / 1e6 / PEAK_HBM_GBS, "traffic": None,
+                     "kernel": "update_tiles, operands in parts of the address space that go together"}}),
+          flush=True)
 
 
 def offload_bench(args):
