@@ -317,106 +317,110 @@ def test_13b_clip_ragged_full_shard_every_element(capsys):
     torch.cuda.empty_cache()
 
 
-def test_single_launch_beyond_2_32_elements():
+def test_single_launch_beyond_2_32_elements(capsys):
     """Maximum size in one launch: the whole 70B shard (8.75e9 elements, 34 million
     workgroups) updated from one pre-reduced fp32 gradient; element indices pass 2^32
-    and byte offsets pass 2^35.  Sampled slices straddle 2^31, 2^32 and 2^33."""
+    and byte offsets pass 2^35.  Every element is compared with the oracle."""
     w = WORKLOADS["70b_zero3"]
     _need(165)
     n, N, t = w.shard_len, w.n_devices, w.first_step
-    _say("single launch over n=%d elements (fp32 pre-reduced gradient)" % n)
+    _say("single launch over n=%d elements (fp32 pre-reduced gradient), every element" % n)
     spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi)
     master, m, v = dgen.workload_state(w)
+    head = [_take(x, 0, 4096) for x in (master, m, v)]
     g = dgen.fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), 1e-4, w.seed, 9)
     out = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
-    sl = _slices(n, extra=[((1 << 31) - 4096, (1 << 31) + 4096), ((1 << 32) - 4096, (1 << 32) + 4096),
-                           ((1 << 33) - 4096, (1 << 33) + 4096)])
-    before = [([_take(x, lo, hi) for x in (master, m, v)], [_take(g, lo, hi)]) for lo, hi in sl]
     hpd, hp = _hp(w, t, grad_scale=1.0)
     ps.ps_step_update(spec, hp, shard_of(master, m, v, out, n),
                       ps.make_grads([g.data_ptr()], ps.PS_F32), 0, n, stream_handle())
     torch.cuda.synchronize()
     s = orc.derive_scalars(t=t, n_devices=N, grad_scale=1.0, **hpd)
-    for (lo, hi), (st, gr) in zip(sl, before):
-        want = [a.copy() for a in st] + [np.zeros(hi - lo, np.uint16)]
-        orc.step_f32(gr, s, *want)
-        got = [_take(x, lo, hi) for x in (master, m, v, out)]
-        assert assert_state_parity(got, want, "big [%d,%d)" % (lo, hi)) == 0
-    _whole_shard_properties(master, m, v, out, n)
-    del master, m, v, g, out
+    pin = _pinned(1, torch.float32, torch.bfloat16)
+    _check_every_element(capsys, "one launch, 8.75e9 elements", w, s, pin,
+                         lambda lo, hi: [pin.fetch("g0", g[lo:hi])], master, m, v, out, n, saved_head=head)
+    del master, m, v, g, out, pin
     torch.cuda.empty_cache()
 
 
 # ---- rows beyond the base path, at the sizes bench.py times them ----
 
-def test_7b_zero1_full_shard_sampled():
+def test_7b_zero1_full_shard_every_element(capsys):
     """ZeRO-1 row: one all-reduced, replicated bf16 gradient of psi elements; the library
     reads and writes slice i.  Run for the shard bench.py uses and for one with a large
-    offset, on the same buffers."""
+    offset; every element of each is compared with the oracle."""
     w = WORKLOADS["7b_zero1"]
     _need(45)
     N, t = w.n_devices, w.first_step
-    master, m, v = dgen.workload_state(w)
     n = w.shard_len
     grad = dgen.fill_gradient_(torch.empty(w.psi, dtype=torch.bfloat16, device="cuda"),
                                w.seed, t, 0, w.grad_std)
     out = torch.zeros(w.psi, dtype=torch.bfloat16, device="cuda")
+    pin = _pinned(1, torch.bfloat16, torch.bfloat16)
     for i in (w.shard_index, 5):
+        master, m, v = dgen.workload_state(w)                     # the same state for either shard index
+        head = [_take(x, 0, 4096) for x in (master, m, v)]
         spec = ps.ps_spec_preset(w.strategy, N, i, w.psi)
         cost = ps.ps_cost_eval(spec)
         assert cost.shard_len == n and cost.psi_padded == w.psi
         off = cost.shard_offset
-        _say("7b_zero1 shard %d: n=%d at offset %d of the replicated gradient" % (i, n, off))
-        sl = _slices(n)
-        before = [([_take(x, lo, hi) for x in (master, m, v)], [_take(grad, off + lo, off + hi)])
-                  for lo, hi in sl]
+        _say("7b_zero1 shard %d: n=%d at offset %d of the replicated gradient, every element" % (i, n, off))
         out.zero_()
         hpd, hp = _hp(w, t)
         ps.ps_step_update(spec, hp, shard_of(master, m, v, out, n),
                           ps.make_grads([grad.data_ptr()], ps.PS_BF16), 0, n, stream_handle())
         torch.cuda.synchronize()
         s = orc.derive_scalars(t=t, n_devices=N, **hpd)          # grad_scale 0: 1/N, the all-reduce sums
-        for (lo, hi), (st, gr) in zip(sl, before):
-            want = [a.copy() for a in st] + [np.zeros(hi - lo, np.uint16)]
-            orc.step_f32(gr, s, *want)
-            got = [_take(x, lo, hi) for x in (master, m, v)] + [_take(out, off + lo, off + hi)]
-            assert assert_state_parity(got, want, "zero1 shard %d [%d,%d)" % (i, lo, hi)) == 0
-        _whole_shard_properties(master, m, v, out[off:off + n], n)
-        if off:                                                    # neighbours' slices untouched
-            assert not bool(out[off - SLICE:off].view(torch.int16).any())
-        if off + n < w.psi:
-            assert not bool(out[off + n:off + n + SLICE].view(torch.int16).any())
-    del master, m, v, grad, out
+        _check_every_element(capsys, "zero1 shard %d" % i, w, s, pin,
+                             lambda lo, hi: [pin.fetch("g0", grad[off + lo:off + hi])],
+                             master, m, v, out[off:off + n], n, saved_head=head)
+        assert not bool(out[:off].view(torch.int16).any())        # the other shards' slices untouched
+        assert not bool(out[off + n:].view(torch.int16).any())
+        del master, m, v
+    del grad, out, pin
     torch.cuda.empty_cache()
 
 
-def test_7b_accum4_full_shard_sampled():
+def test_7b_accum4_full_shard_every_element(capsys):
     """Gradient accumulation row: four micro-batches (fresh contributions each) into the
-    FP32 accumulator, then one update with grad_scale = 1/(N k)."""
+    FP32 accumulator, then one update with grad_scale = 1/(N k).  The accumulator (oracle:
+    accumulate over the whole shard, on all host threads) and the updated state are compared
+    on every element."""
+    import threading
     w = WORKLOADS["7b_accum4"]
     _need(45)
     n, N, t, k = w.shard_len, w.n_devices, w.first_step, w.micro_batches
-    _say("7b_accum4 full shard n=%d, %d micro-batches, sampled slices" % (n, k))
+    _say("7b_accum4 full shard n=%d, %d micro-batches, every element" % (n, k))
     spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi)
     cost = ps.ps_cost_eval(spec)
     master, m, v = dgen.workload_state(w)
+    head = [_take(x, 0, 4096) for x in (master, m, v)]
     out = torch.zeros(n, dtype=torch.bfloat16, device="cuda")      # this shard's slice only
     accum = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
-    sl = _slices(n)
-    acc_want = [np.full(hi - lo, np.float32(np.nan)) for lo, hi in sl]
+    acc_want = np.full(n, np.float32(np.nan))                       # the oracle's accumulator, whole shard
+    pin = _pinned(N, torch.bfloat16, torch.bfloat16, extra=[("acc", torch.float32)])
+    threads = 16
     grads = None
     for j in range(k):
         del grads
         grads = dgen.workload_gradients(w, t * 16 + j)             # a different stream per micro-batch
-        for (lo, hi), a in zip(sl, acc_want):
-            orc.accumulate([_take(g, lo, hi) for g in grads], a, overwrite=(j == 0))
         ps.ps_step_accumulate(spec, ps.make_grads([g.data_ptr() for g in grads], ps.PS_BF16),
                               accum.data_ptr(), j == 0, 0, n, n, stream_handle())
+        for lo in range(0, n, CHUNK):
+            hi = min(lo + CHUNK, n)
+            gr = [pin.fetch("g%d" % r, grads[r][lo:hi]) for r in range(N)]
+            part = acc_want[lo:hi]
+            bounds = [(hi - lo) * q // threads for q in range(threads + 1)]
+            ts = [threading.Thread(target=orc.accumulate, args=(gr, part, j == 0, bounds[q], bounds[q + 1]))
+                  for q in range(threads)]
+            for x in ts:
+                x.start()
+            for x in ts:
+                x.join()
         torch.cuda.synchronize()
-    for (lo, hi), a in zip(sl, acc_want):
-        assert np.array_equal(_take(accum, lo, hi).view(np.uint32), a.view(np.uint32))
-    assert bool(torch.isfinite(accum).all())                       # every element was overwritten first
-    before = [[_take(x, lo, hi) for x in (master, m, v)] for lo, hi in sl]
+        _progress(capsys, "accumulation: micro-batch %d of %d added on both sides" % (j + 1, k))
+    for lo in range(0, n, CHUNK):
+        hi = min(lo + CHUNK, n)
+        assert np.array_equal(pin.fetch("acc", accum[lo:hi]).view(np.uint32), acc_want[lo:hi].view(np.uint32))
     scale = 1.0 / (N * k)
     hpd, hp = _hp(w, t, grad_scale=scale)
     assert cost.shard_offset == 0          # shard 0: its slice of the replicated parameters starts the buffer
@@ -424,13 +428,10 @@ def test_7b_accum4_full_shard_sampled():
                       ps.make_grads([accum.data_ptr()], ps.PS_F32), 0, n, stream_handle())
     torch.cuda.synchronize()
     s = orc.derive_scalars(t=t, n_devices=N, grad_scale=scale, **hpd)
-    for (lo, hi), st, a in zip(sl, before, acc_want):
-        want = [x.copy() for x in st] + [np.zeros(hi - lo, np.uint16)]
-        orc.step_f32([a], s, *want)
-        got = [_take(x, lo, hi) for x in (master, m, v, out)]
-        assert assert_state_parity(got, want, "accum [%d,%d)" % (lo, hi)) == 0
-    _whole_shard_properties(master, m, v, out, n)
-    del master, m, v, out, accum, grads
+    _check_every_element(capsys, "update from the accumulator", w, s, pin,
+                         lambda lo, hi: [np.ascontiguousarray(acc_want[lo:hi])],
+                         master, m, v, out, n, saved_head=head)
+    del master, m, v, out, accum, grads, pin
     torch.cuda.empty_cache()
 
 
@@ -487,27 +488,36 @@ def test_7b_verify_scans_whole_buffers_against_the_oracle():
     torch.cuda.empty_cache()
 
 
-def test_7b_offload_full_shard_sampled():
+@pytest.mark.parametrize("packed", [True, False])
+def test_7b_offload_full_shard_every_element(packed, capsys):
     """ZeRO-Offload row at bench.py's shape: master/m/v and the bf16 parameters of the 7B
-    shard in pinned host memory, streamed through three device slots of 2^24 elements."""
+    shard in pinned host memory (one image packed bucket by bucket, or four flat arrays),
+    streamed through three device slots of 2^24 elements; every element compared."""
     w = WORKLOADS["7b_offload"]
     _need(20)
     n, N, t, B = w.shard_len, w.n_devices, w.first_step, w.bucket_elems
-    _say("7b_offload full shard n=%d, buckets of %d through 3 slots, sampled slices" % (n, B))
-    spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi)
-    pinned = [x.cpu().pin_memory() for x in dgen.workload_state(w)]
-    pinned.append(torch.zeros(n, dtype=torch.bfloat16).pin_memory())
-    torch.cuda.empty_cache()
-    grads = dgen.workload_gradients(w, t)
     n_b = -(-n // B)
-    sl = _slices(n, extra=[(B - 4096, B + 4096), ((n_b - 1) * B - 4096, (n_b - 1) * B + 4096)])
-    before = [([host(x[lo:hi].clone()) for x in pinned[:3]], [_take(g, lo, hi) for g in grads])
-              for lo, hi in sl]
+    _say("7b_offload full shard n=%d, buckets of %d through 3 slots, packed=%s, every element" % (n, B, packed))
+    spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi)
+    state = [x.cpu().numpy() for x in dgen.workload_state(w)]        # the state before the step, on the host
+    torch.cuda.empty_cache()
+    plan = ps.ps_offload_plan_t()
+    if packed:
+        image = torch.full((n_b * 14 * B,), 0xEE, dtype=torch.uint8).pin_memory()
+        img = image.numpy()
+        for b in range(n_b):
+            lo, hi = b * B, min((b + 1) * B, n)
+            for j in range(3):
+                img[b * 14 * B + 4 * B * j:b * 14 * B + 4 * B * j + 4 * (hi - lo)] = state[j][lo:hi].view(np.uint8)
+        plan.host_layout, plan.host_packed = ps.PS_HOST_PACKED, image.data_ptr()
+    else:
+        pinned = [torch.from_numpy(a.copy()).pin_memory() for a in state]
+        pinned.append(torch.zeros(n, dtype=torch.bfloat16).pin_memory())
+        plan.host_master, plan.host_m, plan.host_v, plan.host_param_out = [x.data_ptr() for x in pinned]
+    grads = dgen.workload_gradients(w, t)
     slots = [torch.empty(14 * B, dtype=torch.uint8, device="cuda") for _ in range(3)]
     s1, s2, s3 = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     torch.cuda.synchronize()
-    plan = ps.ps_offload_plan_t()
-    plan.host_master, plan.host_m, plan.host_v, plan.host_param_out = [x.data_ptr() for x in pinned]
     plan.len, plan.valid_len, plan.bucket_elems, plan.n_slots = n, n, B, 3
     for j, x in enumerate(slots):
         plan.slot[j] = x.data_ptr()
@@ -516,16 +526,28 @@ def test_7b_offload_full_shard_sampled():
     ps.ps_step_update_offloaded(spec, hp, plan, ps.make_grads([g.data_ptr() for g in grads], ps.PS_BF16))
     torch.cuda.synchronize()
     s = orc.derive_scalars(t=t, n_devices=N, **hpd)
-    for (lo, hi), (st, gr) in zip(sl, before):
-        want = [x.copy() for x in st] + [np.zeros(hi - lo, np.uint16)]
-        orc.step_f32(gr, s, *want)
-        got = [host(x[lo:hi].clone()) for x in pinned]
-        assert assert_state_parity(got, want, "offload [%d,%d)" % (lo, hi)) == 0
-    # whole shard, on the host: the bf16 image is the cast of the new master weight
-    step = 1 << 26
-    for lo in range(0, n, step):
-        hi = min(lo + step, n)
-        assert torch.equal(pinned[0][lo:hi].to(torch.bfloat16).view(torch.int16),
-                           pinned[3][lo:hi].view(torch.int16))
-    del pinned, grads, slots
+    pin = _pinned(N, torch.bfloat16, torch.bfloat16)
+    bad, t0 = [0, 0, 0, 0], time.time()
+    for b in range(n_b):                                             # one bucket at a time
+        lo, hi = b * B, min((b + 1) * B, n)
+        gr = [pin.fetch("g%d" % r, grads[r][lo:hi]) for r in range(N)]
+        pre = [np.ascontiguousarray(a[lo:hi]) for a in state]
+        if packed:
+            base = b * 14 * B
+            post = [img[base + 4 * B * j:base + 4 * B * j + 4 * (hi - lo)].view(np.float32) for j in range(3)]
+            post.append(img[base + 12 * B:base + 12 * B + 2 * (hi - lo)].view(np.uint16))
+        else:
+            post = [x[lo:hi].numpy() for x in pinned[:3]] + [pinned[3][lo:hi].view(torch.int16).numpy().view(np.uint16)]
+        for j, x in enumerate(oracle_mismatches(orc.step_f32, s, gr, pre, post, hi - lo)):
+            bad[j] += x
+        assert bad == [0, 0, 0, 0], "offload bucket %d: %s" % (b, bad)
+    _progress(capsys, "offload packed=%s: %d elements checked against the oracle, %.0f s, mismatches %s"
+              % (packed, n, time.time() - t0, bad))
+    if packed:                                                       # bytes that belong to no element keep their canary
+        tail = n - (n_b - 1) * B
+        base = (n_b - 1) * 14 * B
+        for j in range(3):
+            assert (img[base + 4 * B * j + 4 * tail:base + 4 * B * (j + 1)] == 0xEE).all()
+        assert (img[base + 12 * B + 2 * tail:base + 14 * B] == 0xEE).all()
+    del grads, slots, pin
     torch.cuda.empty_cache()
