@@ -340,6 +340,209 @@ ps_status_t reduce_sumsq_checked(const ps_spec_t *spec, const ps_grads_t *grads,
     return PS_OK;
 }
 
+// The bucket loop of ps_step_update_bucketed after validation.  Every HIP call goes
+// through PS_ATTEMPT: after the first failure nothing more is enqueued, and finish()
+// reports that failure once the events have been released.
+#define PS_ATTEMPT(call)                                                                          \
+    do {                                                                                          \
+        if (ok())                                                                                 \
+            note((call), #call);                                                                  \
+    } while (0)
+
+class BucketRun {
+  public:
+    BucketRun(const ps_shard_t *shard, const ps_bucket_plan_t *plan, const StepScalars &s,
+              uint64_t out_off, uint64_t n_buckets)
+        : shard_(shard), plan_(plan), s_(s), out_off_(out_off), n_buckets_(n_buckets),
+          eb_(elem_bytes(plan->dtype)), slot_stride_(plan->bucket_elems * elem_bytes(plan->dtype)),
+          copy_(reinterpret_cast<hipStream_t>(plan->copy_stream)),
+          comp_(reinterpret_cast<hipStream_t>(plan->compute_stream)),
+          timed_(plan->kernel_ms != nullptr),
+          // A copy kernel and the update kernel both live on HBM bandwidth: run side by
+          // side they only widen each other's request windows, so they take turns.  A
+          // DMA copy (host or peer source) is bound by its link and overlaps.
+          alternate_(plan->schedule == PS_SCHED_ALTERNATE ||
+                     (plan->schedule == PS_SCHED_AUTO && plan->copy_engine == PS_COPY_KERNEL))
+    {
+    }
+
+    void create_events(bool in_place)
+    {
+        for (int k = 0; k < 2 && !in_place; ++k) {
+            PS_ATTEMPT(hipEventCreateWithFlags(&staged_[k], hipEventDisableTiming));
+            PS_ATTEMPT(hipEventCreateWithFlags(&freed_[k], hipEventDisableTiming));
+        }
+        if (timed_) {
+            t0_.assign(n_buckets_, nullptr);
+            t1_.assign(n_buckets_, nullptr);
+            for (uint64_t b = 0; b < n_buckets_; ++b) {
+                PS_ATTEMPT(hipEventCreate(&t0_[b]));
+                PS_ATTEMPT(hipEventCreate(&t1_[b]));
+            }
+        }
+    }
+
+    // A source in this device's memory is read where it lies: one kernel per bucket on the
+    // compute stream (one per contiguous piece where a repeating source wraps inside a
+    // bucket), no staging slot, no second stream, no events unless timings are asked for.
+    void in_place()
+    {
+        for (uint64_t b = 0; b < n_buckets_ && ok(); ++b) {
+            const uint64_t lo = b * plan_->bucket_elems;
+            const uint64_t cnt = clamp_count(lo, plan_->bucket_elems, shard_->valid_len);
+            mark(t0_, b);
+            for (uint64_t cur = lo; cur < lo + cnt && ok();) {
+                const uint64_t pos = cur % plan_->source_elems;
+                const uint64_t room = plan_->source_elems - pos;
+                const uint64_t take = lo + cnt - cur < room ? lo + cnt - cur : room;
+                ContribPtrs g;
+                std::memset(&g, 0, sizeof g);
+                for (uint32_t r = 0; r < plan_->n_contrib; ++r)
+                    g.p[r] = reinterpret_cast<const char *>(plan_->source[r]) + pos * eb_;
+                update(g, cur, take);
+                cur += take;
+            }
+            mark(t1_, b);
+        }
+    }
+
+    // A source that has to be moved first: bucket b+1 is staged on the copy stream into the
+    // slot the update of bucket b-1 has released, while (or, taking turns, after) bucket b is
+    // updated on the compute stream.  staged_[k]: slot k holds a complete bucket; freed_[k]:
+    // the kernel reading slot k is done.
+    void staged()
+    {
+        stage(0);
+        for (uint64_t b = 0; b < n_buckets_ && ok(); ++b) {
+            const int k = (int)(b & 1);
+            if (b + 1 < n_buckets_ && !alternate_)
+                stage(b + 1);
+            const uint64_t lo = b * plan_->bucket_elems;
+            const uint64_t cnt = clamp_count(lo, plan_->bucket_elems, shard_->valid_len);
+            PS_ATTEMPT(hipStreamWaitEvent(comp_, staged_[k], 0));
+            mark(t0_, b);
+            if (cnt && ok()) {
+                ContribPtrs g;
+                std::memset(&g, 0, sizeof g);
+                for (uint32_t r = 0; r < plan_->n_contrib; ++r)
+                    g.p[r] = reinterpret_cast<const char *>(plan_->staging[k]) + r * slot_stride_;
+                update(g, lo, cnt);
+            }
+            mark(t1_, b);
+            PS_ATTEMPT(hipEventRecord(freed_[k], comp_));
+            if (b + 1 < n_buckets_ && alternate_)
+                stage(b + 1);
+        }
+        // Later work on the copy stream must not overtake the last kernels.
+        if (ok())
+            PS_ATTEMPT(hipStreamWaitEvent(copy_, freed_[(n_buckets_ - 1) & 1], 0));
+    }
+
+    // Timings asked for: wait for the streams and read the per-bucket durations.
+    void collect_timings(bool in_place)
+    {
+        if (!timed_)
+            return;
+        PS_ATTEMPT(hipStreamSynchronize(comp_));
+        if (!in_place)
+            PS_ATTEMPT(hipStreamSynchronize(copy_));
+        for (uint64_t b = 0; b < n_buckets_ && ok(); ++b)
+            PS_ATTEMPT(hipEventElapsedTime(&plan_->kernel_ms[b], t0_[b], t1_[b]));
+    }
+
+    // Destroying an event that is still pending is allowed: its resources are released
+    // once the recorded work has completed.
+    ps_status_t finish()
+    {
+        for (int k = 0; k < 2; ++k) {
+            if (staged_[k])
+                (void)hipEventDestroy(staged_[k]);
+            if (freed_[k])
+                (void)hipEventDestroy(freed_[k]);
+        }
+        for (hipEvent_t ev : t0_)
+            if (ev)
+                (void)hipEventDestroy(ev);
+        for (hipEvent_t ev : t1_)
+            if (ev)
+                (void)hipEventDestroy(ev);
+        return e_ == hipSuccess ? PS_OK : hip_fail(e_, what_);
+    }
+
+  private:
+    bool ok() const { return e_ == hipSuccess; }
+
+    // Records the first failure; PS_ATTEMPT makes no further HIP call after one.
+    void note(hipError_t e, const char *what)
+    {
+        if (e_ == hipSuccess && e != hipSuccess) {
+            e_ = e;
+            what_ = what;
+        }
+    }
+
+    void mark(std::vector<hipEvent_t> &ev, uint64_t b)
+    {
+        if (timed_ && ok())
+            PS_ATTEMPT(hipEventRecord(ev[b], comp_));
+    }
+
+    // The update kernel over shard elements [lo, lo + count) from the contributions at g.
+    void update(const ContribPtrs &g, uint64_t lo, uint64_t count)
+    {
+        uint16_t *out = reinterpret_cast<uint16_t *>(shard_->gather_out) + out_off_ + lo;
+        int le = launch_update(plan_->dtype, plan_->n_contrib, g, shard_->master + lo, shard_->m + lo,
+                               shard_->v + lo, out, count, s_, comp_);
+        if (le != 0)
+            note((hipError_t)le, "update kernel launch");
+    }
+
+    void stage(uint64_t b)
+    {
+        if (!ok())
+            return;
+        const int k = (int)(b & 1);
+        const uint64_t lo = b * plan_->bucket_elems;
+        const uint64_t cnt = clamp_count(lo, plan_->bucket_elems, shard_->len);
+        if (b >= 2) // the slot is reused: wait for the kernel that read it
+            PS_ATTEMPT(hipStreamWaitEvent(copy_, freed_[k], 0));
+        if (alternate_ && b >= 1) // take turns: start after the update of bucket b-1 has finished
+            PS_ATTEMPT(hipStreamWaitEvent(copy_, freed_[k ^ 1], 0));
+        if (plan_->copy_engine == PS_COPY_MEMCPY) {
+            const uint64_t src_off = (lo % plan_->source_elems) * eb_;
+            for (uint32_t r = 0; r < plan_->n_contrib && ok(); ++r)
+                PS_ATTEMPT(hipMemcpyAsync(reinterpret_cast<char *>(plan_->staging[k]) + r * slot_stride_,
+                                       reinterpret_cast<const char *>(plan_->source[r]) + src_off,
+                                       cnt * eb_, hipMemcpyDefault, copy_));
+        } else if (ok()) {
+            ContribPtrs src;
+            std::memset(&src, 0, sizeof src);
+            for (uint32_t r = 0; r < plan_->n_contrib; ++r)
+                src.p[r] = plan_->source[r];
+            int le = launch_stage(plan_->n_contrib, src, plan_->staging[k], slot_stride_, lo * eb_ / 16,
+                                  plan_->source_elems * eb_ / 16, (cnt * eb_ + 15) / 16, alternate_,
+                                  copy_);
+            if (le != 0)
+                note((hipError_t)le, "staging kernel launch");
+        }
+        if (ok())
+            PS_ATTEMPT(hipEventRecord(staged_[k], copy_));
+    }
+
+    const ps_shard_t *shard_;
+    const ps_bucket_plan_t *plan_;
+    const StepScalars s_;
+    const uint64_t out_off_, n_buckets_, eb_, slot_stride_;
+    hipStream_t copy_, comp_;
+    const bool timed_, alternate_;
+    hipEvent_t staged_[2] = {nullptr, nullptr}, freed_[2] = {nullptr, nullptr};
+    std::vector<hipEvent_t> t0_, t1_;
+    hipError_t e_ = hipSuccess;
+    const char *what_ = "";
+};
+
+#undef PS_ATTEMPT
+
 } // namespace
 
 extern "C" {
@@ -605,162 +808,15 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
     if ((st = need_device()) != PS_OK)
         return st;
 
-    hipStream_t copy = reinterpret_cast<hipStream_t>(plan->copy_stream);
-    hipStream_t comp = reinterpret_cast<hipStream_t>(plan->compute_stream);
-    const StepScalars s = derive_scalars(*hp, spec->n_devices, shard->param_dtype);
-    const uint64_t eb = elem_bytes(plan->dtype);
-    const uint64_t slot_stride = plan->bucket_elems * eb; // bytes between contributions in a slot
-    const bool timed = plan->kernel_ms != nullptr;
-    // A copy kernel and the update kernel both live on HBM bandwidth: run side by
-    // side they only widen each other's request windows, so they take turns.  A
-    // DMA copy (host or peer source) is bound by its link and overlaps.
-    const bool alternate = plan->schedule == PS_SCHED_ALTERNATE ||
-                           (plan->schedule == PS_SCHED_AUTO && plan->copy_engine == PS_COPY_KERNEL);
-
-    // staged[k]: slot k holds a complete bucket; freed[k]: the kernel reading slot k is done.
-    hipEvent_t staged[2] = {nullptr, nullptr}, freed[2] = {nullptr, nullptr};
-    std::vector<hipEvent_t> t0, t1;
-    hipError_t e = hipSuccess;
-    const char *what = "";
-#define PS_TRY(call)                                                                              \
-    do {                                                                                          \
-        if (e == hipSuccess) {                                                                    \
-            e = (call);                                                                           \
-            what = #call;                                                                         \
-        }                                                                                         \
-    } while (0)
-    for (int k = 0; k < 2 && !in_place; ++k) {
-        PS_TRY(hipEventCreateWithFlags(&staged[k], hipEventDisableTiming));
-        PS_TRY(hipEventCreateWithFlags(&freed[k], hipEventDisableTiming));
-    }
-    if (timed) {
-        t0.assign(n_buckets, nullptr);
-        t1.assign(n_buckets, nullptr);
-        for (uint64_t b = 0; b < n_buckets; ++b) {
-            PS_TRY(hipEventCreate(&t0[b]));
-            PS_TRY(hipEventCreate(&t1[b]));
-        }
-    }
-
-    ContribPtrs src;
-    std::memset(&src, 0, sizeof src);
-    for (uint32_t r = 0; r < plan->n_contrib; ++r)
-        src.p[r] = plan->source[r];
-
-    auto stage = [&](uint64_t b) {
-        const int k = (int)(b & 1);
-        const uint64_t lo = b * plan->bucket_elems;
-        const uint64_t cnt = clamp_count(lo, plan->bucket_elems, shard->len);
-        if (b >= 2) // the slot is reused: wait for the kernel that read it
-            PS_TRY(hipStreamWaitEvent(copy, freed[k], 0));
-        if (alternate && b >= 1) // take turns: start after the update of bucket b-1 has finished
-            PS_TRY(hipStreamWaitEvent(copy, freed[k ^ 1], 0));
-        if (plan->copy_engine == PS_COPY_MEMCPY) {
-            const uint64_t src_off = (lo % plan->source_elems) * eb;
-            for (uint32_t r = 0; r < plan->n_contrib; ++r)
-                PS_TRY(hipMemcpyAsync(reinterpret_cast<char *>(plan->staging[k]) + r * slot_stride,
-                                      reinterpret_cast<const char *>(plan->source[r]) + src_off,
-                                      cnt * eb, hipMemcpyDefault, copy));
-        } else if (e == hipSuccess) {
-            int le = launch_stage(plan->n_contrib, src, plan->staging[k], slot_stride,
-                                  lo * eb / 16, plan->source_elems * eb / 16,
-                                  (cnt * eb + 15) / 16, alternate, copy);
-            if (le != 0) {
-                e = (hipError_t)le;
-                what = "staging kernel launch";
-            }
-        }
-        PS_TRY(hipEventRecord(staged[k], copy));
-    };
-
-    // A source in this device's memory is read where it lies: one kernel per bucket on the
-    // compute stream (one per contiguous piece where a repeating source wraps inside a
-    // bucket), no staging slot, no second stream, no events.
-    for (uint64_t b = 0; in_place && b < n_buckets && e == hipSuccess; ++b) {
-        const uint64_t lo = b * plan->bucket_elems;
-        const uint64_t cnt = clamp_count(lo, plan->bucket_elems, shard->valid_len);
-        if (timed)
-            PS_TRY(hipEventRecord(t0[b], comp));
-        for (uint64_t cur = lo; cur < lo + cnt && e == hipSuccess;) {
-            const uint64_t pos = cur % plan->source_elems;
-            const uint64_t room = plan->source_elems - pos;
-            const uint64_t take = lo + cnt - cur < room ? lo + cnt - cur : room;
-            ContribPtrs g;
-            std::memset(&g, 0, sizeof g);
-            for (uint32_t r = 0; r < plan->n_contrib; ++r)
-                g.p[r] = reinterpret_cast<const char *>(plan->source[r]) + pos * eb;
-            uint16_t *out = reinterpret_cast<uint16_t *>(shard->gather_out) + out_off + cur;
-            int le = launch_update(plan->dtype, plan->n_contrib, g, shard->master + cur,
-                                   shard->m + cur, shard->v + cur, out, take, s, comp);
-            if (le != 0) {
-                e = (hipError_t)le;
-                what = "update kernel launch";
-            }
-            cur += take;
-        }
-        if (timed)
-            PS_TRY(hipEventRecord(t1[b], comp));
-    }
-
-    if (!in_place)
-        stage(0);
-    for (uint64_t b = 0; !in_place && b < n_buckets && e == hipSuccess; ++b) {
-        const int k = (int)(b & 1);
-        if (b + 1 < n_buckets && !alternate)
-            stage(b + 1);
-        const uint64_t lo = b * plan->bucket_elems;
-        const uint64_t cnt = clamp_count(lo, plan->bucket_elems, shard->valid_len);
-        PS_TRY(hipStreamWaitEvent(comp, staged[k], 0));
-        if (timed)
-            PS_TRY(hipEventRecord(t0[b], comp));
-        if (cnt && e == hipSuccess) {
-            ContribPtrs g;
-            std::memset(&g, 0, sizeof g);
-            for (uint32_t r = 0; r < plan->n_contrib; ++r)
-                g.p[r] = reinterpret_cast<const char *>(plan->staging[k]) + r * slot_stride;
-            uint16_t *out = reinterpret_cast<uint16_t *>(shard->gather_out) + out_off + lo;
-            int le = launch_update(plan->dtype, plan->n_contrib, g, shard->master + lo,
-                                   shard->m + lo, shard->v + lo, out, cnt, s, comp);
-            if (le != 0) {
-                e = (hipError_t)le;
-                what = "update kernel launch";
-            }
-        }
-        if (timed)
-            PS_TRY(hipEventRecord(t1[b], comp));
-        PS_TRY(hipEventRecord(freed[k], comp));
-        if (b + 1 < n_buckets && alternate)
-            stage(b + 1);
-    }
-    // Later work on the copy stream must not overtake the last kernels.
-    if (!in_place)
-        PS_TRY(hipStreamWaitEvent(copy, freed[(n_buckets - 1) & 1], 0));
-
-    if (timed) {
-        PS_TRY(hipStreamSynchronize(comp));
-        if (!in_place)
-            PS_TRY(hipStreamSynchronize(copy));
-        for (uint64_t b = 0; b < n_buckets; ++b)
-            PS_TRY(hipEventElapsedTime(&plan->kernel_ms[b], t0[b], t1[b]));
-    }
-#undef PS_TRY
-    // Destroying an event that is still pending is allowed: its resources are
-    // released once the recorded work has completed.
-    for (int k = 0; k < 2; ++k) {
-        if (staged[k])
-            (void)hipEventDestroy(staged[k]);
-        if (freed[k])
-            (void)hipEventDestroy(freed[k]);
-    }
-    for (hipEvent_t ev : t0)
-        if (ev)
-            (void)hipEventDestroy(ev);
-    for (hipEvent_t ev : t1)
-        if (ev)
-            (void)hipEventDestroy(ev);
-    if (e != hipSuccess)
-        return hip_fail(e, what);
-    return PS_OK;
+    BucketRun run(shard, plan, derive_scalars(*hp, spec->n_devices, shard->param_dtype), out_off,
+                  n_buckets);
+    run.create_events(in_place);
+    if (in_place)
+        run.in_place();
+    else
+        run.staged();
+    run.collect_timings(in_place);
+    return run.finish();
 }
 
 uint64_t ps_verify_workspace_bytes(uint64_t buffer_bytes)

@@ -38,17 +38,22 @@ def _gen(seed, *stream):
     return g
 
 
+def _normal_into_(c, std, g, absolute, square):
+    """One chunk: c <- std * N(0,1) from generator g, optionally |.| or (.)^2."""
+    c.normal_(0.0, std, generator=g)
+    if absolute:
+        c.abs_()
+    if square:
+        c.mul_(c)
+    return c
+
+
 def fill_normal_(t, std, seed, *stream, absolute=False, square=False):
     """t <- std * N(0,1), optionally |.| or (.)^2, chunked."""
     g = _gen(seed, *stream)
     n = t.numel()
     for lo in range(0, n, CHUNK):
-        c = t[lo:min(lo + CHUNK, n)]
-        c.normal_(0.0, std, generator=g)
-        if absolute:
-            c.abs_()
-        if square:
-            c.mul_(c)
+        _normal_into_(t[lo:min(lo + CHUNK, n)], std, g, absolute, square)
     return t
 
 
@@ -101,14 +106,14 @@ def state_chunks(w, n=None):
     gens = [_gen(w.seed, k) for k in (1, 2, 3)]
     for lo in range(0, n, CHUNK):
         hi = min(lo + CHUNK, n)
-        th = torch.empty(hi - lo, dtype=torch.float32, device="cuda").normal_(0.0, w.theta_std, generator=gens[0])
+        th, m, v = [torch.empty(hi - lo, dtype=torch.float32, device="cuda") for _ in range(3)]
+        _normal_into_(th, w.theta_std, gens[0], False, False)
         if w.warm_moments:
-            m = torch.empty(hi - lo, dtype=torch.float32, device="cuda").normal_(0.0, 1e-3, generator=gens[1]).abs_()
-            v = torch.empty(hi - lo, dtype=torch.float32, device="cuda").normal_(0.0, 1e-3, generator=gens[2])
-            v.mul_(v)
+            _normal_into_(m, 1e-3, gens[1], True, False)
+            _normal_into_(v, 1e-3, gens[2], False, True)
         else:
-            m = torch.zeros(hi - lo, dtype=torch.float32, device="cuda")
-            v = torch.zeros(hi - lo, dtype=torch.float32, device="cuda")
+            m.zero_()
+            v.zero_()
         yield lo, hi, th, m, v
 
 

@@ -512,6 +512,58 @@ def test_both_phases_captured_in_a_hip_graph_and_replayed():
             assert np.array_equal(g_[valid:].view(np.uint8), a[valid:].view(np.uint8))
 
 
+def test_allocation_free_step_captured_in_a_hip_graph():
+    """What a caller under stream capture can use: the reduce phase with the library's own
+    partial-sum array (no workspace to allocate), the coefficient on the device, and the
+    bucket loop reading the reduced gradient in place.  One warm-up call outside the capture
+    (the first call per device looks the array up), then three replays against the oracle."""
+    N, n, bucket = 4, 9 * TILE + 120, 2 * TILE
+    _say("graph capture: static reduce + in-place bucket loop, n=%d N=%d" % (n, N))
+    spec = ps.ps_spec_preset("zero3", N, 1, n * N)
+    grads = [gen.gradient(n, 43, 0, r, "bf16", 1e-2) for r in range(N)]
+    state = [gen.master(n, 43), *gen.moments(n, 43, True), np.zeros(n, np.uint16)]
+    t, max_norm = 5, 0.05
+    hpd, _ = hp_of(None, t)
+    want = [a.copy() for a in state]
+    cdev = torch.zeros(1, dtype=torch.float32, device="cuda")
+    hp = ps.ps_adamw_t(hpd["lr"], hpd["beta1"], hpd["beta2"], hpd["eps"], hpd["weight_decay"], t,
+                       1.0, 0.0, cdev.data_ptr())
+    gd = [dev(g) for g in grads]
+    th, m, v, p = [dev(a) for a in state]
+    red = torch.zeros(-(-n // 512) * 512, dtype=torch.float32, device="cuda")
+    ssd = torch.zeros(1, dtype=torch.float64, device="cuda")
+    gl = grads_of(gd, "bf16")
+    plan = ps.ps_bucket_plan_t()
+    arr = (C.c_void_p * 1)(red.data_ptr())
+    plan.source = C.cast(arr, C.POINTER(C.c_void_p))
+    plan.n_contrib, plan.dtype, plan.bucket_elems, plan.source_elems = 1, ps.PS_F32, bucket, red.numel()
+    plan.copy_engine = ps.PS_COPY_NONE
+    shard = shard_of(th, m, v, p, n)
+    ps.ps_step_reduce_sumsq_static(spec, gl, 0.0, 0, ssd.data_ptr(), 0, 0, n, n, stream_handle())   # warm-up
+    torch.cuda.synchronize()
+    coef = orc.clip_coef(float(ssd.item()), 0.0, max_norm)
+    assert coef < 1.0
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.compute_stream = stream_handle()
+        ps.ps_step_reduce_sumsq_static(spec, gl, 0.0, red.data_ptr(), ssd.data_ptr(), 0, 0, n, n,
+                                       stream_handle())
+        ps.ps_step_clip_coef(ssd.data_ptr(), 0, max_norm, cdev.data_ptr(), stream_handle())
+        ps.ps_step_update_bucketed(spec, hp, shard, plan)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(th).view(np.uint32), state[0].view(np.uint32))   # capture ran nothing
+    s = orc.derive_scalars(t=t, n_devices=N, clip_coef=coef, **hpd)
+    for k in range(3):
+        red.fill_(float("nan")); ssd.fill_(-1.0); cdev.fill_(float("nan"))      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        orc.step_f32(grads, s, *want)
+        got = [host(x) for x in (th, m, v, p)]
+        assert assert_state_parity(got, want, "replay %d" % k) == 0
+        assert host(cdev)[0] == np.float32(coef)
+
+
 # ---- bucket pipeline ----
 
 def _bucketed(spec, hp, state, src_np, dtype, n, valid, bucket, engine, timed=False,
