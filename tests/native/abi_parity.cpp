@@ -1,6 +1,8 @@
 // Stand-alone check of the C ABI without Python: hipMalloc'd buffers, ps_step_update and
-// ps_step_reduce_sumsq through include/ps_step.h, compared bit for bit with the C oracle
-// (oracle/step.c, linked in as an object).  Test infrastructure, built by build().
+// ps_step_reduce_sumsq through include/ps_step.h, then a second step on arena buffers with
+// the allocation-free reduce and the bucket loop that reads in place, all compared bit for
+// bit with the C oracle (oracle/step.c, linked in as an object).  Test infrastructure,
+// built by build().
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -104,6 +106,52 @@ int main()
     bad += std::memcmp(rred.data(), omean.data(), n * 4) != 0;          // pad (-1) included
     bad += !(std::fabs(rss - oss) <= 1e-12 * oss);
     for (uint64_t e = valid; e < n; ++e) bad += rp[e] != 0xBEEF;
+    // ---- second step (t = 1001): arena buffers, allocation-free reduce, bucket loop in place ----
+    oracle_scalars s2;
+    oracle_derive_scalars(3e-4, 0.9, 0.999, 1e-8, 0.1, 1001, N, 0.0, 0.0, &s2);
+    oracle_step_f32(gp, N, 1, &s2, oth.data(), om.data(), ov.data(), op.data(), 0, 0, valid);
+    const uint32_t eb[N + 4] = {4, 4, 4, 4, 4, 4, 4, 4, 4, 2};        // six contributions, master, m, v, parameters
+    ps_arena_t *arena = nullptr;
+    PS(ps_arena_create(n, 1u << 20, eb, N + 4, &arena));
+    void *ab[N + 4];
+    for (uint32_t k = 0; k < N + 4; ++k) {
+        ab[k] = ps_arena_buffer(arena, k);
+        bad += ab[k] == nullptr || ((uintptr_t)ab[k] & ((2u << 20) - 1)) != 0;
+    }
+    bad += ps_arena_buffer(arena, N + 4) != nullptr;
+    for (uint32_t r = 0; r < N; ++r) HIP(hipMemcpy(ab[r], dg[r], n * 4, hipMemcpyDeviceToDevice));
+    HIP(hipMemcpy(ab[N], dth, n * 4, hipMemcpyDeviceToDevice));
+    HIP(hipMemcpy(ab[N + 1], dm, n * 4, hipMemcpyDeviceToDevice));
+    HIP(hipMemcpy(ab[N + 2], dv, n * 4, hipMemcpyDeviceToDevice));
+    HIP(hipMemcpy(ab[N + 3], dp, n * 2, hipMemcpyDeviceToDevice));
+    ps_grads_t gr2 = {(const void *const *)ab, N, PS_F32};
+    PS(ps_step_reduce_sumsq_static(&spec, &gr2, 0.0, nullptr, dss, 0, 0, n, valid, st));
+    ps_adamw_t hp2 = hp;
+    hp2.step = 1001;
+    ps_shard_t sh2 = {(float *)ab[N], (float *)ab[N + 1], (float *)ab[N + 2], ab[N + 3], n, valid};
+    ps_bucket_plan_t plan;
+    std::memset(&plan, 0, sizeof plan);
+    plan.source = (const void *const *)ab;
+    plan.n_contrib = N;
+    plan.dtype = PS_F32;
+    plan.bucket_elems = 4096;
+    plan.source_elems = (n + 511) / 512 * 512;     // the arena rounds every buffer up to whole 2 MiB pages
+    plan.compute_stream = st;
+    plan.copy_engine = PS_COPY_NONE;
+    PS(ps_step_update_bucketed(&spec, &hp2, &sh2, &plan));
+    HIP(hipStreamSynchronize(st));
+    double rss2 = 0;
+    HIP(hipMemcpy(rth.data(), ab[N], n * 4, hipMemcpyDeviceToHost));
+    HIP(hipMemcpy(rm.data(), ab[N + 1], n * 4, hipMemcpyDeviceToHost));
+    HIP(hipMemcpy(rv.data(), ab[N + 2], n * 4, hipMemcpyDeviceToHost));
+    HIP(hipMemcpy(rp.data(), ab[N + 3], n * 2, hipMemcpyDeviceToHost));
+    HIP(hipMemcpy(&rss2, dss, 8, hipMemcpyDeviceToHost));
+    bad += std::memcmp(rth.data(), oth.data(), n * 4) != 0;
+    bad += std::memcmp(rm.data(), om.data(), n * 4) != 0;
+    bad += std::memcmp(rv.data(), ov.data(), n * 4) != 0;
+    bad += std::memcmp(rp.data(), op.data(), n * 2) != 0;
+    bad += rss2 != rss;                                                 // same kernels, same tree, same bits
+    PS(ps_arena_destroy(arena));
     // error path through the C ABI
     ps_grads_t missing = {(const void *const *)dg, N - 1, PS_F32};
     bad += ps_step_update(&spec, &hp, &sh, &missing, 0, n, st) != PS_EINVAL;
