@@ -12,19 +12,25 @@
  * Conventions
  *   - Plain C types only.  Every pointer below is marked HOST or DEVICE.
  *   - DEVICE buffers are owned by the caller, must be 16-byte aligned and must
- *     stay alive until the work queued on the given stream has finished.  The
- *     library never allocates, frees or keeps them.  (Speed, not correctness:
- *     the kernels run 3-7 % faster on MI355X when all buffers of a call start
- *     on 4 KiB boundaries, as separate allocations do.)
+ *     stay alive until the work queued on the given stream has finished.  No
+ *     step, scan or copy call allocates, frees or keeps device memory; the one
+ *     call that allocates is ps_arena_create, for callers who want their flat
+ *     buffers laid out for this part's HBM.  (Speed, not correctness: the
+ *     kernels run 3-7 % faster on MI355X when all buffers of a call start on
+ *     4 KiB boundaries, as separate allocations do, and 5 % faster when the
+ *     operands of a launch lie close together physically, see ps_arena_create.)
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *     Calls that take a stream only enqueue work and return; they never
  *     synchronise the device.
  *   - No exceptions and no aborts cross this boundary.  Every call returns a
  *     ps_status_t; validation happens before the first HIP call, so argument
  *     errors are reported identically with or without a GPU.
- *   - The library keeps no state between calls except a thread-local error
- *     string.  The step count t and all buffers belong to the caller, so a
- *     checkpoint is a copy of the flat shard buffers plus t.
+ *   - The library keeps no state of the optimisation between calls: the step
+ *     count t and all buffers belong to the caller, so a checkpoint is a copy of
+ *     the flat shard buffers plus t.  What it does keep: a thread-local error
+ *     string, per device the address of its static partial-sum array
+ *     (ps_step_reduce_sumsq_static), and the measurement override of
+ *     ps_probe_set_update_residency.
  *   - Sizes are element counts unless the name says bytes.  GB = 1e9 bytes in
  *     the cost figures, as in the paper's examples.
  */
