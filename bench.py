@@ -336,7 +336,7 @@ def main():
                    "bucket_elems": (B if bucketed else 0), "launches_per_step": launches_per_step,
                    "bucket_source": ((("every bucket of every contribution resident in HBM and distinct "
                                        "(%d elements per contribution, %.1f GB in all)"
-                                       % (pool_elems, N * pool_elems * esz / 1e9)) if pool_elems >= n else
+                                       % (n, N * n * esz / 1e9)) if pool_elems >= n else
                                       ("resident pool of %d elements per contribution (%.2f GB in all), "
                                        "repeating" % (pool_elems, N * pool_elems * esz / 1e9))) +
                                      ("; read in place by the update kernel, one launch per bucket"
