@@ -647,6 +647,65 @@ def test_bucketed_step_with_a_repeating_source_pool(dtype, engine, pool):
     assert assert_state_parity(got, want, "pool") == 0
 
 
+def test_bucket_loop_geometry_at_random():
+    """Forty seeded draws of shard length, valid length, bucket size, source length and
+    contribution count for the loop that reads in place (the source wraps anywhere inside a
+    bucket, buckets end anywhere) and for the staged pipeline; each compared with the oracle
+    on every element, pads included."""
+    rng = np.random.default_rng(20260102)
+    for case in range(40):
+        N = int(rng.integers(1, 9))
+        dtype = "bf16" if N > 1 and rng.random() < 0.6 else "f32"
+        if N == 1:
+            dtype = "f32"                                           # one contribution: a pre-reduced gradient
+        bucket = int(rng.integers(1, 40)) * 8 * int(rng.choice([1, 8, 64]))
+        n = int(rng.integers(1, 9)) * bucket + int(rng.integers(0, bucket // 8 + 1)) * 8
+        valid = n - int(rng.integers(0, min(n, 300)))
+        pool = int(rng.integers(1, 2 + n // 512)) * 512
+        engine = ps.PS_COPY_NONE if case % 4 else ps.PS_COPY_KERNEL
+        _say("random bucket loop %d: n=%d valid=%d bucket=%d pool=%d N=%d %s engine=%d" %
+             (case, n, valid, bucket, pool, N, dtype, engine))
+        spec = ps.ps_spec_preset("zero3", max(N, 2), 0, n * max(N, 2))
+        src = [gen.gradient(pool, 59, case, r, dtype, 1e-3) for r in range(N)]
+        state = [gen.master(n, 59 + case), *gen.moments(n, 59 + case, True), np.full(n, 0x1234, np.uint16)]
+        hpd, hp = hp_of(None, 3 + case, grad_scale=1.0 if N == 1 else 0.0)
+        want = [a.copy() for a in state]
+        orc.step_f32(_periodic(src, n), orc.derive_scalars(t=3 + case, n_devices=max(N, 2),
+                                                             grad_scale=1.0 if N == 1 else 0.0, **hpd),
+                     *want, lo=0, hi=valid)
+        got, _ = _bucketed(spec, hp, state, src, dtype, n, valid, bucket, engine)
+        assert assert_state_parity(got, want, "random case %d" % case) == 0
+        for g, a in zip(got, state):
+            assert np.array_equal(g[valid:].view(np.uint8), a[valid:].view(np.uint8))
+
+
+def test_residency_override_changes_speed_never_results():
+    """ps_probe_set_update_residency is a measurement aid: with any cap, or none, the update
+    writes the same bits."""
+    n, N = 70 * TILE + 9, 8
+    spec = ps.ps_spec_preset("zero3", N, 0, n * N)
+    grads = [gen.gradient(n, 61, 0, r, "bf16", 1e-3) for r in range(N)]
+    state = [gen.master(n, 61), *gen.moments(n, 61, True), np.zeros(n, np.uint16)]
+    hpd, hp = hp_of(None, 4)
+    ref = None
+    try:
+        for cap in (0, 3, 8, 32, 40):
+            ps.ps_probe_set_update_residency(cap)
+            got = _run_gpu(spec, hp, state, grads, "bf16", n)
+            if ref is None:
+                ref = got
+            for a, b in zip(got, ref):
+                assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), "cap %d changed the result" % cap
+        with pytest.raises(ps.PsError) as e:
+            ps.ps_probe_set_update_residency(2)
+        assert e.value.status == ps.PS_ERANGE
+    finally:
+        ps.ps_probe_set_update_residency(0)
+    want = [a.copy() for a in state]
+    orc.step_f32(grads, orc.derive_scalars(t=4, n_devices=N, **hpd), *want)
+    assert assert_state_parity(ref, want, "residency") == 0
+
+
 def test_step_on_arena_buffers_matches_oracle():
     """Flat buffers whose physical memory is created chunk by chunk (ps_arena_create): the
     bucket loop reads the contributions in place from them.  Chunks of 2^20 elements, a ragged
