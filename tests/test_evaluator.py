@@ -241,3 +241,17 @@ def test_a_library_built_from_other_sources_counts_as_stale(tmp_path, monkeypatc
     assert build.stale()                                  # built from something else
     (tmp_path / "id").write_text(build.source_id() + "\n")
     assert not build.stale()
+
+
+def test_public_header_is_plain_c():
+    """include/ps_step.h is the boundary: it must compile as C11 and as C++17 on its own,
+    with no HIP, torch or library-internal type in sight."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    hdr = os.path.join(root, "include", "ps_step.h")
+    for cmd in (["gcc", "-std=c11", "-x", "c"], ["g++", "-std=c++17", "-x", "c++"]):
+        p = subprocess.run(cmd + ["-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", hdr],
+                           stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        assert p.returncode == 0, p.stdout
+    text = open(hdr).read()
+    assert "hip/" not in text and "torch" not in text
