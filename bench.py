@@ -55,9 +55,11 @@ def main():
     ap.add_argument("--pool-elems", type=int, default=0,
                     help="elements per contribution of the resident bucket source; 0 (default): the "
                          "whole shard length, every bucket distinct; shorter: a pool that repeats")
-    ap.add_argument("--copy-engine", choices=["none", "kernel", "memcpy"], default="none",
+    ap.add_argument("--copy-engine", choices=["none", "kernel", "memcpy", "reduce"], default="none",
                     help="none: the update reads each bucket of the resident source in place; kernel, "
-                         "memcpy: the two-stream pipeline that stages each bucket first")
+                         "memcpy: the two-stream pipeline that stages each bucket first; reduce: the "
+                         "same pipeline with the reduce kernel as its staging engine (the FP32 sum is "
+                         "what gets staged)")
     ap.add_argument("--alloc", choices=["arena", "plain"], default="arena",
                     help="bucketed workload with the whole source resident: arena = flat buffers whose "
                          "physical memory is created bucket by bucket (ps_arena_create), so that a "
@@ -182,7 +184,7 @@ def main():
         plan.n_contrib, plan.dtype = N, dt
         plan.bucket_elems, plan.source_elems = B, pool_elems
         plan.copy_engine = {"none": ps.PS_COPY_NONE, "kernel": ps.PS_COPY_KERNEL,
-                            "memcpy": ps.PS_COPY_MEMCPY}[args.copy_engine]
+                            "memcpy": ps.PS_COPY_MEMCPY, "reduce": ps.PS_COPY_REDUCE}[args.copy_engine]
         plan.schedule = {"auto": ps.PS_SCHED_AUTO, "overlap": ps.PS_SCHED_OVERLAP,
                          "alternate": ps.PS_SCHED_ALTERNATE}[args.schedule]
         if staging:
@@ -292,7 +294,9 @@ def main():
     if bucketed and args.extras:
         variants = [("in_place", ps.PS_COPY_NONE, ps.PS_SCHED_AUTO),
                     ("staged_copy_kernel_alternate", ps.PS_COPY_KERNEL, ps.PS_SCHED_ALTERNATE),
-                    ("staged_copy_kernel_overlap", ps.PS_COPY_KERNEL, ps.PS_SCHED_OVERLAP)]
+                    ("staged_copy_kernel_overlap", ps.PS_COPY_KERNEL, ps.PS_SCHED_OVERLAP),
+                    ("staged_reduce_kernel_alternate", ps.PS_COPY_REDUCE, ps.PS_SCHED_ALTERNATE),
+                    ("staged_reduce_kernel_overlap", ps.PS_COPY_REDUCE, ps.PS_SCHED_OVERLAP)]
         if pool_elems % B == 0:
             variants.append(("staged_memcpy_overlap", ps.PS_COPY_MEMCPY, ps.PS_SCHED_OVERLAP))
         keep = (plan.copy_engine, plan.schedule)

@@ -151,6 +151,15 @@ enum {
                            device code (device memory, or pinned host memory)        */
     PS_COPY_MEMCPY = 1, /* hipMemcpyAsync per contribution (DMA engines for host
                            sources); needs source_elems % bucket_elems == 0          */
+    PS_COPY_REDUCE = 3, /* the library's reduce kernel in place of a copy: it reads the
+                           bucket's N contributions from the source (memory device code
+                           can read: device, peer-mapped or pinned host) and leaves their
+                           fixed-order FP32 sum in the staging slot; the update takes that
+                           sum as its one contribution (same bits as reducing inside the
+                           update).  Slots of bucket_elems FP32 values suffice.  Moves
+                           2N + 4 bytes per element on the copy stream instead of 4N and
+                           leaves the update 4 bytes to read instead of 2N: the form for a
+                           source that is read over a link                             */
     PS_COPY_NONE = 2    /* no copy: the source is memory of THIS device and the update
                            reads every bucket where it lies, one kernel per bucket on
                            compute_stream (one per contiguous piece where a repeating
@@ -161,7 +170,7 @@ enum {
 
 /* How the staging copy of bucket b+1 and the update of bucket b share the device. */
 enum {
-    PS_SCHED_AUTO = 0,     /* PS_COPY_KERNEL: alternate; PS_COPY_MEMCPY: overlap            */
+    PS_SCHED_AUTO = 0,     /* PS_COPY_KERNEL, PS_COPY_REDUCE: alternate; PS_COPY_MEMCPY: overlap */
     PS_SCHED_OVERLAP = 1,  /* both run as soon as their inputs are ready                    */
     PS_SCHED_ALTERNATE = 2 /* the copy of bucket b+1 starts when the update of bucket b has
                               finished; still enqueued ahead on its own stream, no host wait */
@@ -195,10 +204,11 @@ typedef struct ps_bucket_plan_t {
     uint64_t source_elems;      /* >= 1, multiple of 512                                */
     void *staging[2];           /* DEVICE, each n_contrib * bucket_elems elements; slot
                                    layout: contribution r at element r * bucket_elems
-                                   (unused with PS_COPY_NONE)                          */
+                                   (PS_COPY_REDUCE: bucket_elems floats; unused with
+                                   PS_COPY_NONE)                                       */
     void *copy_stream;          /* hipStream_t (unused with PS_COPY_NONE)               */
     void *compute_stream;       /* hipStream_t, must differ from copy_stream            */
-    int32_t copy_engine;        /* PS_COPY_KERNEL, PS_COPY_MEMCPY or PS_COPY_NONE       */
+    int32_t copy_engine;        /* PS_COPY_KERNEL, PS_COPY_MEMCPY, PS_COPY_REDUCE, PS_COPY_NONE */
     int32_t schedule;           /* PS_SCHED_AUTO, PS_SCHED_OVERLAP or PS_SCHED_ALTERNATE */
     float *kernel_ms;           /* HOST, optional (may be NULL): receives, per bucket,
                                    the update kernel's duration in ms from HIP events

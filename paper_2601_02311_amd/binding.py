@@ -15,7 +15,7 @@ import torch  # noqa: F401
 from . import build as _build
 
 __all__ = [
-    "PS_R", "PS_S", "PS_SG", "PS_M", "PS_O", "PS_BF16", "PS_F32", "PS_F16", "PS_MAX_CONTRIB", "PS_COPY_KERNEL", "PS_COPY_MEMCPY", "PS_COPY_NONE", "PS_SCHED_AUTO", "PS_SCHED_OVERLAP", "PS_SCHED_ALTERNATE", "PS_HOST_FLAT", "PS_HOST_PACKED",
+    "PS_R", "PS_S", "PS_SG", "PS_M", "PS_O", "PS_BF16", "PS_F32", "PS_F16", "PS_MAX_CONTRIB", "PS_COPY_KERNEL", "PS_COPY_MEMCPY", "PS_COPY_NONE", "PS_COPY_REDUCE", "PS_SCHED_AUTO", "PS_SCHED_OVERLAP", "PS_SCHED_ALTERNATE", "PS_HOST_FLAT", "PS_HOST_PACKED",
     "PS_OK", "PS_EINVAL", "PS_EUNSUPPORTED", "PS_EALIGN", "PS_ERANGE", "PS_ENODEVICE", "PS_EHIP",
     "PsError", "ps_spec_t", "ps_cost_t", "ps_adamw_t", "ps_shard_t", "ps_grads_t",
     "ps_bucket_plan_t", "ps_offload_plan_t", "ps_device_info_t", "library", "library_path",
@@ -32,7 +32,7 @@ __all__ = [
 ABI_VERSION = 4   # PS_ABI_VERSION of include/ps_step.h this binding mirrors
 PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
 PS_BF16, PS_F32, PS_F16 = 0, 1, 2
-PS_COPY_KERNEL, PS_COPY_MEMCPY, PS_COPY_NONE = 0, 1, 2
+PS_COPY_KERNEL, PS_COPY_MEMCPY, PS_COPY_NONE, PS_COPY_REDUCE = 0, 1, 2, 3
 PS_SCHED_AUTO, PS_SCHED_OVERLAP, PS_SCHED_ALTERNATE = 0, 1, 2
 PS_HOST_FLAT, PS_HOST_PACKED = 0, 1
 PS_MAX_CONTRIB = 16

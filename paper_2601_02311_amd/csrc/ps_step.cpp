@@ -362,7 +362,8 @@ class BucketRun {
           // side they only widen each other's request windows, so they take turns.  A
           // DMA copy (host or peer source) is bound by its link and overlaps.
           alternate_(plan->schedule == PS_SCHED_ALTERNATE ||
-                     (plan->schedule == PS_SCHED_AUTO && plan->copy_engine == PS_COPY_KERNEL))
+                     (plan->schedule == PS_SCHED_AUTO && plan->copy_engine != PS_COPY_MEMCPY)),
+          reduce_(plan->copy_engine == PS_COPY_REDUCE)
     {
     }
 
@@ -399,7 +400,7 @@ class BucketRun {
                 std::memset(&g, 0, sizeof g);
                 for (uint32_t r = 0; r < plan_->n_contrib; ++r)
                     g.p[r] = reinterpret_cast<const char *>(plan_->source[r]) + pos * eb_;
-                update(g, cur, take);
+                update(g, cur, take, plan_->dtype, plan_->n_contrib);
                 cur += take;
             }
             mark(t1_, b);
@@ -424,9 +425,14 @@ class BucketRun {
             if (cnt && ok()) {
                 ContribPtrs g;
                 std::memset(&g, 0, sizeof g);
-                for (uint32_t r = 0; r < plan_->n_contrib; ++r)
-                    g.p[r] = reinterpret_cast<const char *>(plan_->staging[k]) + r * slot_stride_;
-                update(g, lo, cnt);
+                if (reduce_) { // the slot holds the contributions' FP32 sum
+                    g.p[0] = plan_->staging[k];
+                    update(g, lo, cnt, PS_F32, 1);
+                } else {
+                    for (uint32_t r = 0; r < plan_->n_contrib; ++r)
+                        g.p[r] = reinterpret_cast<const char *>(plan_->staging[k]) + r * slot_stride_;
+                    update(g, lo, cnt, plan_->dtype, plan_->n_contrib);
+                }
             }
             mark(t1_, b);
             PS_ATTEMPT(hipEventRecord(freed_[k], comp_));
@@ -488,10 +494,10 @@ class BucketRun {
     }
 
     // The update kernel over shard elements [lo, lo + count) from the contributions at g.
-    void update(const ContribPtrs &g, uint64_t lo, uint64_t count)
+    void update(const ContribPtrs &g, uint64_t lo, uint64_t count, int dtype, uint32_t n_contrib)
     {
         uint16_t *out = reinterpret_cast<uint16_t *>(shard_->gather_out) + out_off_ + lo;
-        int le = launch_update(plan_->dtype, plan_->n_contrib, g, shard_->master + lo, shard_->m + lo,
+        int le = launch_update(dtype, n_contrib, g, shard_->master + lo, shard_->m + lo,
                                shard_->v + lo, out, count, s_, comp_);
         if (le != 0)
             note((hipError_t)le, "update kernel launch");
@@ -514,6 +520,23 @@ class BucketRun {
                 PS_ATTEMPT(hipMemcpyAsync(reinterpret_cast<char *>(plan_->staging[k]) + r * slot_stride_,
                                        reinterpret_cast<const char *>(plan_->source[r]) + src_off,
                                        cnt * eb_, hipMemcpyDefault, copy_));
+        } else if (reduce_) {
+            // one reduce launch per contiguous piece of the (possibly repeating) source
+            for (uint64_t cur = lo; cur < lo + cnt && ok();) {
+                const uint64_t pos = cur % plan_->source_elems;
+                const uint64_t room = plan_->source_elems - pos;
+                const uint64_t take = lo + cnt - cur < room ? lo + cnt - cur : room;
+                ContribPtrs src;
+                std::memset(&src, 0, sizeof src);
+                for (uint32_t r = 0; r < plan_->n_contrib; ++r)
+                    src.p[r] = reinterpret_cast<const char *>(plan_->source[r]) + pos * eb_;
+                int le = launch_accumulate(plan_->dtype, plan_->n_contrib, src,
+                                           reinterpret_cast<float *>(plan_->staging[k]) + (cur - lo), 1,
+                                           take, copy_);
+                if (le != 0)
+                    note((hipError_t)le, "reduce kernel launch");
+                cur += take;
+            }
         } else if (ok()) {
             ContribPtrs src;
             std::memset(&src, 0, sizeof src);
@@ -534,7 +557,7 @@ class BucketRun {
     const StepScalars s_;
     const uint64_t out_off_, n_buckets_, eb_, slot_stride_;
     hipStream_t copy_, comp_;
-    const bool timed_, alternate_;
+    const bool timed_, alternate_, reduce_;
     hipEvent_t staged_[2] = {nullptr, nullptr}, freed_[2] = {nullptr, nullptr};
     std::vector<hipEvent_t> t0_, t1_;
     hipError_t e_ = hipSuccess;
@@ -769,8 +792,9 @@ ps_status_t ps_step_update_bucketed(const ps_spec_t *spec, const ps_adamw_t *hp,
         return PS_EALIGN;
     }
     if (plan->copy_engine != PS_COPY_KERNEL && plan->copy_engine != PS_COPY_MEMCPY &&
-        plan->copy_engine != PS_COPY_NONE) {
-        set_error("copy_engine must be PS_COPY_KERNEL, PS_COPY_MEMCPY or PS_COPY_NONE");
+        plan->copy_engine != PS_COPY_NONE && plan->copy_engine != PS_COPY_REDUCE) {
+        set_error("copy_engine must be PS_COPY_KERNEL, PS_COPY_MEMCPY, PS_COPY_REDUCE or "
+                  "PS_COPY_NONE");
         return PS_EINVAL;
     }
     const bool in_place = plan->copy_engine == PS_COPY_NONE;

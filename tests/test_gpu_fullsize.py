@@ -194,25 +194,30 @@ def test_70b_zero3_in_place_every_element(capsys):
     torch.cuda.empty_cache()
 
 
-def test_70b_zero3_staged_pipeline_whole_buckets(capsys):
-    """The two-stream pipeline that stages each bucket first, at full size, from a pool whose
-    length does not divide the bucket size (every bucket starts somewhere else in the pool and
-    wraps inside it).  Whole buckets 0, 15 (the other staging slot), 16 and the short last one
-    are compared element by element with the oracle; the rest of the shard by properties."""
+@pytest.mark.parametrize("engine", ["copy", "reduce"])
+def test_70b_zero3_staged_pipeline_whole_buckets(engine, capsys):
+    """The two-stream pipeline that stages each bucket first (the copy kernel, or the reduce
+    kernel staging the FP32 sum), at full size, from a pool whose length does not divide the
+    bucket size (every bucket starts somewhere else in the pool and wraps inside it).  Whole
+    buckets 0, 15 (the other staging slot), 16 and the short last one are compared element by
+    element with the oracle; the rest of the shard by properties."""
     w = WORKLOADS["70b_zero3"]
     _need(150)
     n, N, t, B = w.shard_len, w.n_devices, w.first_step, w.bucket_elems
     pool_elems = 5 * (1 << 25) + 3 * 512
     n_b = -(-n // B)
     check = (0, 15, 16, n_b - 1)
-    _say("70b_zero3 staged: n=%d, %d buckets of %d, pool %d, whole buckets %s" % (n, n_b, B, pool_elems, check))
+    _say("70b_zero3 staged (%s): n=%d, %d buckets of %d, pool %d, whole buckets %s" % (engine, n, n_b, B, pool_elems, check))
     spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi)
     master, m, v = dgen.workload_state(w)
     out = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
     pool = [dgen.fill_gradient_(torch.empty(pool_elems, dtype=torch.bfloat16, device="cuda"),
                                 w.seed, t, r, w.grad_std) for r in range(N)]
     pool_np = [host(p) for p in pool]
-    staging = [torch.empty(N * B, dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    if engine == "reduce":          # the slots hold one FP32 sum per element
+        staging = [torch.empty(B, dtype=torch.float32, device="cuda") for _ in range(2)]
+    else:
+        staging = [torch.empty(N * B, dtype=torch.bfloat16, device="cuda") for _ in range(2)]
     copy, comp = torch.cuda.Stream(), torch.cuda.Stream()
     torch.cuda.synchronize()
     plan = ps.ps_bucket_plan_t()
@@ -221,7 +226,8 @@ def test_70b_zero3_staged_pipeline_whole_buckets(capsys):
     plan.n_contrib, plan.dtype, plan.bucket_elems, plan.source_elems = N, ps.PS_BF16, B, pool_elems
     plan.staging[0], plan.staging[1] = staging[0].data_ptr(), staging[1].data_ptr()
     plan.copy_stream, plan.compute_stream = copy.cuda_stream, comp.cuda_stream
-    plan.copy_engine, plan.schedule = ps.PS_COPY_KERNEL, ps.PS_SCHED_AUTO
+    plan.copy_engine = ps.PS_COPY_REDUCE if engine == "reduce" else ps.PS_COPY_KERNEL
+    plan.schedule = ps.PS_SCHED_AUTO
     hpd, hp = _hp(w, t)
     ps.ps_step_update_bucketed(spec, hp, shard_of(master, m, v, out, n), plan)
     torch.cuda.synchronize()

@@ -602,7 +602,9 @@ def _periodic(src_np, n):
                                              (ps.PS_COPY_KERNEL, ps.PS_SCHED_OVERLAP),
                                              (ps.PS_COPY_MEMCPY, ps.PS_SCHED_AUTO),
                                              (ps.PS_COPY_MEMCPY, ps.PS_SCHED_ALTERNATE),
-                                             (ps.PS_COPY_NONE, ps.PS_SCHED_AUTO)])
+                                             (ps.PS_COPY_NONE, ps.PS_SCHED_AUTO),
+                                             (ps.PS_COPY_REDUCE, ps.PS_SCHED_AUTO),
+                                             (ps.PS_COPY_REDUCE, ps.PS_SCHED_OVERLAP)])
 @pytest.mark.parametrize("timed", [False, True])
 def test_bucketed_step_matches_oracle(timed, engine, schedule):
     bucket, N = 2 * TILE + 512, 8          # 4608: a multiple of 512 so that both engines apply
@@ -631,7 +633,10 @@ def test_bucketed_step_matches_oracle(timed, engine, schedule):
                                                ("f32", ps.PS_COPY_KERNEL, 512),          # buckets straddle the wrap
                                                ("f32", ps.PS_COPY_NONE, 2 * TILE),       # read in place: whole
                                                ("bf16", ps.PS_COPY_NONE, 1536),          # buckets, pieces of a
-                                               ("bf16", ps.PS_COPY_NONE, 512)])          # bucket, many pieces
+                                               ("bf16", ps.PS_COPY_NONE, 512),           # bucket, many pieces
+                                               ("f32", ps.PS_COPY_REDUCE, 2 * TILE),     # the reduce kernel as
+                                               ("bf16", ps.PS_COPY_REDUCE, 1536),        # the staging engine,
+                                               ("bf16", ps.PS_COPY_REDUCE, 512)])        # same source shapes
 def test_bucketed_step_with_a_repeating_source_pool(dtype, engine, pool):
     """A source shorter than the shard repeats: element e reads source[e % source_elems]
     (how the benchmark feeds 33 buckets from a small resident pool)."""
@@ -662,7 +667,7 @@ def test_bucket_loop_geometry_at_random():
         n = int(rng.integers(1, 9)) * bucket + int(rng.integers(0, bucket // 8 + 1)) * 8
         valid = n - int(rng.integers(0, min(n, 300)))
         pool = int(rng.integers(1, 2 + n // 512)) * 512
-        engine = ps.PS_COPY_NONE if case % 4 else ps.PS_COPY_KERNEL
+        engine = (ps.PS_COPY_NONE, ps.PS_COPY_KERNEL, ps.PS_COPY_NONE, ps.PS_COPY_REDUCE)[case % 4]
         _say("random bucket loop %d: n=%d valid=%d bucket=%d pool=%d N=%d %s engine=%d" %
              (case, n, valid, bucket, pool, N, dtype, engine))
         spec = ps.ps_spec_preset("zero3", max(N, 2), 0, n * max(N, 2))

@@ -189,7 +189,7 @@ def test_bucketed_rejects_bad_arguments():
     assert _status(lambda: run(spec, hp, shard, plan(bucket_elems=100))) == ps.PS_EALIGN
     assert _status(lambda: run(spec, hp, shard, plan(source_elems=0))) == ps.PS_ERANGE
     assert _status(lambda: run(spec, hp, shard, plan(source_elems=1000))) == ps.PS_EALIGN
-    assert _status(lambda: run(spec, hp, shard, plan(copy_engine=3))) == ps.PS_EINVAL
+    assert _status(lambda: run(spec, hp, shard, plan(copy_engine=4))) == ps.PS_EINVAL
     assert _status(lambda: run(spec, hp, shard, plan(copy_engine=ps.PS_COPY_NONE,
                                                        source_elems=1000))) == ps.PS_EALIGN
     assert _status(lambda: run(spec, hp, shard, plan(schedule=3))) == ps.PS_EINVAL
