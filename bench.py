@@ -107,7 +107,6 @@ def main():
     torch.cuda.set_device(0)
     info = ps.ps_device_info()
     n, N = w.shard_len, w.n_devices
-    clip = w.max_grad_norm > 0
     spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi, align_elems=w.align_elems)
     cost = ps.ps_cost_eval(spec)
     assert cost.shard_len == n
@@ -124,21 +123,34 @@ def main():
     bucketed = w.bucket_elems > 0
     arena = None
     out_len = cost.psi_padded if spec.theta == ps.PS_R else n
-    if (bucketed and args.alloc == "arena" and not args.pool_elems and not args.source_host
-            and out_len == n):
-        # contributions 0..N-1, master, m, v, parameters: flat, physically interleaved by bucket
+    clip = w.max_grad_norm > 0
+    # Which buffers come out of the arena (flat, physical memory created chunk by chunk):
+    # contributions 0..N-1, master, m, v, then the parameters where they are shard-sized, the
+    # reduced gradient of a clipped step and the accumulator of micro-batches.
+    a_out = a_red = a_acc = None
+    eb = [esz] * N + [4, 4, 4]
+    if out_len == n:
+        a_out, eb = len(eb), eb + [2]
+    if clip:
+        a_red, eb = len(eb), eb + [4]
+    if w.micro_batches > 1:
+        a_acc, eb = len(eb), eb + [4]
+    want_arena = args.alloc == "arena" and not args.pool_elems and not args.source_host
+    if want_arena and (bucketed or (w.strategy != "zero1" and n >= (1 << 29))):
         try:
-            arena = ps.ps_arena_create(n, args.arena_chunk_elems or args.bucket_elems or w.bucket_elems,
-                                       [esz] * N + [4, 4, 4, 2])
+            arena = ps.ps_arena_create(n, args.arena_chunk_elems or args.bucket_elems or w.bucket_elems
+                                       or (1 << 28), eb)
         except ps.PsError as err:
             log("arena not created (%s): plain allocations instead" % err.detail)
     if arena is not None:
-        a_buf = [ps.ps_arena_buffer(arena, k) for k in range(N + 4)]
+        a_buf = [ps.ps_arena_buffer(arena, k) for k in range(len(eb))]
         master, m, v = dgen.workload_state(w, into=[dgen.as_tensor(a_buf[N + j], n, torch.float32)
                                                     for j in range(3)])
-        out = dgen.as_tensor(a_buf[N + 3], n, ptd).zero_()
     else:
         master, m, v = dgen.workload_state(w)
+    if arena is not None and a_out is not None:
+        out = dgen.as_tensor(a_buf[a_out], n, ptd).zero_()
+    else:
         out = torch.zeros(out_len, dtype=ptd, device="cuda")
     shard = ps.ps_shard_t(master.data_ptr(), m.data_ptr(), v.data_ptr(), out.data_ptr(), n,
                           cost.valid_len, pdt, 0)
@@ -213,18 +225,24 @@ def main():
         if zero1:      # the all-reduced gradient: one replicated buffer of psi_padded elements
             grads = [dgen.fill_gradient_(torch.empty(cost.psi_padded, dtype=tdt, device="cuda"),
                                          w.seed, w.first_step, 0, w.grad_std)]
+        elif arena is not None:
+            grads = [dgen.fill_gradient_(dgen.as_tensor(a_buf[r], n, tdt), w.seed, w.first_step, r,
+                                         w.grad_std * w.loss_scale, w.outlier_frac, w.outlier_mult,
+                                         w.student_t_dof) for r in range(N)]
         else:
             grads = dgen.workload_gradients(w, w.first_step)
         g = ps.make_grads([t.data_ptr() for t in grads], dt)
         if k_mb > 1:
-            accum = torch.empty(n, dtype=torch.float32, device="cuda")
+            accum = (dgen.as_tensor(a_buf[a_acc], n, torch.float32) if arena is not None
+                     else torch.empty(n, dtype=torch.float32, device="cuda"))
             gacc = ps.make_grads([accum.data_ptr()], ps.PS_F32)
         launches_per_step = 1
         elems_per_launch = cost.valid_len
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
               for _ in range(args.steps)]
         if clip:
-            red = torch.empty(n, dtype=torch.float32, device="cuda")
+            red = (dgen.as_tensor(a_buf[a_red], n, torch.float32) if arena is not None
+                   else torch.empty(n, dtype=torch.float32, device="cuda"))
             ssd = torch.zeros(1, dtype=torch.float64, device="cuda")
             ws = torch.empty(ps.ps_workspace_bytes(n), dtype=torch.uint8, device="cuda")
             gred = ps.make_grads([red.data_ptr()], ps.PS_F32)
@@ -349,9 +367,9 @@ def main():
                                       % (args.copy_engine, args.schedule)) +
                                      (" (source in pinned HOST memory)" if args.source_host else ""))
                                     if bucketed else None,
-                   "allocation": (("arena: flat buffers, physical memory created bucket by bucket"
-                                   if arena is not None else "one plain allocation per buffer")
-                                  if bucketed else None),
+                   "allocation": ("arena: flat buffers, physical memory created chunk by chunk (%s)"
+                                  % ("bucket by bucket" if bucketed else "2^28 elements")
+                                  if arena is not None else "one plain allocation per buffer"),
                    "clip_coefficient": (("host (one sync per step)" if args.clip_on_host
                                          else "device (no host round trip)") if clip else None),
                    "bytes_per_elem": bpe, "step_GBps": bpe * elems_per_step / (ms_per_step * 1e-3) / 1e9,
