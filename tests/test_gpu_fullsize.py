@@ -87,6 +87,27 @@ def _pinned(n_contrib, grad_torch_dtype, param_torch_dtype, extra=()):
     return HostChunks(**spec)
 
 
+class _Arena:
+    """Flat buffers as bench.py allocates them for the large workloads: one arena, physical
+    memory created in chunks of 2^28 elements; views for torch, released on exit."""
+
+    def __init__(self, n, elem_bytes, chunk=1 << 28):
+        self.n = n
+        self.handle = ps.ps_arena_create(n, chunk, elem_bytes)
+        self.ptr = [ps.ps_arena_buffer(self.handle, k) for k in range(len(elem_bytes))]
+
+    def view(self, k, dtype):
+        return dgen.as_tensor(self.ptr[k], self.n, dtype)
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        torch.cuda.synchronize()
+        ps.ps_arena_destroy(self.handle)
+        return False
+
+
 def _check_every_element(capsys, what, w, s, pin, grads_of_chunk, master, m, v, out_slice, valid,
                          saved_head=None):
     """Every element of [0, valid) against the oracle: the state before the step is regenerated
@@ -133,23 +154,25 @@ def test_7b_zero2_full_shard_every_element(name, capsys):
     _say("%s full shard n=%d, one launch, every element" % (name, n))
     spec = ps.ps_spec_preset(w.strategy, N, w.shard_index, w.psi)
     cost = ps.ps_cost_eval(spec)
-    master, m, v = dgen.workload_state(w)
-    head = [_take(x, 0, 4096) for x in (master, m, v)]
-    grads = dgen.workload_gradients(w, t)
-    out = torch.zeros(cost.psi_padded, dtype=tdt, device="cuda")               # replicated Theta
-    gs = 1.0 / (N * w.loss_scale) if w.loss_scale != 1.0 else 0.0
-    hpd, hp = _hp(w, t, grad_scale=gs)
-    ps.ps_step_update(spec, hp, shard_of(master, m, v, out, n), ps.make_grads(
-        [g.data_ptr() for g in grads], ps.PS_F16 if f16 else ps.PS_BF16), 0, n, stream_handle())
-    torch.cuda.synchronize()
-    s = orc.derive_scalars(t=t, n_devices=N, grad_scale=gs, **hpd)
-    off = cost.shard_offset
-    pin = _pinned(N, tdt, tdt)
-    _check_every_element(capsys, name, w, s, pin,
-                         lambda lo, hi: [pin.fetch("g%d" % r, grads[r][lo:hi]) for r in range(N)],
-                         master, m, v, out[off:off + n], n, saved_head=head)
-    assert not bool(out[off + n:].view(torch.int16).any())                     # the other shards' slices untouched
-    del master, m, v, grads, out, pin
+    with _Arena(n, [2] * N + [4, 4, 4]) as ar:                                # contributions, master, m, v
+        master, m, v = dgen.workload_state(w, into=[ar.view(N + j, torch.float32) for j in range(3)])
+        head = [_take(x, 0, 4096) for x in (master, m, v)]
+        grads = [dgen.fill_gradient_(ar.view(r, tdt), w.seed, t, r, w.grad_std * w.loss_scale,
+                                     w.outlier_frac, w.outlier_mult, w.student_t_dof) for r in range(N)]
+        out = torch.zeros(cost.psi_padded, dtype=tdt, device="cuda")           # replicated Theta
+        gs = 1.0 / (N * w.loss_scale) if w.loss_scale != 1.0 else 0.0
+        hpd, hp = _hp(w, t, grad_scale=gs)
+        ps.ps_step_update(spec, hp, shard_of(master, m, v, out, n), ps.make_grads(
+            [g.data_ptr() for g in grads], ps.PS_F16 if f16 else ps.PS_BF16), 0, n, stream_handle())
+        torch.cuda.synchronize()
+        s = orc.derive_scalars(t=t, n_devices=N, grad_scale=gs, **hpd)
+        off = cost.shard_offset
+        pin = _pinned(N, tdt, tdt)
+        _check_every_element(capsys, name, w, s, pin,
+                             lambda lo, hi: [pin.fetch("g%d" % r, grads[r][lo:hi]) for r in range(N)],
+                             master, m, v, out[off:off + n], n, saved_head=head)
+        assert not bool(out[off + n:].view(torch.int16).any())                 # the other shards' slices untouched
+        del master, m, v, grads, out, pin
     torch.cuda.empty_cache()
 
 
@@ -277,49 +300,52 @@ def test_13b_clip_ragged_full_shard_every_element(capsys):
     n, valid = cost.shard_len, cost.valid_len
     assert n == w.shard_len and valid == n - 1001
     _say("13b_clip ragged full shard n=%d valid=%d N=%d fp32, two phases, every element" % (n, valid, N))
-    master, m, v = dgen.workload_state(w)
-    head = [_take(x, 0, 4096) for x in (master, m, v)]
-    grads = dgen.workload_gradients(w, t)
-    out = torch.full((n,), -1.0, dtype=torch.bfloat16, device="cuda")
-    red = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
-    ssd = torch.zeros(1, dtype=torch.float64, device="cuda")
-    ws = torch.empty(ps.ps_workspace_bytes(n), dtype=torch.uint8, device="cuda")
-    g = ps.make_grads([x.data_ptr() for x in grads], ps.PS_F32)
-    ps.ps_step_reduce_sumsq(spec, g, 0.0, red.data_ptr(), ssd.data_ptr(), 0, ws.data_ptr(),
-                            ws.numel(), 0, n, valid, stream_handle())
-    ss_gpu = float(ssd.item())
-    again = torch.zeros(1, dtype=torch.float64, device="cuda")
-    ps.ps_step_reduce_sumsq(spec, g, 0.0, 0, again.data_ptr(), 0, ws.data_ptr(), ws.numel(), 0, n,
-                            valid, stream_handle())
-    assert float(again.item()) == ss_gpu                                      # run-to-run identical
-    # phase 1 against the oracle: the mean bit for bit on every element, the sum within the
-    # sequential sum's own rounding bound (valid * 2^-53 relative, all terms >= 0)
-    pin = _pinned(N, torch.float32, torch.bfloat16, extra=[("red", torch.float32)])
-    gs = np.float32(1.0 / N)
-    ss_oracle, t0 = 0.0, time.time()
-    for lo in range(0, valid, CHUNK):
-        hi = min(lo + CHUNK, valid)
-        gr = [pin.fetch("g%d" % r, grads[r][lo:hi]) for r in range(N)]
-        gm, ss_c = orc.mean_sumsq(gr, gs, 0, hi - lo)
-        ss_oracle += ss_c
-        assert np.array_equal(gm.view(np.uint32), pin.fetch("red", red[lo:hi]).view(np.uint32))
-        if (lo // CHUNK) % 8 == 7 or hi == valid:
-            _progress(capsys, "13b phase 1: mean of %d of %d elements equals the oracle's, %.0f s"
-                      % (hi, valid, time.time() - t0))
-    assert abs(ss_gpu - ss_oracle) <= valid * 2.0 ** -53 * ss_oracle
-    assert bool(torch.isnan(red[valid:]).all())                               # pad never written
-    coef = orc.clip_coef(ss_oracle, 5 * ss_oracle, w.max_grad_norm)           # five iid peer shards
-    assert ps.ps_clip_coef(ss_oracle, 5 * ss_oracle, w.max_grad_norm) == coef
-    hpd, hp = _hp(w, t, grad_scale=1.0, clip_coef=coef)
-    ps.ps_step_update(spec, hp, shard_of(master, m, v, out, n, valid),
-                      ps.make_grads([red.data_ptr()], ps.PS_F32), 0, n, stream_handle())
-    torch.cuda.synchronize()
-    s = orc.derive_scalars(t=t, n_devices=N, clip_coef=coef, **hpd)           # the unsharded definition:
-    _check_every_element(capsys, "13b phase 2", w, s, pin,                    # six contributions, mean 1/N
-                         lambda lo, hi: [pin.fetch("g%d" % r, grads[r][lo:hi]) for r in range(N)],
-                         master, m, v, out, valid, saved_head=head)
-    assert bool((out[valid:].view(torch.int16) == out.new_full((1,), -1.0).view(torch.int16)).all())
-    del master, m, v, out, red, grads, ws, pin
+    # contributions, master, m, v, parameters, reduced gradient: the buffers bench.py allocates
+    with _Arena(n, [4] * N + [4, 4, 4, 2, 4]) as ar:
+        master, m, v = dgen.workload_state(w, into=[ar.view(N + j, torch.float32) for j in range(3)])
+        head = [_take(x, 0, 4096) for x in (master, m, v)]
+        grads = [dgen.fill_gradient_(ar.view(r, torch.float32), w.seed, t, r, w.grad_std * w.loss_scale,
+                                     w.outlier_frac, w.outlier_mult, w.student_t_dof) for r in range(N)]
+        out = ar.view(N + 3, torch.bfloat16).fill_(-1.0)
+        red = ar.view(N + 4, torch.float32).fill_(float("nan"))
+        ssd = torch.zeros(1, dtype=torch.float64, device="cuda")
+        ws = torch.empty(ps.ps_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+        g = ps.make_grads([x.data_ptr() for x in grads], ps.PS_F32)
+        ps.ps_step_reduce_sumsq(spec, g, 0.0, red.data_ptr(), ssd.data_ptr(), 0, ws.data_ptr(),
+                                ws.numel(), 0, n, valid, stream_handle())
+        ss_gpu = float(ssd.item())
+        again = torch.zeros(1, dtype=torch.float64, device="cuda")
+        ps.ps_step_reduce_sumsq(spec, g, 0.0, 0, again.data_ptr(), 0, ws.data_ptr(), ws.numel(), 0, n,
+                                valid, stream_handle())
+        assert float(again.item()) == ss_gpu                                  # run-to-run identical
+        # phase 1 against the oracle: the mean bit for bit on every element, the sum within the
+        # sequential sum's own rounding bound (valid * 2^-53 relative, all terms >= 0)
+        pin = _pinned(N, torch.float32, torch.bfloat16, extra=[("red", torch.float32)])
+        gs = np.float32(1.0 / N)
+        ss_oracle, t0 = 0.0, time.time()
+        for lo in range(0, valid, CHUNK):
+            hi = min(lo + CHUNK, valid)
+            gr = [pin.fetch("g%d" % r, grads[r][lo:hi]) for r in range(N)]
+            gm, ss_c = orc.mean_sumsq(gr, gs, 0, hi - lo)
+            ss_oracle += ss_c
+            assert np.array_equal(gm.view(np.uint32), pin.fetch("red", red[lo:hi]).view(np.uint32))
+            if (lo // CHUNK) % 8 == 7 or hi == valid:
+                _progress(capsys, "13b phase 1: mean of %d of %d elements equals the oracle's, %.0f s"
+                          % (hi, valid, time.time() - t0))
+        assert abs(ss_gpu - ss_oracle) <= valid * 2.0 ** -53 * ss_oracle
+        assert bool(torch.isnan(red[valid:]).all())                           # pad never written
+        coef = orc.clip_coef(ss_oracle, 5 * ss_oracle, w.max_grad_norm)       # five iid peer shards
+        assert ps.ps_clip_coef(ss_oracle, 5 * ss_oracle, w.max_grad_norm) == coef
+        hpd, hp = _hp(w, t, grad_scale=1.0, clip_coef=coef)
+        ps.ps_step_update(spec, hp, shard_of(master, m, v, out, n, valid),
+                          ps.make_grads([red.data_ptr()], ps.PS_F32), 0, n, stream_handle())
+        torch.cuda.synchronize()
+        s = orc.derive_scalars(t=t, n_devices=N, clip_coef=coef, **hpd)       # the unsharded definition:
+        _check_every_element(capsys, "13b phase 2", w, s, pin,                # six contributions, mean 1/N
+                             lambda lo, hi: [pin.fetch("g%d" % r, grads[r][lo:hi]) for r in range(N)],
+                             master, m, v, out, valid, saved_head=head)
+        assert bool((out[valid:].view(torch.int16) == out.new_full((1,), -1.0).view(torch.int16)).all())
+        del master, m, v, out, red, grads, ws, pin
     torch.cuda.empty_cache()
 
 
