@@ -442,6 +442,22 @@ def placement_map(args):
             row.append(e0.elapsed_time(e1) / args.steps)
         rows.append(row)
         log("contributions at %3d GiB: " % x + " ".join("%.3f" % t for t in row))
+    # Second table: relative alignment of the twelve streams.  All of them in one placement
+    # group (the first 16 GiB), stream k at k GiB + k * shift bytes for a few shifts.
+    shifts = [0, 256, 4096, 4352, 65536, 260 << 10, (1 << 20) + 8192]
+    align_ms = []
+    for sh_b in shifts:
+        at = lambda k: base + k * GiB + k * sh_b
+        g = ps.make_grads([at(r) for r in range(N)], ps.PS_BF16)
+        sh = ps.ps_shard_t(at(8), at(9), at(10), at(11), B, B, ps.PS_BF16, 0)
+        ps.ps_step_update(spec, hp, sh, g, 0, B, st)
+        e0.record()
+        for _ in range(args.steps):
+            ps.ps_step_update(spec, hp, sh, g, 0, B, st)
+        e1.record()
+        torch.cuda.synchronize()
+        align_ms.append(e0.elapsed_time(e1) / args.steps)
+    log("stream k at k GiB + k * shift: " + ", ".join("%d B: %.3f ms" % p for p in zip(shifts, align_ms)))
     flat = sorted(t for r in rows for t in r)
     fast = [t for t in flat if t < (flat[0] + flat[-1]) / 2]
     slow = [t for t in flat if t >= (flat[0] + flat[-1]) / 2]
@@ -453,7 +469,8 @@ def placement_map(args):
         "config": {"workload": "placement_map", "device": info.name.decode(),
                    "allocation_GiB": 248, "contribution_offsets_GiB": xs, "state_offsets_GiB": ys,
                    "ms": rows, "fast_pairs": len(fast), "fast_ms_avg": sum(fast) / len(fast),
-                   "slow_pairs": len(slow), "slow_ms_avg": sum(slow) / max(1, len(slow))},
+                   "slow_pairs": len(slow), "slow_ms_avg": sum(slow) / max(1, len(slow)),
+                   "alignment_shift_bytes": shifts, "alignment_ms": align_ms},
         "roofline": {"bound": "hbm", "achieved": 42 * B / (sum(fast) / len(fast)) / 1e6,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": 42 * B / (sum(fast) / len(fast)) / 1e6 / PEAK_HBM_GBS, "traffic": None,
