@@ -711,6 +711,23 @@ def test_residency_override_changes_speed_never_results():
     assert assert_state_parity(ref, want, "residency") == 0
 
 
+def test_arena_that_cannot_be_had_fails_cleanly():
+    """A piece larger than the device's memory: the call reports the runtime's error, leaves
+    nothing mapped or reserved behind, and the next arena is created as usual."""
+    free_before = torch.cuda.mem_get_info()[0]
+    with pytest.raises(ps.PsError) as e:
+        ps.ps_arena_create(1 << 38, 1 << 38, [4, 2])              # pieces of 1 TiB and 512 GiB
+    assert e.value.status == ps.PS_EHIP and e.value.detail
+    assert abs(torch.cuda.mem_get_info()[0] - free_before) < (64 << 20)
+    levels = []
+    for _ in range(3):                      # the runtime keeps some memory of its own after the first
+        arena = ps.ps_arena_create(1 << 24, 1 << 20, [4, 2])      # mapping; after that nothing may grow
+        assert ps.ps_arena_buffer(arena, 0) and ps.ps_arena_buffer(arena, 1)
+        ps.ps_arena_destroy(arena)
+        levels.append(torch.cuda.mem_get_info()[0])
+    assert levels[1] - levels[2] < (8 << 20) and free_before - levels[2] < (512 << 20)
+
+
 def test_step_on_arena_buffers_matches_oracle():
     """Flat buffers whose physical memory is created chunk by chunk (ps_arena_create): the
     bucket loop reads the contributions in place from them.  Chunks of 2^20 elements, a ragged
