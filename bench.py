@@ -367,6 +367,11 @@ def main():
                                       % (args.copy_engine, args.schedule)) +
                                      (" (source in pinned HOST memory)" if args.source_host else ""))
                                     if bucketed else None,
+                   "staged_pipeline": ("not in this figure: the source is resident, nothing is copied; the "
+                                       "two-stream pipeline that stages each bucket first is timed by --extras "
+                                       "and in profiles/stage_update__70b_zero3__hbm_traffic.txt (70-105 ms per "
+                                       "step from a source in HBM)") if bucketed and args.copy_engine == "none"
+                                      else None,
                    "allocation": ("arena: flat buffers, physical memory created chunk by chunk (%s)"
                                   % ("bucket by bucket" if bucketed else "2^28 elements")
                                   if arena is not None else "one plain allocation per buffer"),
