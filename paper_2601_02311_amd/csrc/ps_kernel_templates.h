@@ -16,7 +16,15 @@
 //   - the non-temporal hint on every load and store (nothing is reused);
 //   - every wave-level access one contiguous 1 KiB (FP32, 16 B per lane) or
 //     512 B (bf16, 8 B per lane) span, so each store instruction fills whole
-//     128-byte lines by itself.
+//     128-byte lines by itself;
+//   - outside the kernel's control: where the operands lie physically.  A launch whose
+//     streams are spread over a working set of hundreds of GB runs 5 % slower than one
+//     whose streams lie within a few GiB of one another (ps_arena.cpp lays flat buffers
+//     out accordingly).
+// In this mix a byte read costs about 0.12 ps and a byte written about 0.22 ps (the same
+// kernel with its contributions served from L2: 1.23 ms per 2^28 elements, from HBM: 1.75;
+// read-only scans reach 7.0-7.3 TB/s, the 12 B read + 14 B written of the state alone 5.7),
+// so with a third of its bytes written the step ends at 0.81-0.83 of the 8 TB/s peak.
 //
 // Work decomposition.  A tile is 256 consecutive elements; lane t owns
 // elements 4t..4t+3.  All loads of a tile are issued before the first
@@ -534,7 +542,8 @@ struct ScanArgs {
 // The scans only read, and a read-only stream is fastest on this part with large
 // workgroups that keep four 16-byte loads per lane in flight: 1024 lanes, 64 KiB
 // per workgroup (7.0-7.3 TB/s; single-wave workgroups as in the update kernel
-// stay at 6.1-6.6).  A launch covers whole groups; what is left goes to the tail.
+// stay at 6.1-6.6).  A launch covers whole groups; what is left, and the groups' partial
+// sums, go to one finishing workgroup.
 constexpr int kScanThreads = 1024;
 constexpr int kDiffVecs = 2;     // 16-byte vectors per lane and buffer: a group is 32 KiB of each
 constexpr int kChecksumVecs = 4; // 16-byte vectors per lane: a group is 64 KiB = 8192 words
