@@ -399,6 +399,9 @@ def main():
                                       else "HIP events around each step's launches in the timed region"},
         "extras": extras,
     }
+    # the plain copy kernel of the same launch shape as a second yardstick beside the nominal peak
+    result["roofline"]["copy_yardstick"] = extras["copy_probe"]["GBps"]
+    result["roofline"]["frac_of_copy_yardstick"] = achieved / extras["copy_probe"]["GBps"]
     if arena is not None:       # every view of its buffers is dead from here on
         torch.cuda.synchronize()
         ps.ps_arena_destroy(arena)
