@@ -1496,24 +1496,25 @@ def test_f16_bucket_pipeline_and_offload():
     grads, state, s, hp = _f16_case(n, N, 211)
     want = [a.copy() for a in state]
     orc.step_f32(grads, s, *want, lo=0, hi=valid)
-    # bucket pipeline: the source holds every bucket
-    th, m, v, p = [dev(a) for a in state]
+    # bucket loop, every engine that runs on the device: the source holds every bucket
     src = [dev(g) for g in grads]
-    staging = [torch.zeros(N * bucket * 2, dtype=torch.uint8, device="cuda") for _ in range(2)]
-    copy, comp = torch.cuda.Stream(), torch.cuda.Stream()
-    torch.cuda.synchronize()
-    plan = ps.ps_bucket_plan_t()
     n_src = -(-n // 512) * 512
     src = [torch.cat([x, torch.zeros(n_src - n, dtype=x.dtype, device="cuda")]) for x in src]
-    arr = (C.c_void_p * N)(*[x.data_ptr() for x in src])
-    plan.source = C.cast(arr, C.POINTER(C.c_void_p))
-    plan.n_contrib, plan.dtype, plan.bucket_elems, plan.source_elems = N, ps.PS_F16, bucket, n_src
-    plan.staging[0], plan.staging[1] = staging[0].data_ptr(), staging[1].data_ptr()
-    plan.copy_stream, plan.compute_stream = copy.cuda_stream, comp.cuda_stream
-    plan.copy_engine, plan.schedule = ps.PS_COPY_KERNEL, ps.PS_SCHED_AUTO
-    ps.ps_step_update_bucketed(spec, hp, shard_of(th, m, v, p, n, valid), plan)
-    torch.cuda.synchronize()
-    assert assert_state_parity([host(x) for x in (th, m, v, p)], want, "f16 bucketed") == 0
+    for engine in (ps.PS_COPY_KERNEL, ps.PS_COPY_NONE, ps.PS_COPY_REDUCE):
+        th, m, v, p = [dev(a) for a in state]
+        staging = [torch.zeros(N * bucket * 2, dtype=torch.uint8, device="cuda") for _ in range(2)]
+        copy, comp = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        plan = ps.ps_bucket_plan_t()
+        arr = (C.c_void_p * N)(*[x.data_ptr() for x in src])
+        plan.source = C.cast(arr, C.POINTER(C.c_void_p))
+        plan.n_contrib, plan.dtype, plan.bucket_elems, plan.source_elems = N, ps.PS_F16, bucket, n_src
+        plan.staging[0], plan.staging[1] = staging[0].data_ptr(), staging[1].data_ptr()
+        plan.copy_stream, plan.compute_stream = copy.cuda_stream, comp.cuda_stream
+        plan.copy_engine, plan.schedule = engine, ps.PS_SCHED_AUTO
+        ps.ps_step_update_bucketed(spec, hp, shard_of(th, m, v, p, n, valid), plan)
+        torch.cuda.synchronize()
+        assert assert_state_parity([host(x) for x in (th, m, v, p)], want, "f16 bucketed, engine %d" % engine) == 0
     # offload: state and FP16 parameters in pinned host memory
     spec_o = ps.ps_spec_preset("zero_offload", N, 3, n * N)
     pinned = [torch.from_numpy(a.copy()).pin_memory() for a in state]
