@@ -38,9 +38,9 @@ def bytes_per_elem(w, clip=False):
         return g * w.n_devices + 4 + 4 + 12 + 14
     if w.strategy == "zero1":          # one all-reduced gradient
         return g + 12 + 12 + 2
-    if w.micro_batches > 1:            # k accumulations (the first only writes), then the update
-        k = w.micro_batches
-        return k * (g * w.n_devices + 4) + (k - 1) * 4 + 4 + 12 + 14
+    if w.micro_batches > 1:            # k - 1 accumulations (the first only writes), then the update
+        k = w.micro_batches            # from the last micro-batch and the accumulator
+        return k * g * w.n_devices + (k - 1) * 4 + (k - 2) * 4 + 4 + 12 + 14
     return g * w.n_devices + 12 + 12 + 2
 
 
@@ -235,7 +235,7 @@ def main():
         if k_mb > 1:
             accum = (dgen.as_tensor(a_buf[a_acc], n, torch.float32) if arena is not None
                      else torch.empty(n, dtype=torch.float32, device="cuda"))
-            gacc = ps.make_grads([accum.data_ptr()], ps.PS_F32)
+            g_last = ps.make_grads([t.data_ptr() for t in grads], dt, accum=accum.data_ptr())
         launches_per_step = 1
         elems_per_launch = cost.valid_len
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
@@ -270,10 +270,11 @@ def main():
                         h.clip_coef_device = coef_dev.data_ptr()
                         ps.ps_step_update(spec, h, shard, gred, 0, n, s)
                 elif k_mb > 1:
-                    for j in range(k_mb):   # the same resident contributions stand for each micro-batch
+                    for j in range(k_mb - 1):   # the same resident contributions stand for each micro-batch
                         ps.ps_step_accumulate(spec, g, accum.data_ptr(), j == 0, 0, n,
                                               cost.valid_len, s)
-                    ps.ps_step_update(spec, hp(0.0, 1.0 / (N * k_mb)), shard, gacc, 0, n, s)
+                    # the last one goes straight into the update, beside the accumulator
+                    ps.ps_step_update(spec, hp(0.0, 1.0 / (N * k_mb)), shard, g_last, 0, n, s)
                 else:
                     ps.ps_step_update(spec, hp(), shard, g, 0, n, s)
                 if record:
@@ -389,7 +390,7 @@ def main():
                      "step_frac": bpe * elems_per_step / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
                      "traffic": measured_traffic(w, elems_per_launch),
                      "kernel": ("reduce_sumsq_tiles+update_tiles" if clip else
-                                "accumulate_tiles x%d + update_tiles" % w.micro_batches
+                                "accumulate_tiles x%d + update_tiles (last micro-batch and accumulator)" % (w.micro_batches - 1)
                                 if w.micro_batches > 1 else "update_tiles"),
                      "elems_per_launch": elems_per_launch, "avg_launch_ms": avg_ms,
                      "median_launch_ms": sorted(kernel_ms)[len(kernel_ms) // 2],

@@ -43,7 +43,7 @@
 extern "C" {
 #endif
 
-#define PS_ABI_VERSION 4u
+#define PS_ABI_VERSION 5u
 /* Largest number of gradient contributions one call can reduce. */
 #define PS_MAX_CONTRIB 16u
 
@@ -143,6 +143,12 @@ typedef struct ps_grads_t {
     uint32_t n_contrib;         /* = n_devices, or 1 for an already reduced gradient   */
     int32_t dtype;              /* PS_BF16, PS_F16 or PS_F32, one type for all
                                    (Theorem 4)                                         */
+    const float *accum;         /* DEVICE or NULL, shard-based like ps_shard_t.master: the
+                                   FP32 accumulator of earlier micro-batches
+                                   (ps_step_accumulate).  ps_step_update adds it to the
+                                   contributions' sum before the mean, so the last
+                                   micro-batch needs no accumulation pass of its own;
+                                   every other call wants it NULL (PS_EUNSUPPORTED)    */
 } ps_grads_t;
 
 /* How ps_step_update_bucketed moves a bucket into its staging slot. */
@@ -359,6 +365,7 @@ ps_status_t ps_device_info(ps_device_info_t *info);
  * shard (the whole shard, or one bucket of it).
  *
  *   acc = ((g_0 + g_1) + g_2) + ...          binary32, contribution index ascending
+ *   acc = accum + acc                        only with grads->accum (see below)
  *   g   = (acc * grad_scale) * clip_coef     the global-batch mean (Theorem 3)
  *   m'  = fma(beta1, m, (1-beta1) * g)
  *   v'  = fma(beta2, v, ((1-beta2) * g) * g)
@@ -385,6 +392,12 @@ ps_status_t ps_device_info(ps_device_info_t *info);
  *     n_contrib == 1 as for ZeRO-1.  (ps_cost_eval still reports the Eq. 2
  *     geometry of shard_index; the step does not use it here.)
  * Anything else: PS_EUNSUPPORTED.  elem_offset must be a multiple of 8.
+ * With grads->accum (pi_G = S only, 16-byte aligned) the contributions are the
+ * LAST of k micro-batches and accum holds the sum of the k - 1 before it: the
+ * result is bit for bit that of ps_step_accumulate on these contributions
+ * followed by an update from the accumulator alone, without writing the
+ * accumulator and reading it back (8 bytes per element less).  accum is only
+ * read.  grad_scale is then the caller's to set, 1 / (N k).
  * Deterministic: no atomics, results do not depend on launch shape (Theorem 5,
  * assumption 1).  The call only enqueues kernels on hip_stream: it allocates
  * nothing and waits for nothing, so it may be recorded into a HIP graph by a

@@ -29,7 +29,7 @@ __all__ = [
     "EXPORTED_SYMBOLS", "ABI_VERSION",
 ]
 
-ABI_VERSION = 4   # PS_ABI_VERSION of include/ps_step.h this binding mirrors
+ABI_VERSION = 5   # PS_ABI_VERSION of include/ps_step.h this binding mirrors
 PS_R, PS_S, PS_SG, PS_M, PS_O = range(5)
 PS_BF16, PS_F32, PS_F16 = 0, 1, 2
 PS_COPY_KERNEL, PS_COPY_MEMCPY, PS_COPY_NONE, PS_COPY_REDUCE = 0, 1, 2, 3
@@ -90,7 +90,7 @@ class ps_shard_t(C.Structure):
 
 class ps_grads_t(C.Structure):
     _fields_ = [("contrib", C.POINTER(C.c_void_p)), ("n_contrib", C.c_uint32),
-                ("dtype", C.c_int32)]
+                ("dtype", C.c_int32), ("accum", C.c_void_p)]
 
 
 class ps_bucket_plan_t(C.Structure):
@@ -286,14 +286,16 @@ def ps_device_info():
     return info
 
 
-def make_grads(contrib_ptrs, dtype):
-    """Build a ps_grads_t; the pointer array is kept alive on the returned object."""
+def make_grads(contrib_ptrs, dtype, accum=None):
+    """Build a ps_grads_t; the pointer array is kept alive on the returned object.  accum:
+    device address of the FP32 accumulator of earlier micro-batches (ps_step_update only)."""
     g = ps_grads_t()
     arr = _ptr_array(contrib_ptrs) if contrib_ptrs is not None else None
     g._keep = arr
     g.contrib = C.cast(arr, C.POINTER(C.c_void_p)) if arr is not None else None
     g.n_contrib = len(contrib_ptrs) if contrib_ptrs is not None else 0
     g.dtype = dtype
+    g.accum = accum or None
     return g
 
 

@@ -41,8 +41,10 @@ uint64_t reduce_workspace_doubles(uint64_t count);
 // Launchers, defined in ps_kernels.hip.  All pointers are DEVICE pointers that
 // already point at the first element to process; `count` elements follow.
 // They return the hipError_t of the launch as int (0 = success).
-int launch_update(int dtype, uint32_t n_contrib, const ContribPtrs &g, float *master, float *m,
-                  float *v, uint16_t *out, uint64_t count, const StepScalars &s, void *stream);
+// accum: FP32 values added to the contributions' sum (earlier micro-batches), or NULL.
+int launch_update(int dtype, uint32_t n_contrib, const ContribPtrs &g, const float *accum,
+                  float *master, float *m, float *v, uint16_t *out, uint64_t count,
+                  const StepScalars &s, void *stream);
 int launch_clip_coef(const double *sumsq_local, const double *sumsq_others, double max_norm,
                      float *coef_out, void *stream);
 int launch_reduce_sumsq(int dtype, uint32_t n_contrib, const ContribPtrs &g, float gs,

@@ -232,6 +232,7 @@ __global__ void clip_coef_kernel(const double *sumsq_local, const double *sumsq_
 
 struct UpdateArgs {
     ContribPtrs g;
+    const float *accum; // sum of earlier micro-batches, added to this one's; or NULL
     float *master, *m, *v;
     uint16_t *out;
     uint64_t n_tiles; // whole tiles (tile kernel) or element count (tail kernel)
@@ -245,8 +246,10 @@ struct UpdateArgs {
 // (Definition 1, Eq. 3), or this shard's slice of the replicated parameters.
 //   N : contribution count known at compile time, 0 = read it from args
 //   G : uint16_t (bf16 bits), f16_bits (binary16) or float
+//   A : a.accum is added to the contributions' sum (the last micro-batch of an
+//       accumulated step: what accumulate_tiles would store is used straight away)
 // The loop only repeats when there are more tiles than the grid can hold.
-template <int N, typename G>
+template <int N, typename G, bool A>
 __global__ __launch_bounds__(kWave) void update_tiles(const UpdateArgs a)
 {
     const uint32_t n = N ? N : a.n_contrib;
@@ -255,12 +258,14 @@ __global__ __launch_bounds__(kWave) void update_tiles(const UpdateArgs a)
         return;
     for (uint64_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
         const uint64_t e = tile * kTileElems + (uint64_t)threadIdx.x * 4;
-        f32x4 acc, th, mm, vv;
+        f32x4 acc, run, th, mm, vv;
         if constexpr (N != 0) {
             f32x4 gr[N];
 #pragma unroll
             for (int r = 0; r < N; ++r)
                 gr[r] = load_contrib4<G, true>(a.g.p[r], e);
+            if constexpr (A)
+                run = load_vec<true>(reinterpret_cast<const f32x4 *>(a.accum + e));
             th = load_vec<true>(reinterpret_cast<const f32x4 *>(a.master + e));
             mm = load_vec<true>(reinterpret_cast<const f32x4 *>(a.m + e));
             vv = load_vec<true>(reinterpret_cast<const f32x4 *>(a.v + e));
@@ -269,6 +274,8 @@ __global__ __launch_bounds__(kWave) void update_tiles(const UpdateArgs a)
             for (int r = 1; r < N; ++r)
                 acc = acc + gr[r];
         } else {
+            if constexpr (A)
+                run = load_vec<true>(reinterpret_cast<const f32x4 *>(a.accum + e));
             th = load_vec<true>(reinterpret_cast<const f32x4 *>(a.master + e));
             mm = load_vec<true>(reinterpret_cast<const f32x4 *>(a.m + e));
             vv = load_vec<true>(reinterpret_cast<const f32x4 *>(a.v + e));
@@ -276,6 +283,8 @@ __global__ __launch_bounds__(kWave) void update_tiles(const UpdateArgs a)
             for (uint32_t r = 1; r < n; ++r)
                 acc = acc + load_contrib4<G, true>(a.g.p[r], e);
         }
+        if constexpr (A)
+            acc = run + acc;
         step_element4(acc, th, mm, vv, s);
         u32x2 pk;
         pk.x = narrow16(th.x, s.out_f16) | (narrow16(th.y, s.out_f16) << 16);
@@ -299,6 +308,8 @@ __global__ __launch_bounds__(kWave) void update_tail(const UpdateArgs a)
     float acc = load_contrib1<G>(a.g.p[0], e);
     for (uint32_t r = 1; r < a.n_contrib; ++r)
         acc = acc + load_contrib1<G>(a.g.p[r], e);
+    if (a.accum)
+        acc = a.accum[e] + acc;
     float th = a.master[e], m = a.m[e], v = a.v[e];
     step_element(acc, th, m, v, s);
     a.master[e] = th;

@@ -29,14 +29,15 @@ static std::atomic<uint32_t> update_residency_override{0};
 
 void set_update_residency(uint32_t waves_per_cu) { update_residency_override.store(waves_per_cu); }
 
-static uint32_t update_lds(uint32_t n_contrib, int dtype)
+static uint32_t update_lds(uint32_t n_contrib, int dtype, bool with_accum)
 {
     const uint32_t forced = update_residency_override.load();
     if (forced)
         return forced > 32 ? 0u : lds_for_waves(forced < 3 ? 3 : forced);
-    if (n_contrib == 1)
+    if (n_contrib == 1 && !with_accum)
         return lds_for_waves(dtype == PS_BF16 ? 12 : 10);
-    const uint32_t in_flight = n_contrib * (dtype == PS_BF16 ? 512u : 1024u) + 3072u;
+    const uint32_t in_flight = n_contrib * (dtype == PS_BF16 ? 512u : 1024u) + 3072u +
+                               (with_accum ? 1024u : 0u);
     return lds_for_waves(in_flight <= 4608u ? 10 : 8);
 }
 
@@ -70,19 +71,23 @@ static const void *advance(const void *p, uint64_t elems)
 template <int N, typename G>
 static void launch_update_n(const UpdateArgs &a, uint32_t grid, hipStream_t st)
 {
-    const uint32_t lds = update_lds(a.n_contrib, sizeof(G) == 2 ? PS_BF16 : PS_F32);
-    hipLaunchKernelGGL((update_tiles<N, G>), dim3(grid), dim3(kWave), lds, st, a);
+    const uint32_t lds = update_lds(a.n_contrib, sizeof(G) == 2 ? PS_BF16 : PS_F32, a.accum != nullptr);
+    if (a.accum)
+        hipLaunchKernelGGL((update_tiles<N, G, true>), dim3(grid), dim3(kWave), lds, st, a);
+    else
+        hipLaunchKernelGGL((update_tiles<N, G, false>), dim3(grid), dim3(kWave), lds, st, a);
 }
 
 template <typename G>
-static int launch_update_t(uint32_t n_contrib, const ContribPtrs &g, float *master, float *m,
-                           float *v, uint16_t *out, uint64_t count, const StepScalars &s,
-                           hipStream_t st)
+static int launch_update_t(uint32_t n_contrib, const ContribPtrs &g, const float *accum,
+                           float *master, float *m, float *v, uint16_t *out, uint64_t count,
+                           const StepScalars &s, hipStream_t st)
 {
     const uint64_t n_tiles = count / kTileElems;
     const uint64_t body = n_tiles * kTileElems;
     UpdateArgs a;
     a.g = g;
+    a.accum = accum;
     a.master = master;
     a.m = m;
     a.v = v;
@@ -111,6 +116,7 @@ static int launch_update_t(uint32_t n_contrib, const ContribPtrs &g, float *mast
         const uint64_t rest = count - body;
         for (uint32_t r = 0; r < n_contrib; ++r)
             a.g.p[r] = advance<G>(g.p[r], body);
+        a.accum = accum ? accum + body : nullptr;
         a.master = master + body;
         a.m = m + body;
         a.v = v + body;
@@ -125,15 +131,16 @@ static int launch_update_t(uint32_t n_contrib, const ContribPtrs &g, float *mast
     return 0;
 }
 
-int launch_update(int dtype, uint32_t n_contrib, const ContribPtrs &g, float *master, float *m,
-                  float *v, uint16_t *out, uint64_t count, const StepScalars &s, void *stream)
+int launch_update(int dtype, uint32_t n_contrib, const ContribPtrs &g, const float *accum,
+                  float *master, float *m, float *v, uint16_t *out, uint64_t count,
+                  const StepScalars &s, void *stream)
 {
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     if (dtype == PS_BF16)
-        return launch_update_t<uint16_t>(n_contrib, g, master, m, v, out, count, s, st);
+        return launch_update_t<uint16_t>(n_contrib, g, accum, master, m, v, out, count, s, st);
     if (dtype == PS_F16)
-        return launch_update_t<f16_bits>(n_contrib, g, master, m, v, out, count, s, st);
-    return launch_update_t<float>(n_contrib, g, master, m, v, out, count, s, st);
+        return launch_update_t<f16_bits>(n_contrib, g, accum, master, m, v, out, count, s, st);
+    return launch_update_t<float>(n_contrib, g, accum, master, m, v, out, count, s, st);
 }
 
 template <int N, typename G>

@@ -256,6 +256,17 @@ ps_status_t check_param_dtype(int32_t param_dtype, int32_t reserved, int32_t gra
     return PS_OK;
 }
 
+// Entry points other than ps_step_update take no accumulator beside the contributions.
+ps_status_t no_accum(const ps_grads_t *grads, const char *call)
+{
+    if (grads && grads->accum) {
+        set_error("%s takes no grads->accum: only ps_step_update adds an accumulator to the "
+                  "contributions", call);
+        return PS_EUNSUPPORTED;
+    }
+    return PS_OK;
+}
+
 // Both reduce entry points: `workspace` is the caller's, or NULL for the library's
 // static per-device array (then workspace_bytes is ignored and nothing is allocated).
 ps_status_t reduce_sumsq_checked(const ps_spec_t *spec, const ps_grads_t *grads, double grad_scale,
@@ -274,6 +285,8 @@ ps_status_t reduce_sumsq_checked(const ps_spec_t *spec, const ps_grads_t *grads,
         set_error("grads or sumsq_out is NULL");
         return PS_EINVAL;
     }
+    if ((st = no_accum(grads, "the reduce phase")) != PS_OK)
+        return st;
     if (std::isnan(grad_scale)) {
         set_error("grad_scale is NaN");
         return PS_ERANGE;
@@ -497,7 +510,7 @@ class BucketRun {
     void update(const ContribPtrs &g, uint64_t lo, uint64_t count, int dtype, uint32_t n_contrib)
     {
         uint16_t *out = reinterpret_cast<uint16_t *>(shard_->gather_out) + out_off_ + lo;
-        int le = launch_update(dtype, n_contrib, g, shard_->master + lo, shard_->m + lo,
+        int le = launch_update(dtype, n_contrib, g, nullptr, shard_->master + lo, shard_->m + lo,
                                shard_->v + lo, out, count, s_, comp_);
         if (le != 0)
             note((hipError_t)le, "update kernel launch");
@@ -627,6 +640,17 @@ ps_status_t ps_step_update(const ps_spec_t *spec, const ps_adamw_t *hp, const ps
         (st = check_param_dtype(shard->param_dtype, shard->reserved, grads->dtype)) != PS_OK ||
         (st = check_range(elem_offset, elem_count, shard->len)) != PS_OK)
         return st;
+    if (grads->accum) {
+        if (z1) {
+            set_error("grads->accum goes with pi_G = S contributions; under pi_G = R the "
+                      "all-reduce has already summed the micro-batch");
+            return PS_EUNSUPPORTED;
+        }
+        if (!aligned16(grads->accum)) {
+            set_error("grads->accum is not 16-byte aligned");
+            return PS_EALIGN;
+        }
+    }
     const uint64_t count = clamp_count(elem_offset, elem_count, shard->valid_len);
     if (count == 0)
         return PS_OK;
@@ -642,8 +666,10 @@ ps_status_t ps_step_update(const ps_spec_t *spec, const ps_adamw_t *hp, const ps
         g.p[0] = reinterpret_cast<const char *>(g.p[0]) +
                  (out_off + elem_offset) * elem_bytes(grads->dtype);
     uint16_t *out = reinterpret_cast<uint16_t *>(shard->gather_out) + out_off + elem_offset;
-    int e = launch_update(grads->dtype, grads->n_contrib, g, shard->master + elem_offset,
-                          shard->m + elem_offset, shard->v + elem_offset, out, count, s, stream);
+    int e = launch_update(grads->dtype, grads->n_contrib, g,
+                          grads->accum ? grads->accum + elem_offset : nullptr,
+                          shard->master + elem_offset, shard->m + elem_offset,
+                          shard->v + elem_offset, out, count, s, stream);
     if (e != 0)
         return hip_fail((hipError_t)e, "update kernel launch");
     return PS_OK;
@@ -666,6 +692,8 @@ ps_status_t ps_step_accumulate(const ps_spec_t *spec, const ps_grads_t *grads, f
         set_error("grads or accum is NULL");
         return PS_EINVAL;
     }
+    if ((st = no_accum(grads, "ps_step_accumulate (its accumulator is the accum argument)")) != PS_OK)
+        return st;
     if (!aligned16(accum)) {
         set_error("accum is not 16-byte aligned");
         return PS_EALIGN;
@@ -923,6 +951,8 @@ ps_status_t ps_step_update_offloaded(const ps_spec_t *spec, const ps_adamw_t *hp
         set_error("plan or grads is NULL");
         return PS_EINVAL;
     }
+    if ((st = no_accum(grads, "the offloaded step")) != PS_OK)
+        return st;
     if ((plan->host_layout != PS_HOST_FLAT && plan->host_layout != PS_HOST_PACKED) ||
         plan->reserved != 0) {
         set_error("host_layout must be PS_HOST_FLAT or PS_HOST_PACKED, reserved 0");
@@ -1043,8 +1073,8 @@ ps_status_t ps_step_update_offloaded(const ps_spec_t *spec, const ps_adamw_t *hp
             std::memset(&g, 0, sizeof g);
             for (uint32_t r = 0; r < grads->n_contrib; ++r)
                 g.p[r] = reinterpret_cast<const char *>(grads->contrib[r]) + lo * eb;
-            int le = launch_update(grads->dtype, grads->n_contrib, g, d_master, d_m, d_v, d_out, cnt,
-                                   s, comp);
+            int le = launch_update(grads->dtype, grads->n_contrib, g, nullptr, d_master, d_m, d_v,
+                                   d_out, cnt, s, comp);
             if (le != 0) {
                 e = (hipError_t)le;
                 what = "update kernel launch";

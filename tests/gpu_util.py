@@ -46,9 +46,11 @@ def shard_of(master, m, v, out, length, valid=None):
                          length if valid is None else valid, fmt, 0)
 
 
-def grads_of(tensors, dtype, elem_offset=0):
+def grads_of(tensors, dtype, elem_offset=0, accum=None):
+    """accum: the FP32 accumulator tensor of earlier micro-batches (shard-based, no offset)."""
     esz = 4 if dtype == "f32" else 2
-    return ps.make_grads([t.data_ptr() + elem_offset * esz for t in tensors], DT[dtype])
+    return ps.make_grads([t.data_ptr() + elem_offset * esz for t in tensors], DT[dtype],
+                         accum=None if accum is None else accum.data_ptr())
 
 
 def ulp_diff(a, b):

@@ -413,10 +413,12 @@ def test_7b_zero1_full_shard_every_element(capsys):
 
 
 def test_7b_accum4_full_shard_every_element(capsys):
-    """Gradient accumulation row: four micro-batches (fresh contributions each) into the
-    FP32 accumulator, then one update with grad_scale = 1/(N k).  The accumulator (oracle:
-    accumulate over the whole shard, on all host threads) and the updated state are compared
-    on every element."""
+    """Gradient accumulation row: four micro-batches (fresh contributions each), the first
+    three into the FP32 accumulator, the last straight into the update beside the
+    accumulator, grad_scale = 1/(N k).  The accumulator after three micro-batches (oracle:
+    accumulate over the whole shard, on all host threads) and the updated state (oracle:
+    the fourth accumulation, then the update from the accumulator alone) are compared on
+    every element."""
     import threading
     w = WORKLOADS["7b_accum4"]
     _need(45)
@@ -435,8 +437,14 @@ def test_7b_accum4_full_shard_every_element(capsys):
     for j in range(k):
         del grads
         grads = dgen.workload_gradients(w, t * 16 + j)             # a different stream per micro-batch
-        ps.ps_step_accumulate(spec, ps.make_grads([g.data_ptr() for g in grads], ps.PS_BF16),
-                              accum.data_ptr(), j == 0, 0, n, n, stream_handle())
+        if j < k - 1:
+            ps.ps_step_accumulate(spec, ps.make_grads([g.data_ptr() for g in grads], ps.PS_BF16),
+                                  accum.data_ptr(), j == 0, 0, n, n, stream_handle())
+        else:       # what the device's accumulator holds when the last micro-batch arrives
+            for lo in range(0, n, CHUNK):
+                hi = min(lo + CHUNK, n)
+                assert np.array_equal(pin.fetch("acc", accum[lo:hi]).view(np.uint32),
+                                      acc_want[lo:hi].view(np.uint32))
         for lo in range(0, n, CHUNK):
             hi = min(lo + CHUNK, n)
             gr = [pin.fetch("g%d" % r, grads[r][lo:hi]) for r in range(N)]
@@ -449,16 +457,22 @@ def test_7b_accum4_full_shard_every_element(capsys):
             for x in ts:
                 x.join()
         torch.cuda.synchronize()
-        _progress(capsys, "accumulation: micro-batch %d of %d added on both sides" % (j + 1, k))
-    for lo in range(0, n, CHUNK):
-        hi = min(lo + CHUNK, n)
-        assert np.array_equal(pin.fetch("acc", accum[lo:hi]).view(np.uint32), acc_want[lo:hi].view(np.uint32))
+        _progress(capsys, "accumulation: micro-batch %d of %d %s" %
+                  (j + 1, k, "added on both sides" if j < k - 1 else "added by the oracle"))
     scale = 1.0 / (N * k)
     hpd, hp = _hp(w, t, grad_scale=scale)
     assert cost.shard_offset == 0          # shard 0: its slice of the replicated parameters starts the buffer
+    ws = torch.empty(ps.ps_verify_workspace_bytes(n * 4), dtype=torch.uint8, device="cuda")
+    sums = torch.zeros(2, dtype=torch.int64, device="cuda")
+    ps.ps_verify_checksum(accum.data_ptr(), n * 4, 0, sums[0:].data_ptr(), 0, ws.data_ptr(), ws.numel(),
+                          stream_handle())
     ps.ps_step_update(spec, hp, shard_of(master, m, v, out, n),
-                      ps.make_grads([accum.data_ptr()], ps.PS_F32), 0, n, stream_handle())
+                      ps.make_grads([g.data_ptr() for g in grads], ps.PS_BF16, accum=accum.data_ptr()),
+                      0, n, stream_handle())
+    ps.ps_verify_checksum(accum.data_ptr(), n * 4, 0, sums[1:].data_ptr(), 0, ws.data_ptr(), ws.numel(),
+                          stream_handle())
     torch.cuda.synchronize()
+    assert sums[0].item() == sums[1].item()                        # the accumulator is only read
     s = orc.derive_scalars(t=t, n_devices=N, grad_scale=scale, **hpd)
     _check_every_element(capsys, "update from the accumulator", w, s, pin,
                          lambda lo, hi: [np.ascontiguousarray(acc_want[lo:hi])],

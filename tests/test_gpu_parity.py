@@ -907,6 +907,43 @@ def test_gradient_accumulation_then_update(dtype, N):
     assert assert_state_parity([host(x) for x in (th, m, v, p)], want, "accumulated") == 0
 
 
+@pytest.mark.parametrize("dtype,N", [("bf16", 8), ("f32", 6), ("bf16", 3), ("f16", 4), ("bf16", 12),
+                                     ("f32", 1)])
+def test_last_micro_batch_goes_straight_into_the_update(dtype, N):
+    """The last of k micro-batches needs no accumulation pass: ps_step_update adds the
+    accumulator of the k - 1 before it to the contributions' sum.  Bit for bit the oracle's
+    accumulate-then-update; the accumulator is only read."""
+    n, k = 5 * TILE + 250 + 5, 3
+    valid = n - 3
+    _say("fused last micro-batch k=%d n=%d valid=%d N=%d %s" % (k, n, valid, N, dtype))
+    spec = ps.ps_spec_preset("zero3", max(N, 2), 1, n * max(N, 2))
+    acc_want = np.full(n, np.float32(7.0))
+    for j in range(k - 1):
+        grads = [gen.gradient(n, 87, j, r, dtype, std=1e-3) for r in range(N)]
+        orc.accumulate(grads, acc_want, overwrite=(j == 0), lo=0, hi=valid)
+    acc_dev = dev(acc_want.copy())          # the first k - 1 passes are another test's business
+    before = acc_want.copy()
+    last = [gen.gradient(n, 87, k - 1, r, dtype, std=1e-3) for r in range(N)]
+    orc.accumulate(last, acc_want, overwrite=False, lo=0, hi=valid)
+    image = np.full(n, np.float16(-77.0), np.float16) if dtype == "f16" else np.zeros(n, np.uint16)
+    state = [gen.master(n, 87), *gen.moments(n, 87, True), image]
+    scale = 1.0 / (N * k)
+    hpd, hp = hp_of(None, 9, grad_scale=scale)
+    want = [a.copy() for a in state]
+    orc.step_f32([acc_want], orc.derive_scalars(t=9, n_devices=max(N, 2), grad_scale=scale, **hpd),
+                 *want, lo=0, hi=valid)
+    th, m, v, p = [dev(a) for a in state]
+    gd = [dev(g) for g in last]
+    shard = shard_of(th, m, v, p, n, valid)
+    cut = 2 * TILE + 8                      # two calls: the accumulator follows elem_offset
+    ps.ps_step_update(spec, hp, shard, grads_of(gd, dtype, accum=acc_dev), 0, cut, stream_handle())
+    ps.ps_step_update(spec, hp, shard, grads_of(gd, dtype, cut, accum=acc_dev), cut, n - cut,
+                      stream_handle())
+    torch.cuda.synchronize()
+    assert assert_state_parity([host(x) for x in (th, m, v, p)], want, "fused last micro-batch") == 0
+    assert np.array_equal(host(acc_dev).view(np.uint32), before.view(np.uint32))
+
+
 # ---- offloaded optimizer state (ZeRO-Offload row) ----
 
 def _pack_host(state, bucket):

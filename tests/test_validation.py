@@ -130,6 +130,30 @@ def test_accumulate_rejects_bad_arguments():
     acc(spec, grads, FAKE, 1, 512, 512, 512)                                         # all padding
 
 
+def test_accumulator_beside_the_contributions_is_for_the_update_only():
+    """grads.accum: the sum of earlier micro-batches, taken by ps_step_update under pi_G = S."""
+    spec, hp, shard, _ = _valid()
+    upd = ps.ps_step_update
+    with_acc = ps.make_grads([FAKE] * 4, ps.PS_BF16, accum=FAKE * 5)
+    upd(spec, hp, shard, with_acc, 0, 0)                                             # valid, empty
+    crooked = ps.make_grads([FAKE] * 4, ps.PS_BF16, accum=FAKE * 5 + 4)
+    assert _status(lambda: upd(spec, hp, shard, crooked, 0, 8)) == ps.PS_EALIGN
+    z1 = ps.ps_spec_preset("zero1", 4, 1, 4096)
+    one = ps.make_grads([FAKE], ps.PS_BF16, accum=FAKE * 5)
+    assert _status(lambda: upd(z1, hp, shard, one, 0, 8)) == ps.PS_EUNSUPPORTED
+    assert "pi_G = R" in ps.ps_last_error()
+    # nobody else takes it
+    assert _status(lambda: ps.ps_step_accumulate(spec, with_acc, FAKE, 1, 0, 8, 1024)) == ps.PS_EUNSUPPORTED
+    ws = ps.ps_workspace_bytes(8)
+    assert _status(lambda: ps.ps_step_reduce_sumsq(spec, with_acc, 0.0, FAKE, FAKE, 0, FAKE, ws, 0, 8,
+                                                   1024, 0)) == ps.PS_EUNSUPPORTED
+    assert _status(lambda: ps.ps_step_reduce_sumsq_static(spec, with_acc, 0.0, FAKE, FAKE, 0, 0, 8,
+                                                          1024, 0)) == ps.PS_EUNSUPPORTED
+    off = ps.ps_spec_preset("zero_offload", 4, 0, 4096)
+    assert _status(lambda: ps.ps_step_update_offloaded(off, hp, ps.ps_offload_plan_t(), with_acc)) \
+        == ps.PS_EUNSUPPORTED
+
+
 def test_zero2_output_offset_must_keep_alignment():
     spec = ps.ps_spec_preset("zero2", 4, 1, 4 * 1028)     # shard offset 1028, not a multiple of 8
     _, hp, _, grads = _valid()
