@@ -79,6 +79,9 @@ def main():
     ap.add_argument("--offload-layout", choices=["packed", "flat"], default="packed",
                     help="7b_offload: host state as one image packed bucket by bucket (one copy per "
                          "direction per bucket) or as four flat arrays (three copies up, four down)")
+    ap.add_argument("--sync-each-step", action="store_true",
+                    help="7b_offload: wait for the device after every step instead of enqueueing the "
+                         "steps back to back")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-baseline-seconds", type=float, default=15.0,
                     help="about how much CPU work the oracle baseline may take")
@@ -533,6 +536,8 @@ def offload_bench(args):
         hp = ps.ps_adamw_t(w.lr, w.beta1, w.beta2, w.eps, w.weight_decay, t_no[0], 0.0, 0.0)
         ps.ps_step_update_offloaded(spec, hp, plan, g)     # consecutive steps are ordered on the streams
         t_no[0] += 1
+        if args.sync_each_step:
+            torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -547,21 +552,25 @@ def offload_bench(args):
 
     # Yardstick, like the copy kernel for HBM: the same bytes over the same link as plain
     # pinned copies, 12 B bytes up and 14 B bytes down per bucket, both directions at once.
-    src_up = torch.empty(12 * B, dtype=torch.uint8).pin_memory()
-    dst_down = torch.empty(14 * B, dtype=torch.uint8).pin_memory()
+    # The host side of the probe walks the step's own pinned memory, bucket after bucket (its
+    # contents are not needed any more): a small buffer copied over and over would stay in the
+    # host's caches and hide what the host's memory costs when other jobs share it.
+    host = image if args.offload_layout == "packed" else master.view(torch.uint8)
+    span = (host.numel() - 14 * B) // 4096 * 4096
     dev_up = torch.empty(12 * B, dtype=torch.uint8, device="cuda")
     dev_down = torch.empty(14 * B, dtype=torch.uint8, device="cuda")
 
     def probe(do_up, do_down):
         torch.cuda.synchronize()
         p0 = time.perf_counter()
-        for _ in range(n_b):
+        for b in range(n_b):
+            at = (b * 14 * B) % span if span > 0 else 0
             if do_up:
                 with torch.cuda.stream(s1):
-                    dev_up.copy_(src_up, non_blocking=True)
+                    dev_up.copy_(host[at:at + 12 * B], non_blocking=True)
             if do_down:
                 with torch.cuda.stream(s3):
-                    dst_down.copy_(dev_down, non_blocking=True)
+                    host[at:at + 14 * B].copy_(dev_down, non_blocking=True)
         torch.cuda.synchronize()
         return (time.perf_counter() - p0) * 1e3
     probe(True, True)
@@ -569,7 +578,8 @@ def offload_bench(args):
     link = {"both_directions_ms": both_ms,
             "up_GBps_both": 12 * B * n_b / both_ms / 1e6, "down_GBps_both": 14 * B * n_b / both_ms / 1e6,
             "up_GBps_alone": 12 * B * n_b / up_ms / 1e6, "down_GBps_alone": 14 * B * n_b / down_ms / 1e6,
-            "note": "plain pinned copies of the step's bytes, one per direction per bucket"}
+            "note": "plain pinned copies of the step's bytes over the step's own host memory, one per "
+                    "direction per bucket"}
     log("link probe: %s" % json.dumps(link))
     print(json.dumps({
         "metric": "offloaded shard reduce+AdamW+cast: host-link GB/s, elements/s",
