@@ -79,3 +79,23 @@ def test_json_line_of_the_other_workloads(workload):
     assert KEYS <= set(d) and d["config"]["workload"] == workload and d["value"] > 0
     r = d["roofline"]
     assert r["peak"] == 8000.0 and 0.5 < r["frac"] < 1.0     # an HBM-bound kernel on this part
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("layout", ["packed", "flat"])
+def test_json_line_of_the_offloaded_workload(layout):
+    """The offloaded workload is bound by the host link: its line carries that roofline and
+    the probe of plain pinned copies it is measured against."""
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "7b_offload",
+                        "--offload-layout", layout, "--steps", "2", "--warmup", "1", "--no-cpu-baseline"],
+                       stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=280)
+    assert p.returncode == 0, p.stderr[-2000:]
+    lines = [l for l in p.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert KEYS <= set(d) and d["config"]["workload"] == "7b_offload" and d["value"] > 0
+    assert d["config"]["host_layout"] == layout
+    r = d["roofline"]
+    assert r["bound"].startswith("host link") and r["peak"] == 64.0 and 0.0 < r["frac"] < 1.0
+    assert d["extras"]["link_probe"]["both_directions_ms"] > 0
+
