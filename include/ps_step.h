@@ -240,7 +240,10 @@ typedef struct ps_offload_plan_t {
                                the updated parameters                                    */
     uint64_t len;           /* shard length n = psi_padded / N                           */
     uint64_t valid_len;     /* elements [valid_len, len) are never read or written       */
-    uint64_t bucket_elems;  /* multiple of 8                                             */
+    uint64_t bucket_elems;  /* multiple of 8.  On MI355X copies of 0.4-0.5 GB (2^25
+                               elements) keep the host link at its full-duplex rate run
+                               after run; half that size has measured up to twice the
+                               step time, the DMA engines then being shared unevenly    */
     uint32_t n_slots;       /* 2 or 3 DEVICE slots; 3 lets upload, update and download
                                of neighbouring buckets run at the same time             */
     int32_t param_dtype;    /* PS_BF16 (0) or PS_F16, as in ps_shard_t                   */

@@ -90,7 +90,7 @@ WORKLOADS = {
     # host memory (11.8 GB), streamed through the device (bound by the host link).
     "7b_offload": Workload("7b_offload", psi=6_738_415_616, n_devices=8, shard_index=0,
                            strategy="zero_offload", grad_dtype="bf16", first_step=1000,
-                           warm_moments=True, grad_std=1e-4, bucket_elems=1 << 24),
+                           warm_moments=True, grad_std=1e-4, bucket_elems=1 << 25),
     # Ragged 13B FSDP-style shard, fp32 heavy-tailed gradients, global-norm clip.
     # psi is already a multiple of 6*256; "psi_ragged" drops 1001 elements so that
     # the last shard owns a pad of 1001 elements that must stay untouched.

@@ -538,7 +538,7 @@ def test_7b_verify_scans_whole_buffers_against_the_oracle():
 def test_7b_offload_full_shard_every_element(packed, capsys):
     """ZeRO-Offload row at bench.py's shape: master/m/v and the bf16 parameters of the 7B
     shard in pinned host memory (one image packed bucket by bucket, or four flat arrays),
-    streamed through three device slots of 2^24 elements; every element compared."""
+    streamed through three device slots of 2^25 elements; every element compared."""
     w = WORKLOADS["7b_offload"]
     _need(20)
     n, N, t, B = w.shard_len, w.n_devices, w.first_step, w.bucket_elems
