@@ -36,6 +36,9 @@ def test_measured_traffic_matches_the_algorithmic_bytes_or_is_absent():
     assert bench.bytes_per_elem(w) == 42 and bench.bytes_per_elem(WORKLOADS["13b_clip"], True) == 58
     assert bench.bytes_per_elem(WORKLOADS["tiny"]) == 34
     assert bench.bytes_per_elem(WORKLOADS["7b_zero1"]) == 28
+    # three accumulation passes (20, 24, 24) and the update from the last micro-batch and the
+    # accumulator (16 + 4 + 12 read, 14 written)
+    assert bench.bytes_per_elem(WORKLOADS["7b_accum4"]) == 20 + 24 + 24 + 46 == 114
 
 
 @pytest.mark.gpu
